@@ -1,0 +1,160 @@
+/*
+ * dfgnn.h - C ABI of the fused attention-GNN graph convolution for AMD MI355X (gfx950).
+ *
+ * The library computes, for a graph stored as CSR by destination, the three fused steps of an
+ * attention-GNN layer (Eq. 1, Sec. 2.1):  S = SDDMM(Q, K, A)  ->  P = Softmax(S) over each node's
+ * neighbourhood (Appendix A)  ->  O = SpMM(P, V),  and the backward pass of Appendix B, for the three
+ * models of Sec. 5.1: GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features).
+ * Per-edge scores and attention weights live only in registers; nothing of size O(edges) is written
+ * to memory by the layer calls.
+ *
+ * General rules
+ *  - Every pointer named d_* or documented as "device" is GPU global memory owned by the caller; the
+ *    library never allocates or frees device memory and keeps only a small host-side handle.
+ *  - Node tensors are [N, H, D] row-major (one node's H*D values contiguous), in the layer's dtype
+ *    (fp32 or bf16); statistics and attention vectors are fp32.  Device pointers must be 16-byte aligned.
+ *  - Row i of the CSR is destination i; indices[indptr[i] .. indptr[i+1]) are its in-neighbours
+ *    (sources).  Sources need not be sorted inside a row; repeated edges are separate softmax terms;
+ *    empty rows are legal (O = 0, row_max = -inf, row_sum = 0, no gradient contribution).
+ *  - All layer calls are asynchronous on the HIP stream passed as `stream` (a hipStream_t; NULL = the
+ *    default stream).  Only dfgnn_graph_create synchronises that stream.
+ *  - Every function returns a dfgnn_status; nothing throws or aborts across this boundary.  On any
+ *    error no output buffer has defined contents.  dfgnn_last_error() gives a thread-local detail text.
+ *  - Outputs are overwritten, never accumulated into.
+ */
+#ifndef DFGNN_H
+#define DFGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DFGNN_OK = 0,
+    DFGNN_EINVAL = 1,       /* NULL pointer, negative size, inconsistent arguments, malformed graph */
+    DFGNN_EUNSUPPORTED = 2, /* shape / dtype / alignment the kernels do not cover                    */
+    DFGNN_EWORKSPACE = 3,   /* a caller-provided buffer is too small                                 */
+    DFGNN_EHIP = 4          /* a HIP runtime call failed (text in dfgnn_last_error)                  */
+} dfgnn_status;
+
+typedef enum { DFGNN_GT = 0, DFGNN_GAT = 1, DFGNN_AGNN = 2 } dfgnn_model;
+typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
+
+/*
+ * Degree-aware scheduling parameters.  The switch between one fused node-parallel pass and an
+ * edge-parallel treatment of super nodes (Sec. 3, Sec. 4.2 "SDDMM") is taken per row here: a row with
+ * at least super_threshold neighbours is cut into chunks of chunk_edges edges whose partial softmax
+ * statistics are merged in a second pass.  0 selects the library default for either field
+ * (super_threshold 1024, chunk_edges 512).
+ */
+typedef struct {
+    int32_t super_threshold;
+    int32_t chunk_edges;
+    int32_t reserved[6]; /* must be 0 */
+} dfgnn_sched_params;
+
+/* One layer call's model description. */
+typedef struct {
+    int32_t model;   /* dfgnn_model */
+    int32_t dtype;   /* dfgnn_dtype of node tensors (inputs, outputs and their gradients) */
+    int32_t H;       /* heads */
+    int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
+                        of two (vec = 4 for fp32, 8 for bf16) and H*D/vec <= 64 */
+    float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT: ignored */
+    float neg_slope; /* GAT: LeakyReLU slope (derivative at 0 is neg_slope) */
+    float eps;       /* AGNN: lower clamp of the feature norm */
+    int32_t reserved[1];
+} dfgnn_layer;
+
+typedef struct dfgnn_graph dfgnn_graph; /* opaque host handle over caller-owned device metadata */
+
+/* Items of dfgnn_graph_query.  Arrays are int32 in device memory inside the metadata buffer. */
+typedef enum {
+    DFGNN_Q_ROW_ORDER = 0,     /* [N]   rows: super rows (ascending id) first, then by descending bit_length(degree), stable */
+    DFGNN_Q_ROW_CHUNK_PTR = 1, /* [n_super_rows + 1] first chunk of every super row */
+    DFGNN_Q_ROW_CHUNKS = 2,    /* [n_row_chunks * 3] (row, begin, end) CSR edge ranges */
+    DFGNN_Q_T_INDPTR = 3,      /* [N + 1] CSC pointer (by source) */
+    DFGNN_Q_T_INDICES = 4,     /* [E]   destination of every out-edge, columns ascending, CSR position ascending inside a column */
+    DFGNN_Q_T_EID = 5,         /* [E]   CSR position of every CSC entry */
+    DFGNN_Q_COL_ORDER = 6,     /* [N]   same ordering rule applied to out-degrees */
+    DFGNN_Q_COL_CHUNK_PTR = 7, /* [n_super_cols + 1] */
+    DFGNN_Q_COL_CHUNKS = 8,    /* [n_col_chunks * 3] (column, begin, end) CSC entry ranges */
+    DFGNN_Q_N_SUPER_ROWS = 9,  /* count only (d_ptr = NULL) */
+    DFGNN_Q_N_SUPER_COLS = 10  /* count only */
+} dfgnn_query;
+
+const char* dfgnn_status_string(int status);
+const char* dfgnn_last_error(void); /* never NULL; valid until the calling thread's next library call */
+int dfgnn_version(int* major, int* minor);
+
+/*
+ * Scheduler metadata (the preprocessing step of Sec. 5.3: CSR for the forward pass, CSC for the
+ * backward pass, plus the per-row work classification that replaces the whole-graph strategy switch
+ * of Sec. 4.2).
+ *
+ * dfgnn_graph_meta_bytes: sizes of the two device buffers dfgnn_graph_create needs for a graph of N
+ *   nodes and E edges: meta_bytes (lives as long as the graph handle) and scratch_bytes (used only
+ *   during creation).  sched may be NULL (defaults).  Host-only; needs no GPU.
+ *
+ * dfgnn_graph_create: validates the CSR (monotone indptr starting at 0 and ending at E, indices in
+ *   [0, N)), then builds on the GPU: the row order, the super-row chunk list, the CSC transpose
+ *   (out-edges of a source listed in increasing CSR position) and the same order / chunk list for
+ *   columns.  d_indptr [N+1] and d_indices [E] are device int32, caller-owned, and must stay valid and
+ *   unchanged while the handle is used.  Requires 0 <= N, 0 <= E < 2^31 - 2^20.  Synchronises `stream`.
+ *   Errors: EINVAL (NULL / negative / malformed CSR), EWORKSPACE (buffers smaller than
+ *   dfgnn_graph_meta_bytes reports), EHIP.  On success *out receives a handle to be released with
+ *   dfgnn_graph_destroy (host memory only; device buffers stay the caller's).
+ *
+ * dfgnn_graph_query: device pointer and element count of one metadata array (for bit-exact checks).
+ */
+int dfgnn_graph_meta_bytes(int64_t N, int64_t E, const dfgnn_sched_params* sched, size_t* meta_bytes,
+                           size_t* scratch_bytes);
+int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr, const int32_t* d_indices,
+                       const dfgnn_sched_params* sched, void* d_meta, size_t meta_bytes, void* d_scratch,
+                       size_t scratch_bytes, void* stream);
+int dfgnn_graph_destroy(dfgnn_graph* graph);
+int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, int64_t* count);
+
+/*
+ * Bytes of device workspace one forward / one backward call needs for this graph and layer (partial
+ * results of super-row chunks, per-node score terms, statistics handed from the row pass to the
+ * column pass, reduction staging).  Either output pointer may be NULL.  Errors: EINVAL, EUNSUPPORTED.
+ */
+int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer* layer, size_t* fwd_bytes, size_t* bwd_bytes);
+
+/*
+ * Forward: O_i = sum_{j in N(i)} softmax_j(s_ij) Val_j per head (Eq. 1; edge softmax of Appendix A).
+ *   GT   s_ij = scale * q_i . k_j                         x = Q, k = K, v = V (Val = V)
+ *   GAT  s_ij = LeakyReLU(a_l . Wh_i + a_r . Wh_j)        x = Wh, a_l, a_r [H, D] fp32 device (Val = Wh); k = v = NULL
+ *   AGNN s_ij = beta * cos(h_i, h_j) per head             x = h (Val = h, un-normalised); k = v = a_l = a_r = NULL
+ * out [N,H,D] in the layer dtype; row_max, row_sum [N,H] fp32 are the softmax statistics
+ * (max_j s_ij and sum_j exp(s_ij - max)) that dfgnn_backward consumes.
+ * workspace: device, >= fwd_bytes of dfgnn_workspace_bytes, 256-byte aligned, contents undefined on
+ * entry and exit.  Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP.
+ */
+int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k, const void* v,
+                  const float* a_l, const float* a_r, void* out, float* row_max, float* row_sum, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/*
+ * Backward (Appendix B; the fused SDDMM -> softmax-backward -> SpMM chain of Sec. 4.3 over the CSR,
+ * and the transposed products over the CSC).  Inputs are those of the forward call plus its results
+ * out, row_max, row_sum and the upstream gradient d_out = dL/dO [N,H,D].
+ *   GT   -> d_x = dL/dQ, d_k = dL/dK, d_v = dL/dV                        (d_a_l = d_a_r = d_scale = NULL)
+ *   GAT  -> d_x = dL/dWh, d_a_l, d_a_r [H,D] fp32                        (d_k = d_v = d_scale = NULL)
+ *   AGNN -> d_x = dL/dh, d_scale = dL/dbeta (1 float, device)            (d_k = d_v = d_a_l = d_a_r = NULL)
+ * Gradient node tensors are in the layer dtype.  workspace: >= bwd_bytes, 256-byte aligned.
+ * Results are deterministic (no floating-point atomics).
+ */
+int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k, const void* v,
+                   const float* a_l, const float* a_r, const void* out, const float* row_max, const float* row_sum,
+                   const void* d_out, void* d_x, void* d_k, void* d_v, float* d_a_l, float* d_a_r, float* d_scale,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFGNN_H */

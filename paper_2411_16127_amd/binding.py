@@ -1,0 +1,292 @@
+"""ctypes binding of include/dfgnn.h.  Function names and argument order follow the C ABI.
+
+The low-level functions (graph_meta_bytes, graph_create, graph_query, workspace_bytes, forward,
+backward) take torch tensors or raw pointers and only marshal them.  `Graph` and the `alloc=True`
+conveniences allocate the caller-owned buffers with torch and pass them through unchanged.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdfgnn.so")
+
+MODEL = {"gt": 0, "gat": 1, "agnn": 2}
+DTYPE = {"f32": 0, "bf16": 1}
+QUERY = {
+    "row_order": 0, "row_chunk_ptr": 1, "row_chunks": 2, "t_indptr": 3, "t_indices": 4, "t_eid": 5,
+    "col_order": 6, "col_chunk_ptr": 7, "col_chunks": 8, "n_super_rows": 9, "n_super_cols": 10,
+}
+
+
+class DfgnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} - {last_error()}")
+
+
+class _CSched(ctypes.Structure):
+    _fields_ = [("super_threshold", ctypes.c_int32), ("chunk_edges", ctypes.c_int32), ("reserved", ctypes.c_int32 * 6)]
+
+
+class _CLayer(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_int32), ("dtype", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("neg_slope", ctypes.c_float), ("eps", ctypes.c_float),
+                ("reserved", ctypes.c_int32 * 1)]
+
+
+@dataclass
+class SchedParams:
+    super_threshold: int = 0  # 0 = library default
+    chunk_edges: int = 0
+
+    def _c(self) -> _CSched:
+        return _CSched(self.super_threshold, self.chunk_edges, (ctypes.c_int32 * 6)())
+
+
+@dataclass
+class Layer:
+    model: str          # 'gt' | 'gat' | 'agnn'
+    H: int
+    D: int
+    dtype: str = "f32"  # 'f32' | 'bf16'
+    scale: float = 1.0  # GT: score scale; AGNN: beta
+    neg_slope: float = 0.2
+    eps: float = 1e-12
+
+    def _c(self) -> _CLayer:
+        return _CLayer(MODEL[self.model], DTYPE[self.dtype], self.H, self.D, self.scale, self.neg_slope, self.eps,
+                       (ctypes.c_int32 * 1)())
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """Load libdfgnn.so (built in-tree by paper_2411_16127_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is not built: run `python -m paper_2411_16127_amd.build` "
+                               "(there is no fallback implementation)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+        L.dfgnn_status_string.restype = ctypes.c_char_p
+        L.dfgnn_status_string.argtypes = [ctypes.c_int]
+        L.dfgnn_last_error.restype = ctypes.c_char_p
+        L.dfgnn_last_error.argtypes = []
+        L.dfgnn_version.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.dfgnn_graph_meta_bytes.argtypes = [i64, i64, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.dfgnn_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.dfgnn_graph_destroy.argtypes = [vp]
+        L.dfgnn_graph_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
+        L.dfgnn_backward.argtypes = [vp, vp] + [vp] * 15 + [vp, sz, vp]
+        for name in ("dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
+                     "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().dfgnn_status_string(int(status)).decode()
+
+
+def last_error() -> str:
+    return lib().dfgnn_last_error().decode()
+
+
+def version() -> Tuple[int, int]:
+    a, b = ctypes.c_int(), ctypes.c_int()
+    lib().dfgnn_version(ctypes.byref(a), ctypes.byref(b))
+    return a.value, b.value
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise DfgnnError(rc, where)
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    """Device pointer of a torch tensor (or None / int passed through)."""
+    if t is None:
+        return ctypes.c_void_p(None)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if not t.is_cuda:
+        raise ValueError("dfgnn entry points take device tensors")
+    if not t.is_contiguous():
+        raise ValueError("dfgnn entry points take contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def graph_meta_bytes(N: int, E: int, sched: Optional[SchedParams] = None) -> Tuple[int, int]:
+    meta, scratch = ctypes.c_size_t(), ctypes.c_size_t()
+    cs = sched._c() if sched else None
+    _check(lib().dfgnn_graph_meta_bytes(N, E, ctypes.byref(cs) if cs else None, ctypes.byref(meta),
+                                        ctypes.byref(scratch)), "dfgnn_graph_meta_bytes")
+    return meta.value, scratch.value
+
+
+def graph_create(N: int, E: int, d_indptr, d_indices, sched: Optional[SchedParams], d_meta, meta_bytes: int,
+                 d_scratch, scratch_bytes: int, stream=None) -> ctypes.c_void_p:
+    handle = ctypes.c_void_p()
+    cs = sched._c() if sched else None
+    _check(lib().dfgnn_graph_create(ctypes.byref(handle), N, E, _ptr(d_indptr), _ptr(d_indices),
+                                    ctypes.byref(cs) if cs else None, _ptr(d_meta), meta_bytes, _ptr(d_scratch),
+                                    scratch_bytes, _stream(stream)), "dfgnn_graph_create")
+    return handle
+
+
+def graph_destroy(handle) -> None:
+    _check(lib().dfgnn_graph_destroy(handle), "dfgnn_graph_destroy")
+
+
+def graph_query(handle, what) -> Tuple[int, int]:
+    """(device pointer, element count) of one metadata array."""
+    p, c = ctypes.c_void_p(), ctypes.c_int64()
+    item = QUERY[what] if isinstance(what, str) else int(what)
+    _check(lib().dfgnn_graph_query(handle, item, ctypes.byref(p), ctypes.byref(c)), "dfgnn_graph_query")
+    return (p.value or 0), c.value
+
+
+def workspace_bytes(handle, layer: Layer) -> Tuple[int, int]:
+    f, b = ctypes.c_size_t(), ctypes.c_size_t()
+    cl = layer._c()
+    _check(lib().dfgnn_workspace_bytes(handle, ctypes.byref(cl), ctypes.byref(f), ctypes.byref(b)),
+           "dfgnn_workspace_bytes")
+    return f.value, b.value
+
+
+def forward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, workspace, workspace_bytes_: int,
+            stream=None) -> None:
+    cl = layer._c()
+    _check(lib().dfgnn_forward(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r), _ptr(out),
+                               _ptr(row_max), _ptr(row_sum), _ptr(workspace), workspace_bytes_, _stream(stream)),
+           "dfgnn_forward")
+
+
+def backward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l, d_a_r,
+             d_scale, workspace, workspace_bytes_: int, stream=None) -> None:
+    cl = layer._c()
+    _check(lib().dfgnn_backward(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r), _ptr(out),
+                                _ptr(row_max), _ptr(row_sum), _ptr(d_out), _ptr(d_x), _ptr(d_k), _ptr(d_v),
+                                _ptr(d_a_l), _ptr(d_a_r), _ptr(d_scale), _ptr(workspace), workspace_bytes_,
+                                _stream(stream)), "dfgnn_backward")
+
+
+class Graph:
+    """Owns the device buffers of one graph (CSR arrays, metadata) and its library handle."""
+
+    def __init__(self, indptr, indices, sched: Optional[SchedParams] = None, device="cuda:0", stream=None):
+        import torch
+        self.device = torch.device(device)
+        self.indptr = torch.as_tensor(indptr, dtype=torch.int32).to(self.device).contiguous()
+        self.indices = torch.as_tensor(indices, dtype=torch.int32).to(self.device).contiguous()
+        self.N = int(self.indptr.numel() - 1)
+        self.E = int(self.indices.numel())
+        self.sched = sched
+        meta_b, scratch_b = graph_meta_bytes(self.N, self.E, sched)
+        self.meta = torch.empty(meta_b, dtype=torch.uint8, device=self.device)
+        scratch = torch.empty(scratch_b, dtype=torch.uint8, device=self.device)
+        self.handle = graph_create(self.N, self.E, self.indptr, self.indices, sched, self.meta, meta_b, scratch,
+                                   scratch_b, stream)
+        del scratch
+        self._ws: Dict[tuple, object] = {}
+
+    def close(self) -> None:
+        if getattr(self, "handle", None) is not None:
+            graph_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def query(self, what: str):
+        """Copy of one metadata array as an int32 torch tensor (counts come back as int)."""
+        import torch
+        p, c = graph_query(self.handle, what)
+        if what.startswith("n_"):
+            return c
+        if c == 0:
+            return torch.empty(0, dtype=torch.int32, device=self.device)
+        off = p - self.meta.data_ptr()
+        return self.meta[off:off + 4 * c].view(torch.int32).clone()
+
+    def workspace(self, layer: Layer, backward_: bool):
+        import torch
+        f, b = workspace_bytes(self.handle, layer)
+        need = b if backward_ else f
+        key = (layer.model, layer.dtype, layer.H, layer.D, backward_)
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            self._ws[key] = ws
+        return ws, need
+
+    def _check_tensors(self, layer: Layer, node_tensors, head_tensors=(), stat_tensors=()) -> None:
+        """Host-side shape / dtype checks: the C ABI carries no tensor sizes, so a wrong one would fault."""
+        import torch
+        want = torch.float32 if layer.dtype == "f32" else torch.bfloat16
+        for t in node_tensors:
+            if t is None:
+                continue
+            if t.dtype != want or t.numel() != self.N * layer.H * layer.D or t.device != self.device:
+                raise ValueError(f"node tensor must be {want} with {self.N}x{layer.H}x{layer.D} elements on {self.device}")
+        for t in head_tensors:
+            if t is not None and (t.dtype != torch.float32 or t.numel() != layer.H * layer.D):
+                raise ValueError("attention vectors must be float32 [H, D]")
+        for t in stat_tensors:
+            if t is not None and (t.dtype != torch.float32 or t.numel() != self.N * layer.H):
+                raise ValueError("softmax statistics must be float32 [N, H]")
+
+    def forward(self, layer: Layer, x, k=None, v=None, a_l=None, a_r=None, stream=None):
+        """Allocates out / row_max / row_sum and calls dfgnn_forward."""
+        import torch
+        self._check_tensors(layer, (x, k, v), (a_l, a_r))
+        out = torch.empty_like(x)
+        row_max = torch.empty((self.N, layer.H), dtype=torch.float32, device=self.device)
+        row_sum = torch.empty((self.N, layer.H), dtype=torch.float32, device=self.device)
+        ws, need = self.workspace(layer, False)
+        forward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+        return out, row_max, row_sum
+
+    def backward(self, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, stream=None):
+        """Allocates the gradient tensors and calls dfgnn_backward; returns a dict."""
+        import torch
+        self._check_tensors(layer, (x, k, v, out, d_out), (a_l, a_r), (row_max, row_sum))
+        res = {"d_x": torch.empty_like(x)}
+        d_k = d_v = d_a_l = d_a_r = d_scale = None
+        if layer.model == "gt":
+            d_k = res["d_k"] = torch.empty_like(x)
+            d_v = res["d_v"] = torch.empty_like(x)
+        elif layer.model == "gat":
+            d_a_l = res["d_a_l"] = torch.empty((layer.H, layer.D), dtype=torch.float32, device=self.device)
+            d_a_r = res["d_a_r"] = torch.empty((layer.H, layer.D), dtype=torch.float32, device=self.device)
+        else:
+            d_scale = res["d_scale"] = torch.empty(1, dtype=torch.float32, device=self.device)
+        ws, need = self.workspace(layer, True)
+        backward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, res["d_x"], d_k, d_v, d_a_l,
+                 d_a_r, d_scale, ws, ws.numel(), stream)
+        return res

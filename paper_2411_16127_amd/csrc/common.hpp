@@ -1,0 +1,65 @@
+// Internal host-side definitions shared by the translation units of libdfgnn (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/dfgnn.h"
+
+namespace dfgnn {
+
+constexpr int kDefaultSuperThreshold = 1024;
+constexpr int kDefaultChunkEdges = 512;
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Thread-local error text behind dfgnn_last_error().
+void set_error(const char* fmt, ...);
+void clear_error();
+
+#define DFGNN_HIP(expr)                                                                         \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) {                                                                 \
+            ::dfgnn::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return DFGNN_EHIP;                                                                  \
+        }                                                                                       \
+    } while (0)
+
+#define DFGNN_REQUIRE(cond, status, ...)   \
+    do {                                   \
+        if (!(cond)) {                     \
+            ::dfgnn::set_error(__VA_ARGS__); \
+            return (status);               \
+        }                                  \
+    } while (0)
+
+// Capacity of the chunk arrays for a graph with E edges: a super row has at least T edges, and a row of
+// deg edges has ceil(deg / C) <= deg / C + 1 chunks.
+inline int64_t super_capacity(int64_t E, int T) { return E / T + 1; }
+inline int64_t chunk_capacity(int64_t E, int T, int C) { return E / C + super_capacity(E, T) + 1; }
+
+// Byte offsets of the arrays inside the caller's metadata buffer.
+struct MetaLayout {
+    size_t row_order, col_order, t_indptr, t_indices, t_eid;
+    size_t row_chunk_ptr, row_chunks, col_chunk_ptr, col_chunks, counters, total;
+};
+MetaLayout meta_layout(int64_t N, int64_t E, int T, int C);
+
+}  // namespace dfgnn
+
+// The opaque handle of the ABI.
+struct dfgnn_graph {
+    int64_t N, E;
+    int T, C;
+    const int32_t* indptr;
+    const int32_t* indices;
+    int32_t *row_order, *col_order, *t_indptr, *t_indices, *t_eid;
+    int32_t *row_chunk_ptr, *row_chunks, *col_chunk_ptr, *col_chunks;
+    int32_t n_super_rows, n_row_chunks, n_super_cols, n_col_chunks;
+};

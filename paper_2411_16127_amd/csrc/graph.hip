@@ -1,0 +1,543 @@
+// Scheduler metadata for a CSR-by-destination graph, built on the GPU: row order by degree class,
+// super-row chunk list, CSC transpose, and the same for columns.  This is the preprocessing step that
+// Sec. 5.3 lists next to the fused kernels (CSR for the forward pass, CSC for the backward pass); the
+// per-row split by neighbourhood size replaces the whole-graph strategy switch of Sec. 4.2.
+//
+// All integer work; results are unique and are compared bit for bit with a CPU reference in the tests.
+// Primitives (exclusive scan, stable LSD radix sort) are written here so that buffer sizes are plain
+// formulas and no device query is needed to size them.
+#include "common.hpp"
+
+#include <cstring>
+#include <new>
+
+namespace dfgnn {
+
+// ------------------------------------------------------------------------------------------------
+// exclusive scan (int32), three launches; in == out allowed
+// ------------------------------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 8;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+__device__ inline int block_exclusive_scan(int v, int* total) {
+    // 256 threads; returns the exclusive prefix of v over the block and the block total
+    __shared__ int wave_sums[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    __syncthreads();  // protects wave_sums against a previous call
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        int s = wave_sums[w];
+        if (w < wave) before += s;
+        all += s;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_block_sums(const int* __restrict__ in, int n, int* __restrict__ sums) {
+    const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k)
+        if (base + k < n) s += in[base + k];
+    int total;
+    block_exclusive_scan(s, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_sums_inplace(int* sums, int nb) {
+    int carry = 0;
+    for (int base = 0; base < nb; base += kScanThreads) {
+        const int i = base + threadIdx.x;
+        const int v = i < nb ? sums[i] : 0;
+        int total;
+        const int ex = block_exclusive_scan(v, &total);
+        if (i < nb) sums[i] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_apply(const int* in, int* out, int n, const int* __restrict__ sums) {
+    const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+    int v[kScanItems];
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        v[k] = base + k < n ? in[base + k] : 0;
+        s += v[k];
+    }
+    int total;
+    int run = block_exclusive_scan(s, &total) + sums[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        if (base + k < n) out[base + k] = run;
+        run += v[k];
+    }
+}
+
+inline int64_t scan_blocks(int64_t n) { return (n + kScanTile - 1) / kScanTile; }
+
+static int exclusive_scan(const int* in, int* out, int64_t n, int* sums_tmp, hipStream_t st) {
+    if (n <= 0) return DFGNN_OK;
+    const int nb = (int)scan_blocks(n);
+    hipLaunchKernelGGL(k_scan_block_sums, dim3(nb), dim3(kScanThreads), 0, st, in, (int)n, sums_tmp);
+    hipLaunchKernelGGL(k_scan_sums_inplace, dim3(1), dim3(kScanThreads), 0, st, sums_tmp, nb);
+    hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(kScanThreads), 0, st, in, out, (int)n, sums_tmp);
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// stable LSD radix sort of (uint32 key, int32 value) pairs, 8-bit digits
+// ------------------------------------------------------------------------------------------------
+constexpr int kSortThreads = 256;
+constexpr int kSortItems = 16;
+constexpr int kSortTile = kSortThreads * kSortItems;  // 4096 keys per workgroup, 1024 per wave
+
+inline int64_t sort_blocks(int64_t n) { return (n + kSortTile - 1) / kSortTile; }
+
+__global__ __launch_bounds__(kSortThreads) void k_radix_hist(const uint32_t* __restrict__ keys, int n, int shift,
+                                                             int* __restrict__ counts, int nblocks) {
+    __shared__ int hist[256];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kSortTile;
+#pragma unroll
+    for (int s = 0; s < kSortItems; ++s) {
+        const int idx = base + s * kSortThreads + threadIdx.x;
+        if (idx < n) atomicAdd(&hist[(keys[idx] >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    counts[threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];
+}
+
+// lanes of the wave whose (valid) digit equals this lane's digit
+__device__ inline unsigned long long match_digit(unsigned d, bool valid) {
+    unsigned long long mask = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const unsigned long long bal = __ballot(valid && bit);
+        mask &= bit ? bal : ~bal;
+    }
+    return mask;
+}
+
+// Each wave owns 1024 consecutive keys of the tile and places them in index order, so equal digits keep
+// their relative order (stability).  values_in == nullptr means value = index (first pass).
+__global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t* __restrict__ keys_in,
+                                                                const int* __restrict__ vals_in,
+                                                                uint32_t* __restrict__ keys_out, int* __restrict__ vals_out,
+                                                                int n, int shift, const int* __restrict__ offsets,
+                                                                int nblocks) {
+    __shared__ int hist[4][256];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int base = blockIdx.x * kSortTile + wave * (kSortTile / 4);
+    uint32_t k[kSortItems];
+    int v[kSortItems];
+#pragma unroll
+    for (int s = 0; s < kSortItems; ++s) {
+        const int idx = base + s * 64 + lane;
+        const bool valid = idx < n;
+        k[s] = valid ? keys_in[idx] : 0u;
+        v[s] = valid ? (vals_in ? vals_in[idx] : idx) : 0;
+    }
+    for (int i = tid; i < 4 * 256; i += kSortThreads) (&hist[0][0])[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < kSortItems; ++s)
+        if (base + s * 64 + lane < n) atomicAdd(&hist[wave][(k[s] >> shift) & 255u], 1);
+    __syncthreads();
+    {
+        int run = offsets[tid * nblocks + blockIdx.x];  // thread tid owns digit tid
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int c = hist[w][tid];
+            hist[w][tid] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int s = 0; s < kSortItems; ++s) {
+        const bool valid = base + s * 64 + lane < n;
+        const unsigned d = (k[s] >> shift) & 255u;
+        const unsigned long long same = match_digit(d, valid);
+        if (valid) {
+            const int rank = __popcll(same & below);
+            const int first = hist[wave][d];
+            keys_out[first + rank] = k[s];
+            vals_out[first + rank] = v[s];
+            if (rank == 0) hist[wave][d] = first + __popcll(same);
+        }
+    }
+}
+
+struct SortBuffers {
+    uint32_t* keys[2];
+    int* vals[2];   // vals[final parity] is where the caller wants the sorted values
+    int* counts;    // 256 * sort_blocks(n)
+    int* scan_tmp;  // scan_blocks(256 * sort_blocks(n))
+};
+
+// Sorts by the low `bits` bits.  Returns (through *keys_sorted) the buffer holding the sorted keys;
+// sorted values land in vals_final.  vals_other is a second value buffer of n ints.
+static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32_t* keys_a, uint32_t* keys_b,
+                            int* vals_final, int* vals_other, int* counts, int* scan_tmp, const uint32_t** keys_sorted,
+                            hipStream_t st) {
+    const int passes = bits <= 8 ? 1 : (bits + 7) / 8;
+    const int nb = (int)sort_blocks(n);
+    uint32_t* kb[2] = {keys_a, keys_b};
+    int* vb[2];
+    vb[(passes - 1) & 1] = vals_final;
+    vb[passes & 1] = vals_other;
+    const uint32_t* kin = keys_in;
+    const int* vin = nullptr;
+    for (int p = 0; p < passes; ++p) {
+        hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(kSortThreads), 0, st, kin, (int)n, p * 8, counts, nb);
+        int rc = exclusive_scan(counts, counts, (int64_t)256 * nb, scan_tmp, st);
+        if (rc != DFGNN_OK) return rc;
+        hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(kSortThreads), 0, st, kin, vin, kb[p & 1], vb[p & 1], (int)n,
+                           p * 8, counts, nb);
+        kin = kb[p & 1];
+        vin = vb[p & 1];
+    }
+    DFGNN_HIP(hipGetLastError());
+    *keys_sorted = kin;
+    return DFGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// scheduler kernels
+// ------------------------------------------------------------------------------------------------
+enum { CNT_SUPER_ROWS = 0, CNT_ROW_CHUNKS = 1, CNT_SUPER_COLS = 2, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_TOTAL = 16 };
+
+__global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int bad = 0;
+    if (t <= n) {
+        const int p = indptr[t];
+        if (t == 0 && p != 0) bad |= 1;
+        if (t == n && p != e) bad |= 2;
+        if (t < n && indptr[t + 1] < p) bad |= 4;
+        if (p < 0 || p > e) bad |= 8;
+    }
+    if (t < e) {
+        const int j = indices[t];
+        if (j < 0 || j >= n) bad |= 16;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+// key 0 for super rows, else 33 - bit_length(degree): long rows sort before short ones
+__global__ void k_degree_keys(const int* __restrict__ ptr, int n, int T, uint32_t* __restrict__ keys) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int deg = ptr[i + 1] - ptr[i];
+    keys[i] = deg >= T ? 0u : (uint32_t)(33 - (32 - __clz(deg)));
+}
+
+// number of leading zero keys in the sorted key array
+__global__ void k_count_zero_keys(const uint32_t* __restrict__ sorted, int n, int* out) {
+    if (blockIdx.x || threadIdx.x) return;
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (sorted[mid] == 0u) lo = mid + 1; else hi = mid;
+    }
+    *out = lo;
+}
+
+__global__ void k_chunk_counts(const int* __restrict__ order, const int* __restrict__ ptr, int n_super, int C,
+                               int* __restrict__ cnt) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s > n_super) return;
+    if (s == n_super) { cnt[s] = 0; return; }
+    const int r = order[s];
+    cnt[s] = (ptr[r + 1] - ptr[r] + C - 1) / C;
+}
+
+__global__ void k_fill_chunks(const int* __restrict__ order, const int* __restrict__ ptr,
+                              const int* __restrict__ chunk_ptr, int n_super, int n_chunks, int C, int* __restrict__ chunks) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n_chunks) return;
+    int lo = 0, hi = n_super;  // last s with chunk_ptr[s] <= c
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (chunk_ptr[mid] <= c) lo = mid; else hi = mid;
+    }
+    const int r = order[lo];
+    const int b = ptr[r] + (c - chunk_ptr[lo]) * C;
+    const int e = min(b + C, ptr[r + 1]);
+    chunks[3 * c + 0] = r;
+    chunks[3 * c + 1] = b;
+    chunks[3 * c + 2] = e;
+}
+
+// t_indptr[j] = number of edges whose source is < j = lower bound of j in the sorted source array
+__global__ void k_pointer_from_sorted(const uint32_t* __restrict__ sorted, int e, int n, int* __restrict__ t_indptr) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j > n) return;
+    int lo = 0, hi = e;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (sorted[mid] < (uint32_t)j) lo = mid + 1; else hi = mid;
+    }
+    t_indptr[j] = lo;
+}
+
+// destination row of CSR position p: the last row whose pointer is <= p
+__global__ void k_rows_of_positions(const int* __restrict__ t_eid, const int* __restrict__ indptr, int n, int e,
+                                    int* __restrict__ t_indices) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= e) return;
+    const int p = t_eid[t];
+    int lo = 0, hi = n;  // invariant: indptr[lo] <= p < indptr[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (indptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    t_indices[t] = lo;
+}
+
+// ------------------------------------------------------------------------------------------------
+// layout of the caller's buffers
+// ------------------------------------------------------------------------------------------------
+MetaLayout meta_layout(int64_t N, int64_t E, int T, int C) {
+    MetaLayout L{};
+    size_t off = 0;
+    auto take = [&](int64_t count) { size_t o = off; off += align_up((size_t)(count > 0 ? count : 1) * sizeof(int32_t)); return o; };
+    L.row_order = take(N);
+    L.col_order = take(N);
+    L.t_indptr = take(N + 1);
+    L.t_indices = take(E);
+    L.t_eid = take(E);
+    L.row_chunk_ptr = take(super_capacity(E, T) + 1);
+    L.row_chunks = take(3 * chunk_capacity(E, T, C));
+    L.col_chunk_ptr = take(super_capacity(E, T) + 1);
+    L.col_chunks = take(3 * chunk_capacity(E, T, C));
+    L.counters = take(CNT_TOTAL);
+    L.total = off;
+    return L;
+}
+
+struct ScratchLayout {
+    size_t keys_a, keys_b, vals, counts, scan_tmp, cnt, total;
+};
+
+static ScratchLayout scratch_layout(int64_t N, int64_t E, int T) {
+    ScratchLayout L{};
+    const int64_t M = N > E ? N : E;
+    size_t off = 0;
+    auto take = [&](int64_t count) { size_t o = off; off += align_up((size_t)(count > 0 ? count : 1) * sizeof(int32_t)); return o; };
+    L.keys_a = take(M);
+    L.keys_b = take(M);
+    L.vals = take(M);
+    const int64_t ncounts = 256 * sort_blocks(M);
+    L.counts = take(ncounts);
+    const int64_t cap = super_capacity(E, T) + 2;
+    L.scan_tmp = take(scan_blocks(ncounts > cap ? ncounts : cap) + 1);
+    L.cnt = take(cap);
+    L.total = off;
+    return L;
+}
+
+static int resolve_params(const dfgnn_sched_params* sched, int* T, int* C) {
+    *T = kDefaultSuperThreshold;
+    *C = kDefaultChunkEdges;
+    if (sched) {
+        for (int r : sched->reserved) DFGNN_REQUIRE(r == 0, DFGNN_EINVAL, "dfgnn_sched_params.reserved must be zero");
+        DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
+                      "negative scheduling parameter");
+        if (sched->super_threshold > 0) *T = sched->super_threshold;
+        if (sched->chunk_edges > 0) *C = sched->chunk_edges;
+    }
+    return DFGNN_OK;
+}
+
+// Row (or column) order and super chunks for one pointer array.
+static int build_schedule(const int* ptr, int64_t n, int T, int C, int* order, int* chunk_ptr, int* chunks,
+                          int* d_counters, int slot_super, int slot_chunks, char* scratch, const ScratchLayout& S,
+                          int* n_super_out, int* n_chunks_out, hipStream_t st) {
+    *n_super_out = 0;
+    *n_chunks_out = 0;
+    if (n == 0) return DFGNN_OK;
+    uint32_t* keys_a = (uint32_t*)(scratch + S.keys_a);
+    uint32_t* keys_b = (uint32_t*)(scratch + S.keys_b);
+    int* vals = (int*)(scratch + S.vals);
+    int* counts = (int*)(scratch + S.counts);
+    int* scan_tmp = (int*)(scratch + S.scan_tmp);
+    int* cnt = (int*)(scratch + S.cnt);
+    const int tpb = 256;
+    hipLaunchKernelGGL(k_degree_keys, dim3((unsigned)((n + tpb - 1) / tpb)), dim3(tpb), 0, st, ptr, (int)n, T, keys_a);
+    const uint32_t* sorted = nullptr;
+    int rc = radix_sort_pairs(keys_a, n, 6, keys_b, keys_a, order, vals, counts, scan_tmp, &sorted, st);
+    if (rc != DFGNN_OK) return rc;
+    hipLaunchKernelGGL(k_count_zero_keys, dim3(1), dim3(64), 0, st, sorted, (int)n, d_counters + slot_super);
+    int n_super = 0;
+    DFGNN_HIP(hipMemcpyAsync(&n_super, d_counters + slot_super, sizeof(int), hipMemcpyDeviceToHost, st));
+    DFGNN_HIP(hipStreamSynchronize(st));
+    *n_super_out = n_super;
+    if (n_super == 0) return DFGNN_OK;
+    hipLaunchKernelGGL(k_chunk_counts, dim3((unsigned)((n_super + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
+                       n_super, C, cnt);
+    rc = exclusive_scan(cnt, chunk_ptr, (int64_t)n_super + 1, scan_tmp, st);
+    if (rc != DFGNN_OK) return rc;
+    int n_chunks = 0;
+    DFGNN_HIP(hipMemcpyAsync(&n_chunks, chunk_ptr + n_super, sizeof(int), hipMemcpyDeviceToHost, st));
+    DFGNN_HIP(hipMemcpyAsync(d_counters + slot_chunks, chunk_ptr + n_super, sizeof(int), hipMemcpyDeviceToDevice, st));
+    DFGNN_HIP(hipStreamSynchronize(st));
+    *n_chunks_out = n_chunks;
+    hipLaunchKernelGGL(k_fill_chunks, dim3((unsigned)((n_chunks + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
+                       chunk_ptr, n_super, n_chunks, C, chunks);
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+}  // namespace dfgnn
+
+using namespace dfgnn;
+
+extern "C" int dfgnn_graph_meta_bytes(int64_t N, int64_t E, const dfgnn_sched_params* sched, size_t* meta_bytes,
+                                      size_t* scratch_bytes) {
+    clear_error();
+    DFGNN_REQUIRE(N >= 0 && E >= 0, DFGNN_EINVAL, "negative graph size N=%lld E=%lld", (long long)N, (long long)E);
+    DFGNN_REQUIRE(N < (int64_t)INT32_MAX - (1 << 20) && E < (int64_t)INT32_MAX - (1 << 20), DFGNN_EUNSUPPORTED,
+                  "graph too large for int32 indexing");
+    int T, C;
+    int rc = resolve_params(sched, &T, &C);
+    if (rc != DFGNN_OK) return rc;
+    if (meta_bytes) *meta_bytes = meta_layout(N, E, T, C).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(N, E, T).total;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr,
+                                  const int32_t* d_indices, const dfgnn_sched_params* sched, void* d_meta,
+                                  size_t meta_bytes, void* d_scratch, size_t scratch_bytes, void* stream) {
+    clear_error();
+    DFGNN_REQUIRE(out != nullptr, DFGNN_EINVAL, "out is NULL");
+    *out = nullptr;
+    size_t need_meta = 0, need_scratch = 0;
+    int rc = dfgnn_graph_meta_bytes(N, E, sched, &need_meta, &need_scratch);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_REQUIRE(d_indptr != nullptr && (E == 0 || d_indices != nullptr), DFGNN_EINVAL, "indptr / indices is NULL");
+    DFGNN_REQUIRE(d_meta != nullptr && d_scratch != nullptr, DFGNN_EINVAL, "metadata / scratch buffer is NULL");
+    DFGNN_REQUIRE(((uintptr_t)d_meta % kAlign) == 0 && ((uintptr_t)d_scratch % kAlign) == 0, DFGNN_EUNSUPPORTED,
+                  "metadata / scratch buffer must be 256-byte aligned");
+    DFGNN_REQUIRE(meta_bytes >= need_meta, DFGNN_EWORKSPACE, "metadata buffer has %zu bytes, needs %zu", meta_bytes, need_meta);
+    DFGNN_REQUIRE(scratch_bytes >= need_scratch, DFGNN_EWORKSPACE, "scratch buffer has %zu bytes, needs %zu",
+                  scratch_bytes, need_scratch);
+    int T, C;
+    rc = resolve_params(sched, &T, &C);
+    if (rc != DFGNN_OK) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    const MetaLayout M = meta_layout(N, E, T, C);
+    const ScratchLayout S = scratch_layout(N, E, T);
+    char* meta = (char*)d_meta;
+    char* scratch = (char*)d_scratch;
+
+    dfgnn_graph g{};
+    g.N = N; g.E = E; g.T = T; g.C = C;
+    g.indptr = d_indptr; g.indices = d_indices;
+    g.row_order = (int*)(meta + M.row_order);
+    g.col_order = (int*)(meta + M.col_order);
+    g.t_indptr = (int*)(meta + M.t_indptr);
+    g.t_indices = (int*)(meta + M.t_indices);
+    g.t_eid = (int*)(meta + M.t_eid);
+    g.row_chunk_ptr = (int*)(meta + M.row_chunk_ptr);
+    g.row_chunks = (int*)(meta + M.row_chunks);
+    g.col_chunk_ptr = (int*)(meta + M.col_chunk_ptr);
+    g.col_chunks = (int*)(meta + M.col_chunks);
+    int* d_counters = (int*)(meta + M.counters);
+
+    const int tpb = 256;
+    DFGNN_HIP(hipMemsetAsync(d_counters, 0, CNT_TOTAL * sizeof(int), st));
+    {
+        const int64_t span = (N + 1 > E ? N + 1 : E);
+        hipLaunchKernelGGL(k_validate, dim3((unsigned)((span + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr, d_indices,
+                           (int)N, (int)E, d_counters + CNT_ERROR);
+        int flags = 0;
+        DFGNN_HIP(hipMemcpyAsync(&flags, d_counters + CNT_ERROR, sizeof(int), hipMemcpyDeviceToHost, st));
+        DFGNN_HIP(hipStreamSynchronize(st));
+        DFGNN_REQUIRE(flags == 0, DFGNN_EINVAL,
+                      "malformed CSR (flags 0x%x: 1 indptr[0]!=0, 2 indptr[N]!=E, 4 indptr decreases, 8 indptr out of "
+                      "range, 16 index out of range)", flags);
+    }
+
+    // rows: order and chunks
+    rc = build_schedule(d_indptr, N, T, C, g.row_order, g.row_chunk_ptr, g.row_chunks, d_counters, CNT_SUPER_ROWS,
+                        CNT_ROW_CHUNKS, scratch, S, &g.n_super_rows, &g.n_row_chunks, st);
+    if (rc != DFGNN_OK) return rc;
+
+    // CSC transpose: stable sort of CSR positions by source id
+    if (E > 0) {
+        int bits = 1;
+        while (((int64_t)1 << bits) < N) ++bits;
+        const uint32_t* sorted = nullptr;
+        rc = radix_sort_pairs((const uint32_t*)d_indices, E, bits, (uint32_t*)(scratch + S.keys_a),
+                              (uint32_t*)(scratch + S.keys_b), g.t_eid, (int*)(scratch + S.vals),
+                              (int*)(scratch + S.counts), (int*)(scratch + S.scan_tmp), &sorted, st);
+        if (rc != DFGNN_OK) return rc;
+        hipLaunchKernelGGL(k_pointer_from_sorted, dim3((unsigned)((N + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, sorted,
+                           (int)E, (int)N, g.t_indptr);
+        hipLaunchKernelGGL(k_rows_of_positions, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid,
+                           d_indptr, (int)N, (int)E, g.t_indices);
+        DFGNN_HIP(hipGetLastError());
+    } else {
+        DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));
+    }
+
+    // columns: order and chunks
+    rc = build_schedule(g.t_indptr, N, T, C, g.col_order, g.col_chunk_ptr, g.col_chunks, d_counters, CNT_SUPER_COLS,
+                        CNT_COL_CHUNKS, scratch, S, &g.n_super_cols, &g.n_col_chunks, st);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_HIP(hipStreamSynchronize(st));
+
+    dfgnn_graph* h = new (std::nothrow) dfgnn_graph(g);
+    DFGNN_REQUIRE(h != nullptr, DFGNN_EINVAL, "out of host memory");
+    *out = h;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_graph_destroy(dfgnn_graph* graph) {
+    clear_error();
+    delete graph;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_graph_query(const dfgnn_graph* g, int what, const void** d_ptr, int64_t* count) {
+    clear_error();
+    DFGNN_REQUIRE(g != nullptr && count != nullptr, DFGNN_EINVAL, "NULL argument");
+    const void* p = nullptr;
+    int64_t c = 0;
+    switch (what) {
+    case DFGNN_Q_ROW_ORDER: p = g->row_order; c = g->N; break;
+    case DFGNN_Q_ROW_CHUNK_PTR: p = g->row_chunk_ptr; c = g->n_super_rows ? g->n_super_rows + 1 : 0; break;
+    case DFGNN_Q_ROW_CHUNKS: p = g->row_chunks; c = 3 * (int64_t)g->n_row_chunks; break;
+    case DFGNN_Q_T_INDPTR: p = g->t_indptr; c = g->N + 1; break;
+    case DFGNN_Q_T_INDICES: p = g->t_indices; c = g->E; break;
+    case DFGNN_Q_T_EID: p = g->t_eid; c = g->E; break;
+    case DFGNN_Q_COL_ORDER: p = g->col_order; c = g->N; break;
+    case DFGNN_Q_COL_CHUNK_PTR: p = g->col_chunk_ptr; c = g->n_super_cols ? g->n_super_cols + 1 : 0; break;
+    case DFGNN_Q_COL_CHUNKS: p = g->col_chunks; c = 3 * (int64_t)g->n_col_chunks; break;
+    case DFGNN_Q_N_SUPER_ROWS: c = g->n_super_rows; break;
+    case DFGNN_Q_N_SUPER_COLS: c = g->n_super_cols; break;
+    default: DFGNN_REQUIRE(false, DFGNN_EINVAL, "unknown query item %d", what);
+    }
+    if (d_ptr) *d_ptr = p;
+    *count = c;
+    return DFGNN_OK;
+}

@@ -1,0 +1,328 @@
+// Host side of the layer calls: argument checks, workspace carving, lane-geometry selection and the
+// launch sequence of the fused kernels (Eq. 1 forward; Appendix B backward as a CSR row pass and a CSC
+// column pass).  Every launch goes to the caller's stream; nothing here synchronises or allocates.
+#include "common.hpp"
+#include "layer_device.hpp"
+
+namespace dfgnn {
+
+constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the first is consumed
+
+// ---------------------------------------------------------------------------------------------
+// lane geometry
+// ---------------------------------------------------------------------------------------------
+struct Geometry {
+    int vec;  // elements per lane
+    int lph;  // lanes per head
+    int lpe;  // lanes per neighbour row (power of two, >= 4)
+    int id;   // index into the instantiation table, -1 if none
+};
+
+// (type, LPE, LPH): LPH = 0 handles any head width at run time; the others are the shapes of the
+// benchmark workloads with compile-time DPP reductions.
+#define DFGNN_GEOMETRIES(X)                                                                        \
+    X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)   \
+    X(5, float, 16, 16) X(6, float, 32, 4) X(7, float, 16, 2)                                      \
+    X(8, bf16_t, 4, 0) X(9, bf16_t, 8, 0) X(10, bf16_t, 16, 0) X(11, bf16_t, 32, 0) X(12, bf16_t, 64, 0) \
+    X(13, bf16_t, 16, 2)
+
+static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
+    DFGNN_REQUIRE(L->dtype == DFGNN_F32 || L->dtype == DFGNN_BF16, DFGNN_EINVAL, "unknown dtype %d", L->dtype);
+    DFGNN_REQUIRE(L->H >= 1 && L->D >= 1, DFGNN_EINVAL, "H and D must be positive (H=%d D=%d)", L->H, L->D);
+    Geometry g{};
+    g.vec = L->dtype == DFGNN_F32 ? 4 : 8;
+    DFGNN_REQUIRE(L->D % g.vec == 0, DFGNN_EUNSUPPORTED, "D=%d: a head must be a multiple of 16 bytes", L->D);
+    g.lph = L->D / g.vec;
+    DFGNN_REQUIRE((g.lph & (g.lph - 1)) == 0, DFGNN_EUNSUPPORTED, "D=%d: D/%d must be a power of two", L->D, g.vec);
+    const int lanes = L->H * g.lph;
+    DFGNN_REQUIRE(lanes <= 64, DFGNN_EUNSUPPORTED, "H*D=%d exceeds one wavefront of 16-byte lanes", L->H * L->D);
+    g.lpe = 4;
+    while (g.lpe < lanes) g.lpe <<= 1;
+    const bool f32 = L->dtype == DFGNN_F32;
+    g.id = -1;
+    if (f32 && g.lpe == 16 && lanes == 16 && g.lph == 16) g.id = 5;
+    else if (f32 && g.lpe == 32 && lanes == 32 && g.lph == 4) g.id = 6;
+    else if (f32 && g.lpe == 16 && lanes == 16 && g.lph == 2) g.id = 7;
+    else if (!f32 && g.lpe == 16 && lanes == 16 && g.lph == 2) g.id = 13;
+    else {
+        int k = 0;
+        for (int l = 4; l < g.lpe; l <<= 1) ++k;
+        g.id = (f32 ? 0 : 8) + k;
+    }
+    *out = g;
+    return DFGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// workspace layout (float offsets turned into pointers)
+// ---------------------------------------------------------------------------------------------
+struct Workspace {
+    size_t node_a, node_b, stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, reduce, total;
+};
+
+static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward) {
+    Workspace W{};
+    size_t off = 0;
+    auto take = [&](size_t floats) { size_t o = off; off += align_up((floats ? floats : 1) * sizeof(float)); return o; };
+    const size_t N = (size_t)g->N, H = (size_t)L->H, HD = (size_t)L->H * L->D;
+    const size_t chunks = backward ? (size_t)(g->n_row_chunks > g->n_col_chunks ? g->n_row_chunks : g->n_col_chunks)
+                                   : (size_t)g->n_row_chunks;
+    const bool gat = L->model == DFGNN_GAT, agnn = L->model == DFGNN_AGNN;
+    W.node_a = take(gat || agnn ? N * H : 0);
+    W.node_b = take(gat ? N * H : 0);
+    W.part_v0 = take(chunks * HD);
+    W.part_s0 = take(chunks * H);
+    W.part_s1 = take(chunks * H);
+    if (backward) {
+        W.stats = take(N * H * (L->model == DFGNN_GT ? 2 : 4));
+        W.part_v1 = take(chunks * HD);
+        W.d_el = take(gat ? N * H : 0);
+        W.d_er = take(gat ? N * H : 0);
+        W.g_row = take(agnn ? N * HD : 0);
+        W.dbeta_row = take(agnn ? N * H : 0);
+        W.reduce = take(gat ? (size_t)kReduceBlocks * 2 * HD : (agnn ? (size_t)kReduceBlocks : 0));
+    }
+    W.total = off;
+    return W;
+}
+
+static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward) {
+    char* b = (char*)ws;
+    a.node_a = (float*)(b + W.node_a);
+    a.node_b = (float*)(b + W.node_b);
+    a.part_v0 = (float*)(b + W.part_v0);
+    a.part_s0 = (float*)(b + W.part_s0);
+    a.part_s1 = (float*)(b + W.part_s1);
+    if (backward) {
+        a.stats = (float*)(b + W.stats);
+        a.part_v1 = (float*)(b + W.part_v1);
+        a.d_el = (float*)(b + W.d_el);
+        a.d_er = (float*)(b + W.d_er);
+        a.g_row = (float*)(b + W.g_row);
+        a.dbeta_row = (float*)(b + W.dbeta_row);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launch sequences
+// ---------------------------------------------------------------------------------------------
+static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock); }
+
+// chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
+template <class G, template <class, int> class PassT>
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, hipStream_t st) {
+    a.ptr = columns ? g->t_indptr : g->indptr;
+    a.idx = columns ? g->t_indices : g->indices;
+    a.order = columns ? g->col_order : g->row_order;
+    a.chunks = columns ? g->col_chunks : g->row_chunks;
+    a.chunk_ptr = columns ? g->col_chunk_ptr : g->row_chunk_ptr;
+    const int n_super = columns ? g->n_super_cols : g->n_super_rows;
+    const int n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
+    const int64_t n_direct = g->N - n_super;
+    const dim3 block(64 * kWavesPerBlock);
+    if (n_chunks > 0) {
+        a.first = 0;
+        a.n_items = n_chunks;
+        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, true>), dim3(blocks_for(n_chunks)), block, 0, st, a);
+    }
+    if (n_direct > 0) {
+        a.first = n_super;
+        a.n_items = (int)n_direct;
+        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, false>), dim3(blocks_for(n_direct)), block, 0, st, a);
+    }
+    if (n_super > 0) {
+        a.first = 0;
+        a.n_items = n_super;
+        hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
+    }
+}
+
+template <class G, bool IS_GAT> static void run_node_terms(const Args& a, hipStream_t st) {
+    if (a.n_nodes <= 0) return;
+    const int64_t waves = ((int64_t)a.n_nodes + G::EPW - 1) / G::EPW;
+    hipLaunchKernelGGL((k_node_terms<G, IS_GAT>), dim3(blocks_for(waves)), dim3(64 * kWavesPerBlock), 0, st, a);
+}
+
+template <class G> static void run_forward(const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
+    switch (model) {
+    case DFGNN_GT: run_pass<G, GtFwd>(g, false, a, st); break;
+    case DFGNN_GAT:
+        run_node_terms<G, true>(a, st);
+        run_pass<G, GatFwd>(g, false, a, st);
+        break;
+    default:
+        run_node_terms<G, false>(a, st);
+        run_pass<G, AgnnFwd>(g, false, a, st);
+        break;
+    }
+}
+
+template <class G>
+static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
+                         float* d_scale, hipStream_t st) {
+    switch (model) {
+    case DFGNN_GT:
+        run_pass<G, GtBwdRow>(g, false, a, st);
+        run_pass<G, GtBwdCol>(g, true, a, st);
+        break;
+    case DFGNN_GAT:
+        run_node_terms<G, true>(a, st);
+        run_pass<G, GatBwdRow>(g, false, a, st);
+        run_pass<G, GatBwdCol>(g, true, a, st);
+        hipLaunchKernelGGL((k_gat_param_partial<typename G::T>), dim3(kReduceBlocks), dim3(256), 0, st, a, reduce_tmp);
+        hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+        break;
+    default:
+        run_node_terms<G, false>(a, st);
+        run_pass<G, AgnnBwdRow>(g, false, a, st);
+        run_pass<G, AgnnBwdCol>(g, true, a, st);
+        hipLaunchKernelGGL(k_sum_partial, dim3(kReduceBlocks), dim3(256), 0, st, a.dbeta_row,
+                           (int64_t)a.n_nodes * a.H, reduce_tmp);
+        hipLaunchKernelGGL(k_sum_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, d_scale);
+        break;
+    }
+}
+
+static int dispatch_forward(int geo, const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
+    switch (geo) {
+#define X(ID, T, LPE, LPH) case ID: run_forward<Geo<T, LPE, LPH>>(g, model, a, st); break;
+        DFGNN_GEOMETRIES(X)
+#undef X
+    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    }
+    return DFGNN_OK;
+}
+
+static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l,
+                             float* d_a_r, float* d_scale, hipStream_t st) {
+    switch (geo) {
+#define X(ID, T, LPE, LPH) case ID: run_backward<Geo<T, LPE, LPH>>(g, model, a, reduce_tmp, d_a_l, d_a_r, d_scale, st); break;
+        DFGNN_GEOMETRIES(X)
+#undef X
+    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    }
+    return DFGNN_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo) {
+    DFGNN_REQUIRE(g != nullptr && L != nullptr, DFGNN_EINVAL, "graph / layer is NULL");
+    DFGNN_REQUIRE(L->model == DFGNN_GT || L->model == DFGNN_GAT || L->model == DFGNN_AGNN, DFGNN_EINVAL,
+                  "unknown model %d", L->model);
+    DFGNN_REQUIRE(L->reserved[0] == 0, DFGNN_EINVAL, "dfgnn_layer.reserved must be zero");
+    int rc = pick_geometry(L, geo);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_REQUIRE((int64_t)g->N * L->H * L->D < ((int64_t)1 << 40), DFGNN_EUNSUPPORTED, "node tensor too large");
+    if (L->model == DFGNN_AGNN) DFGNN_REQUIRE(L->eps > 0.f, DFGNN_EINVAL, "AGNN eps must be positive");
+    return DFGNN_OK;
+}
+
+static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, const Geometry& geo) {
+    a.n_nodes = (int)g->N;
+    a.H = L->H;
+    a.D = L->D;
+    a.HD = L->H * L->D;
+    a.lph = geo.lph;
+    a.scale = L->model == DFGNN_GAT ? 1.f : L->scale;
+    a.c_score = a.scale * kLog2e;
+    a.neg_slope = L->neg_slope;
+    a.eps = L->eps;
+}
+
+}  // namespace dfgnn
+
+using namespace dfgnn;
+
+extern "C" int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer* layer, size_t* fwd_bytes,
+                                     size_t* bwd_bytes) {
+    clear_error();
+    Geometry geo;
+    int rc = check_layer(graph, layer, &geo);
+    if (rc != DFGNN_OK) return rc;
+    if (fwd_bytes) *fwd_bytes = workspace_layout(graph, layer, false).total;
+    if (bwd_bytes) *bwd_bytes = workspace_layout(graph, layer, true).total;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                             const void* v, const float* a_l, const float* a_r, void* out, float* row_max,
+                             float* row_sum, void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    Geometry geo;
+    int rc = check_layer(graph, layer, &geo);
+    if (rc != DFGNN_OK) return rc;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT;
+    DFGNN_REQUIRE(x && out && row_max && row_sum, DFGNN_EINVAL, "x / out / row_max / row_sum is NULL");
+    DFGNN_REQUIRE(!gt || (k && v), DFGNN_EINVAL, "GT needs k and v");
+    DFGNN_REQUIRE(gt || (!k && !v), DFGNN_EINVAL, "k and v must be NULL unless the model is GT");
+    DFGNN_REQUIRE(!gat || (a_l && a_r), DFGNN_EINVAL, "GAT needs a_l and a_r");
+    DFGNN_REQUIRE(gat || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT");
+    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
+                  DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+    const Workspace W = workspace_layout(graph, layer, false);
+    DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
+    DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
+    DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, forward needs %zu",
+                  workspace_bytes, W.total);
+    if (graph->N == 0) return DFGNN_OK;
+
+    Args a{};
+    fill_common(a, graph, layer, geo);
+    a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
+    a.o = out; a.o_max = row_max; a.o_sum = row_sum;
+    bind_workspace(a, W, workspace, false);
+    rc = dispatch_forward(geo.id, graph, layer->model, a, (hipStream_t)stream);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                              const void* v, const float* a_l, const float* a_r, const void* out, const float* row_max,
+                              const float* row_sum, const void* d_out, void* d_x, void* d_k, void* d_v, float* d_a_l,
+                              float* d_a_r, float* d_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    Geometry geo;
+    int rc = check_layer(graph, layer, &geo);
+    if (rc != DFGNN_OK) return rc;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN;
+    DFGNN_REQUIRE(x && out && row_max && row_sum && d_out && d_x, DFGNN_EINVAL,
+                  "x / out / row_max / row_sum / d_out / d_x is NULL");
+    DFGNN_REQUIRE(!gt || (k && v && d_k && d_v), DFGNN_EINVAL, "GT needs k, v, d_k and d_v");
+    DFGNN_REQUIRE(gt || (!k && !v && !d_k && !d_v), DFGNN_EINVAL, "k, v, d_k, d_v must be NULL unless the model is GT");
+    DFGNN_REQUIRE(!gat || (a_l && a_r && d_a_l && d_a_r), DFGNN_EINVAL, "GAT needs a_l, a_r, d_a_l and d_a_r");
+    DFGNN_REQUIRE(gat || (!a_l && !a_r && !d_a_l && !d_a_r), DFGNN_EINVAL,
+                  "a_l, a_r, d_a_l, d_a_r must be NULL unless the model is GAT");
+    DFGNN_REQUIRE(!agnn || d_scale, DFGNN_EINVAL, "AGNN needs d_scale");
+    DFGNN_REQUIRE(agnn || !d_scale, DFGNN_EINVAL, "d_scale must be NULL unless the model is AGNN");
+    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&
+                      aligned16(d_k) && aligned16(d_v) && aligned16(a_l) && aligned16(a_r),
+                  DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+    const Workspace W = workspace_layout(graph, layer, true);
+    DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
+    DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
+    DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, backward needs %zu",
+                  workspace_bytes, W.total);
+    hipStream_t st = (hipStream_t)stream;
+    if (graph->N == 0) {
+        if (gat) {
+            DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, st));
+            DFGNN_HIP(hipMemsetAsync(d_a_r, 0, sizeof(float) * layer->H * layer->D, st));
+        }
+        if (agnn) DFGNN_HIP(hipMemsetAsync(d_scale, 0, sizeof(float), st));
+        return DFGNN_OK;
+    }
+
+    Args a{};
+    fill_common(a, graph, layer, geo);
+    a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
+    a.out = out; a.row_max = row_max; a.row_sum = row_sum; a.d_out = d_out;
+    a.d_x = d_x; a.d_k = d_k; a.d_v = d_v;
+    bind_workspace(a, W, workspace, true);
+    float* reduce_tmp = (float*)((char*)workspace + W.reduce);
+    rc = dispatch_backward(geo.id, graph, layer->model, a, reduce_tmp, d_a_l, d_a_r, d_scale, st);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}

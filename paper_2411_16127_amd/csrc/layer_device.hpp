@@ -1,0 +1,957 @@
+// Device-side building blocks of the fused attention-GNN layer kernels (gfx950, wave64).
+//
+// Work mapping (the node-parallel / edge-parallel choice of Sec. 2.2 and Sec. 4.1, taken per row):
+//   * one wavefront processes one work item: a whole row (node-parallel) or one chunk of a super row
+//     (edge-parallel split); chunk partials are combined by a merge kernel;
+//   * inside the wavefront, LPE adjacent lanes cover one neighbour's feature row with one 16-byte load
+//     each, so 64/LPE neighbours are in flight per load instruction (coalesced, vectorised access of
+//     Sec. 4.2 "SpMM"); U such instructions are issued back to back before any is consumed;
+//   * a head's dot product is reduced over its LPH lanes with DPP cross-lane moves; the softmax is kept
+//     online per edge slot (max / sum / accumulator in registers), so no score or attention weight is
+//     ever stored (Sec. 4.2 "Softmax": no duplicated work, no recomputation inside a pass).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace dfgnn {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+struct bf16_t { uint16_t bits; };
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ---------------------------------------------------------------------------------------------
+// element types: a lane owns VEC consecutive elements = 16 bytes of a node row
+// ---------------------------------------------------------------------------------------------
+template <typename T> struct Elem;
+
+template <> struct Elem<float> {
+    static constexpr int VEC = 4;
+    __device__ static void unpack(const u32x4& r, float (&x)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = __builtin_bit_cast(float, (uint32_t)r[i]);
+    }
+    __device__ static void store(float* p, const float (&x)[4]) {
+        f32x4 t = {x[0], x[1], x[2], x[3]};
+        *reinterpret_cast<f32x4*>(p) = t;
+    }
+};
+
+template <> struct Elem<bf16_t> {
+    static constexpr int VEC = 8;
+    __device__ static void unpack(const u32x4& r, float (&x)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w = r[i];
+            x[2 * i] = __builtin_bit_cast(float, w << 16);
+            x[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
+        }
+    }
+    __device__ static uint32_t round_bits(float f) {  // round to nearest even, keep the high half
+        uint32_t u = __builtin_bit_cast(uint32_t, f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    __device__ static void store(bf16_t* p, const float (&x)[8]) {
+        u32x4 t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = round_bits(x[2 * i]) | (round_bits(x[2 * i + 1]) << 16);
+        *reinterpret_cast<u32x4*>(p) = t;
+    }
+};
+
+template <typename T> __device__ inline u32x4 load_raw(const void* base, size_t elem_offset) {
+    return *reinterpret_cast<const u32x4*>(static_cast<const T*>(base) + elem_offset);
+}
+
+template <int VEC> __device__ inline void load_f32(const float* p, float (&x)[VEC]) {
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(p + i);
+        x[i] = t[0]; x[i + 1] = t[1]; x[i + 2] = t[2]; x[i + 3] = t[3];
+    }
+}
+template <int VEC> __device__ inline void store_f32(float* p, const float (&x)[VEC]) {
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) {
+        f32x4 t = {x[i], x[i + 1], x[i + 2], x[i + 3]};
+        *reinterpret_cast<f32x4*>(p + i) = t;
+    }
+}
+
+template <int VEC> __device__ inline float dotv(const float (&a)[VEC], const float (&b)[VEC]) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s = fmaf(a[i], b[i], s);
+    return s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// cross-lane reductions
+// ---------------------------------------------------------------------------------------------
+template <int CTRL> __device__ inline float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPH adjacent lanes of one head; every lane of the head gets the total.
+// LPH = 0: the head width is the run-time value lph (a power of two).
+template <int LPH> __device__ inline float head_sum(float x, int lph) {
+    if constexpr (LPH == 0) {
+        for (int o = 1; o < lph; o <<= 1) x += __shfl_xor(x, o);
+    } else {
+        if constexpr (LPH >= 2) x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+        if constexpr (LPH >= 4) x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+        if constexpr (LPH >= 8) x += dpp_move<0x141>(x);  // row_half_mirror
+        if constexpr (LPH >= 16) x += dpp_move<0x140>(x); // row_mirror
+        if constexpr (LPH >= 32) x += __shfl_xor(x, 16);
+        if constexpr (LPH >= 64) x += __shfl_xor(x, 32);
+    }
+    return x;
+}
+
+// Sum over the 64/LPE edge slots of the wavefront (lanes that own the same features).
+template <int LPE> __device__ inline float slot_sum(float x) {
+#pragma unroll
+    for (int o = LPE; o < 64; o <<= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernel arguments
+// ---------------------------------------------------------------------------------------------
+struct Args {
+    // work list: CSR (rows) for forward / backward row pass, CSC (columns) for the backward column pass
+    const int* ptr;
+    const int* idx;
+    const int* order;
+    const int* chunks;
+    const int* chunk_ptr;
+    int first;    // direct pass: items are order[first + w]
+    int n_items;  // waves that have work
+    int n_nodes;
+    // shape and constants
+    int H, D, HD, lph;
+    float c_score;  // GT scale*log2(e); AGNN beta*log2(e); GAT log2(e)
+    float scale;    // GT scale; AGNN beta
+    float neg_slope, eps;
+    // tensors in the layer dtype
+    const void *x, *k, *v, *out, *d_out;
+    void *o, *d_x, *d_k, *d_v;
+    // fp32 tensors
+    const float *a_l, *a_r, *row_max, *row_sum;
+    float *o_max, *o_sum;
+    // workspace
+    float* node_a;     // GAT: el*log2e [N,H]; AGNN: 1/max(|h|,eps) [N,H]
+    float* node_b;     // GAT: er*log2e [N,H]
+    float* stats;      // per (row, head): GT {lse2, delta}; GAT {el2, lse2, delta, 0}; AGNN {rn, lse2, delta, 0}
+    float* d_el;       // GAT [N,H]
+    float* d_er;       // GAT [N,H]
+    float* g_row;      // AGNN [N,HD] row-side gradient w.r.t. normalised features
+    float* dbeta_row;  // AGNN [N,H]
+    float* part_v0;    // [chunks, HD]
+    float* part_v1;    // [chunks, HD]
+    float* part_s0;    // [chunks, H]
+    float* part_s1;    // [chunks, H]
+};
+
+// Lane geometry: LPE lanes per neighbour row, LPH lanes per head (0 = run-time), element type T.
+template <typename T_, int LPE_, int LPH_> struct Geo {
+    using T = T_;
+    static constexpr int LPE = LPE_, LPH = LPH_, VEC = Elem<T_>::VEC, EPW = 64 / LPE_;
+};
+
+struct Ctx {
+    int lane, c, g, f0, h, node;
+    bool active;  // this lane's features exist (f0 < HD)
+    bool head0;   // first lane of its head
+    size_t off;   // node*HD + f0
+};
+
+template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int node) {
+    Ctx c;
+    c.lane = lane;
+    c.c = lane % G::LPE;
+    c.g = lane / G::LPE;
+    c.f0 = c.c * G::VEC;
+    c.active = c.f0 < a.HD;
+    c.h = c.active ? c.f0 / a.D : 0;
+    c.head0 = c.active && (c.f0 % a.D) == 0;
+    c.node = node;
+    c.off = (size_t)node * a.HD + c.f0;
+    return c;
+}
+
+template <class G> __device__ inline void load_row(const void* base, const Ctx& c, float (&x)[G::VEC]) {
+    if (c.active) {
+        Elem<typename G::T>::unpack(load_raw<typename G::T>(base, c.off), x);
+    } else {
+#pragma unroll
+        for (int i = 0; i < G::VEC; ++i) x[i] = 0.f;
+    }
+}
+
+template <class G> __device__ inline u32x4 gather_raw(const void* base, const Args& a, const Ctx& c, int j) {
+    u32x4 z = {0u, 0u, 0u, 0u};
+    if (j >= 0 && c.active) z = load_raw<typename G::T>(base, (size_t)j * a.HD + c.f0);
+    return z;
+}
+
+// ---------------------------------------------------------------------------------------------
+// online softmax accumulator shared by the three forward passes (edge softmax of Appendix A in its
+// streaming form: running maximum m, running sum l and running weighted value sum acc, in log2 units)
+// ---------------------------------------------------------------------------------------------
+template <class G, int U> struct SoftmaxAcc {
+    static constexpr int VEC = G::VEC;
+    float m, l, acc[VEC];
+
+    __device__ void reset() {
+        m = -INFINITY;
+        l = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    }
+    // s[u] = -inf for slots without an edge (their value registers hold zeros); s[0] must be finite
+    __device__ void update(const float (&s)[U], const u32x4 (&val)[U]) {
+        float mn = m;
+#pragma unroll
+        for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u]);
+        const float corr = fast_exp2(m - mn);
+        l *= corr;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] *= corr;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float p = fast_exp2(s[u] - mn);
+            float vf[VEC];
+            Elem<typename G::T>::unpack(val[u], vf);
+            l += p;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
+        }
+        m = mn;
+    }
+    __device__ void merge(float mo, float lo, const float (&ao)[VEC]) {
+        const float mn = fmaxf(m, mo);
+        const float c1 = (m == mn) ? 1.f : fast_exp2(m - mn);
+        const float c2 = (mo == mn) ? 1.f : fast_exp2(mo - mn);
+        l = l * c1 + lo * c2;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = acc[i] * c1 + ao[i] * c2;
+        m = mn;
+    }
+    __device__ void combine_slots() {
+#pragma unroll
+        for (int o = G::LPE; o < 64; o <<= 1) {
+            const float mo = __shfl_xor(m, o);
+            const float lo = __shfl_xor(l, o);
+            float ao[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) ao[i] = __shfl_xor(acc[i], o);
+            merge(mo, lo, ao);
+        }
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) const {
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, acc);
+        if (c.head0) {
+            a.part_s0[(size_t)item * a.H + c.h] = m;
+            a.part_s1[(size_t)item * a.H + c.h] = l;
+        }
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float ao[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, ao);
+        merge(a.part_s0[(size_t)chunk * a.H + c.h], a.part_s1[(size_t)chunk * a.H + c.h], ao);
+    }
+    // O = acc / l; statistics back in natural-log units
+    __device__ void finalize(const Args& a, const Ctx& c) const {
+        if (c.g != 0 || !c.active) return;
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = acc[i] * inv;
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.o) + c.off, o);
+        if (c.head0) {
+            a.o_max[(size_t)c.node * a.H + c.h] = m * kLn2;
+            a.o_sum[(size_t)c.node * a.H + c.h] = l;
+        }
+    }
+};
+
+// Row-side quantities every backward row pass starts from: delta = dO_i . O_i per head (equal to
+// sum_j p_ij dP_ij) and lse2 = log2 of the softmax denominator including the maximum.
+template <class G> struct RowBackwardBase {
+    static constexpr int VEC = G::VEC;
+    float g[VEC];  // dO_i
+    float delta, lse2;
+    __device__ void init_row(const Args& a, const Ctx& c) {
+        float o[VEC];
+        load_row<G>(a.d_out, c, g);
+        load_row<G>(a.out, c, o);
+        delta = head_sum<G::LPH>(dotv<VEC>(g, o), a.lph);
+        float mx = 0.f, sm = 1.f;
+        if (c.active) {
+            mx = a.row_max[(size_t)c.node * a.H + c.h];
+            sm = a.row_sum[(size_t)c.node * a.H + c.h];
+        }
+        lse2 = mx * kLog2e + fast_log2(sm);
+    }
+};
+
+// =============================================================================================
+// GT (dot-SDDMM, Sec. 5.1): s_ij = scale q_i.k_j
+// =============================================================================================
+template <class G, int U> struct GtFwd {
+    static constexpr int VEC = G::VEC;
+    float q[VEC];
+    SoftmaxAcc<G, U> sm;
+    u32x4 K[U], V[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, q);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) q[i] *= a.c_score;
+        sm.reset();
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        K[u] = gather_raw<G>(a.k, a, c, j);
+        V[u] = gather_raw<G>(a.v, a, c, j);
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[VEC];
+            Elem<typename G::T>::unpack(K[u], kf);
+            s[u] = head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph);
+            if (!FULL && j[u] < 0) s[u] = -INFINITY;
+        }
+        if (!FULL && j[0] < 0) return;
+        sm.update(s, V);
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
+};
+
+// dQ_i = scale sum_j dS_ij k_j with dS_ij = p_ij (dO_i.v_j - delta_i)   (Appendix B; fused chain of Sec. 4.3)
+template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
+    static constexpr int VEC = G::VEC;
+    float q[VEC], dq[VEC];
+    u32x4 K[U], V[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, q);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; }
+        this->init_row(a, c);
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        K[u] = gather_raw<G>(a.k, a, c, j);
+        V[u] = gather_raw<G>(a.v, a, c, j);
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[VEC], vf[VEC];
+            Elem<typename G::T>::unpack(K[u], kf);
+            Elem<typename G::T>::unpack(V[u], vf);
+            const float s = head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
+            const float ds = p * (dp - this->delta);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) dq[i] = fmaf(ds, kf[i], dq[i]);
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dq[i] = slot_sum<G::LPE>(dq[i]);
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g == 0 && c.active) store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dq);
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float t[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dq[i] += t[i];
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (c.g != 0 || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = a.scale * dq[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
+        if (c.head0) {
+            f32x2 st = {this->lse2, this->delta};
+            *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)c.node * a.H + c.h)) = st;
+        }
+    }
+};
+
+// Column pass over the CSC (transposed products of Appendix B): for source j and every edge i <- j,
+// dV_j += p_ij dO_i,  dK_j += scale dS_ij q_i, with p and dS recomputed from the row statistics.
+template <class G, int U> struct GtBwdCol {
+    static constexpr int VEC = G::VEC;
+    float k2[VEC], vv[VEC], dk[VEC], dv[VEC];
+    u32x4 Q[U], Gd[U];
+    f32x2 St[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.k, c, k2);
+        load_row<G>(a.v, c, vv);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { k2[i] *= a.c_score; dk[i] = 0.f; dv[i] = 0.f; }
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+        Q[u] = gather_raw<G>(a.x, a, c, i);
+        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
+        f32x2 z = {0.f, 0.f};
+        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x2*>(a.stats + 2 * ((size_t)i * a.H + c.h));
+        St[u] = z;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float qf[VEC], gf[VEC];
+            Elem<typename G::T>::unpack(Q[u], qf);
+            Elem<typename G::T>::unpack(Gd[u], gf);
+            const float s = head_sum<G::LPH>(dotv<VEC>(qf, k2), a.lph);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, vv), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
+            const float ds = p * (dp - St[u][1]);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                dv[i] = fmaf(p, gf[i], dv[i]);
+                dk[i] = fmaf(ds, qf[i], dk[i]);
+            }
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dv[i] = slot_sum<G::LPE>(dv[i]); }
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
+        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dv);
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float t0[VEC], t1[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
+        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] += t0[i]; dv[i] += t1[i]; }
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (c.g != 0 || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = a.scale * dk[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_k) + c.off, o);
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_v) + c.off, dv);
+    }
+};
+
+// =============================================================================================
+// GAT (add-SDDMM, Sec. 5.1): s_ij = LeakyReLU(el_i + er_j); el, er are per-node scalars per head
+// =============================================================================================
+__device__ inline float leaky(float z, float slope) { return z > 0.f ? z : slope * z; }
+
+template <class G, int U> struct GatFwd {
+    static constexpr int VEC = G::VEC;
+    float el2;
+    SoftmaxAcc<G, U> sm;
+    u32x4 V[U];
+    float Er[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        el2 = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        sm.reset();
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        Er[u] = (j >= 0 && c.active) ? a.node_b[(size_t)j * a.H + c.h] : 0.f;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            s[u] = leaky(el2 + Er[u], a.neg_slope);
+            if (!FULL && j[u] < 0) s[u] = -INFINITY;
+        }
+        if (!FULL && j[0] < 0) return;
+        sm.update(s, V);
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
+};
+
+// d_el_i = sum_j dS_ij LeakyReLU'(z_ij)
+template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
+    static constexpr int VEC = G::VEC;
+    float el2, d_el;
+    u32x4 V[U];
+    float Er[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        el2 = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        d_el = 0.f;
+        this->init_row(a, c);
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        Er[u] = (j >= 0 && c.active) ? a.node_b[(size_t)j * a.H + c.h] : 0.f;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[VEC];
+            Elem<typename G::T>::unpack(V[u], vf);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
+            const float z = el2 + Er[u];
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - this->lse2) : 0.f;
+            const float ds = p * (dp - this->delta);
+            d_el += ds * (z > 0.f ? 1.f : a.neg_slope);
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { d_el = slot_sum<G::LPE>(d_el); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g == 0 && c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_el;
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (c.active) d_el += a.part_s0[(size_t)chunk * a.H + c.h];
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (c.g != 0 || !c.head0) return;
+        const size_t nh = (size_t)c.node * a.H + c.h;
+        a.d_el[nh] = d_el;
+        f32x4 st = {el2, this->lse2, this->delta, 0.f};
+        *reinterpret_cast<f32x4*>(a.stats + 4 * nh) = st;
+    }
+};
+
+// dWh_j = sum_i p_ij dO_i + d_el_j a_l + d_er_j a_r ;  d_er_j = sum_i dS_ij LeakyReLU'(z_ij)
+template <class G, int U> struct GatBwdCol {
+    static constexpr int VEC = G::VEC;
+    float wh[VEC], dwh[VEC];
+    float er2, d_er;
+    u32x4 Gd[U];
+    f32x4 St[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, wh);
+        er2 = c.active ? a.node_b[(size_t)c.node * a.H + c.h] : 0.f;
+        d_er = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dwh[i] = 0.f;
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x4*>(a.stats + 4 * ((size_t)i * a.H + c.h));
+        St[u] = z;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float gf[VEC];
+            Elem<typename G::T>::unpack(Gd[u], gf);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, wh), a.lph);
+            const float z = St[u][0] + er2;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - St[u][1]) : 0.f;
+            const float ds = p * (dp - St[u][2]);
+            d_er += ds * (z > 0.f ? 1.f : a.neg_slope);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) dwh[i] = fmaf(p, gf[i], dwh[i]);
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+        d_er = slot_sum<G::LPE>(d_er);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dwh[i] = slot_sum<G::LPE>(dwh[i]);
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dwh);
+        if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_er;
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float t[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dwh[i] += t[i];
+        d_er += a.part_s0[(size_t)chunk * a.H + c.h];
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (c.g != 0 || !c.active) return;
+        const size_t nh = (size_t)c.node * a.H + c.h;
+        const float del = a.d_el[nh];
+        float al[VEC], ar[VEC], o[VEC];
+        load_f32<VEC>(a.a_l + c.f0, al);
+        load_f32<VEC>(a.a_r + c.f0, ar);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = dwh[i] + del * al[i] + d_er * ar[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
+        if (c.head0) a.d_er[nh] = d_er;
+    }
+};
+
+// =============================================================================================
+// AGNN (Sec. 5.1): s_ij = beta * cos(h_i, h_j); aggregated value is the raw feature row
+// =============================================================================================
+template <class G, int U> struct AgnnFwd {
+    static constexpr int VEC = G::VEC;
+    float x2[VEC];
+    SoftmaxAcc<G, U> sm;
+    u32x4 V[U];
+    float Rn[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, x2);
+        const float rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
+        sm.reset();
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        Rn[u] = (j >= 0 && c.active) ? a.node_a[(size_t)j * a.H + c.h] : 0.f;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[VEC];
+            Elem<typename G::T>::unpack(V[u], vf);
+            s[u] = head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * Rn[u];
+            if (!FULL && j[u] < 0) s[u] = -INFINITY;
+        }
+        if (!FULL && j[0] < 0) return;
+        sm.update(s, V);
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
+};
+
+// row side: g_i = beta sum_j dS_ij xhat_j ;  dbeta_i = sum_j dS_ij cos_ij
+template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
+    static constexpr int VEC = G::VEC;
+    float xh[VEC], ga[VEC];
+    float rn, dbeta;
+    u32x4 V[U];
+    float Rn[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, xh);
+        rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        dbeta = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; }
+        this->init_row(a, c);
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        Rn[u] = (j >= 0 && c.active) ? a.node_a[(size_t)j * a.H + c.h] : 0.f;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[VEC];
+            Elem<typename G::T>::unpack(V[u], vf);
+            const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * Rn[u];
+            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - this->lse2) : 0.f;
+            const float ds = p * (dp - this->delta);
+            dbeta = fmaf(ds, cs, dbeta);
+            const float w = ds * Rn[u];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, vf[i], ga[i]);
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+        dbeta = slot_sum<G::LPE>(dbeta);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ga[i] = slot_sum<G::LPE>(ga[i]);
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, ga);
+        if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = dbeta;
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float t[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ga[i] += t[i];
+        dbeta += a.part_s0[(size_t)chunk * a.H + c.h];
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (c.g != 0 || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = a.scale * ga[i];
+        store_f32<VEC>(a.g_row + c.off, o);
+        if (c.head0) {
+            const size_t nh = (size_t)c.node * a.H + c.h;
+            a.dbeta_row[nh] = dbeta;
+            f32x4 st = {rn, this->lse2, this->delta, 0.f};
+            *reinterpret_cast<f32x4*>(a.stats + 4 * nh) = st;
+        }
+    }
+};
+
+// column side: value term sum_i p_ij dO_i, key term beta sum_i dS_ij xhat_i, then the derivative of the
+// normalisation x -> x / max(|x|, eps) applied to the summed row+column gradient of xhat_j
+template <class G, int U> struct AgnnBwdCol {
+    static constexpr int VEC = G::VEC;
+    float hj[VEC], xh[VEC], val[VEC], ga[VEC];
+    float rn;
+    u32x4 Xi[U], Gd[U];
+    f32x4 St[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, hj);
+        rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+        Xi[u] = gather_raw<G>(a.x, a, c, i);
+        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x4*>(a.stats + 4 * ((size_t)i * a.H + c.h));
+        St[u] = z;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float xf[VEC], gf[VEC];
+            Elem<typename G::T>::unpack(Xi[u], xf);
+            Elem<typename G::T>::unpack(Gd[u], gf);
+            const float cs = head_sum<G::LPH>(dotv<VEC>(xf, xh), a.lph) * St[u][0];
+            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, hj), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - St[u][1]) : 0.f;
+            const float ds = p * (dp - St[u][2]);
+            const float w = ds * St[u][0];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                val[i] = fmaf(p, gf[i], val[i]);
+                ga[i] = fmaf(w, xf[i], ga[i]);
+            }
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { val[i] = slot_sum<G::LPE>(val[i]); ga[i] = slot_sum<G::LPE>(ga[i]); }
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, val);
+        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, ga);
+    }
+    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
+        if (!c.active) return;
+        float t0[VEC], t1[VEC];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
+        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { val[i] += t0[i]; ga[i] += t1[i]; }
+    }
+    // all lanes of the wave must call this (it reduces over the head's lanes)
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        float gt[VEC];
+        if (c.active) {
+            load_f32<VEC>(a.g_row + c.off, gt);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) gt[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) gt[i] = fmaf(a.scale, ga[i], gt[i]);
+        const float proj = head_sum<G::LPH>(dotv<VEC>(gt, xh), a.lph);
+        const float nrm2 = head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph);
+        const bool clamped = !(sqrtf(nrm2) > a.eps);
+        if (c.g != 0 || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = (clamped ? gt[i] * rn : rn * (gt[i] - proj * xh[i])) + val[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
+    }
+};
+
+// =============================================================================================
+// kernels
+// =============================================================================================
+constexpr int kWavesPerBlock = 4;
+
+template <class G, int U>
+__device__ inline void load_indices(const Args& a, const Ctx& c, int base, int ee, int (&j)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int e = base + u * G::EPW + c.g;
+        j[u] = e < ee ? a.idx[e] : -1;
+    }
+}
+
+// One wavefront per work item; PARTIAL: items are chunks of super rows and results go to the workspace.
+template <class G, template <class, int> class PassT, int U, bool PARTIAL>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int item = blockIdx.x * kWavesPerBlock + wave;
+    if (item >= a.n_items) return;
+    int node, eb, ee;
+    if (PARTIAL) {
+        node = a.chunks[3 * item];
+        eb = a.chunks[3 * item + 1];
+        ee = a.chunks[3 * item + 2];
+    } else {
+        node = a.order[a.first + item];
+        eb = a.ptr[node];
+        ee = a.ptr[node + 1];
+    }
+    const Ctx c = make_ctx<G>(a, lane, node);
+    PassT<G, U> p;
+    p.init(a, c);
+    constexpr int STEP = G::EPW * U;
+    int j[U], jn[U];
+    load_indices<G, U>(a, c, eb, ee, j);
+    for (int base = eb; base < ee; base += STEP) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u]);
+        load_indices<G, U>(a, c, base + STEP, ee, jn);
+        if (base + STEP <= ee) p.template consume<true>(a, c, j);
+        else p.template consume<false>(a, c, j);
+#pragma unroll
+        for (int u = 0; u < U; ++u) j[u] = jn[u];
+    }
+    p.combine_slots(a, c);
+    if (PARTIAL) p.store_partial(a, c, item);
+    else p.finalize(a, c);
+}
+
+// One wavefront per super row / column: sums (or, for the forward pass, softmax-merges) the partial
+// results of its chunks in chunk order and finishes the row exactly as the direct pass would.
+template <class G, template <class, int> class PassT, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int s = blockIdx.x * kWavesPerBlock + wave;
+    if (s >= a.n_items) return;
+    const int node = a.order[s];
+    const int c0 = a.chunk_ptr[s], c1 = a.chunk_ptr[s + 1];
+    const Ctx c = make_ctx<G>(a, lane, node);
+    PassT<G, U> p;
+    p.init(a, c);
+    for (int ch = c0; ch < c1; ++ch) p.add_partial(a, c, ch);
+    p.finalize(a, c);
+}
+
+// Per-node score terms: GAT el = a_l.Wh, er = a_r.Wh (times log2 e); AGNN 1 / max(|h|, eps).
+// One edge slot (LPE lanes) per node.
+template <class G, bool IS_GAT>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_node_terms(const Args a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane / G::LPE;
+    const int node = (blockIdx.x * kWavesPerBlock + wave) * G::EPW + g;
+    const bool live = node < a.n_nodes;
+    const Ctx c = make_ctx<G>(a, lane, live ? node : 0);
+    float x[G::VEC];
+    load_row<G>(a.x, c, x);
+    if (IS_GAT) {
+        float al[G::VEC], ar[G::VEC];
+        if (c.active) {
+            load_f32<G::VEC>(a.a_l + c.f0, al);
+            load_f32<G::VEC>(a.a_r + c.f0, ar);
+        } else {
+#pragma unroll
+            for (int i = 0; i < G::VEC; ++i) { al[i] = 0.f; ar[i] = 0.f; }
+        }
+        const float el = head_sum<G::LPH>(dotv<G::VEC>(x, al), a.lph);
+        const float er = head_sum<G::LPH>(dotv<G::VEC>(x, ar), a.lph);
+        if (live && c.head0) {
+            a.node_a[(size_t)node * a.H + c.h] = el * kLog2e;
+            a.node_b[(size_t)node * a.H + c.h] = er * kLog2e;
+        }
+    } else {
+        const float n2 = head_sum<G::LPH>(dotv<G::VEC>(x, x), a.lph);
+        if (live && c.head0) a.node_a[(size_t)node * a.H + c.h] = 1.f / fmaxf(sqrtf(n2), a.eps);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// small deterministic reductions (two stages, fixed summation order)
+// ---------------------------------------------------------------------------------------------
+constexpr int kReduceBlocks = 256;
+
+// stage 1 of da_l[h,d] = sum_v d_el[v,h] Wh[v,h,d] and da_r likewise: block b takes nodes b, b+B, ...
+template <typename T>
+__global__ __launch_bounds__(256) void k_gat_param_partial(const Args a, float* __restrict__ partial) {
+    for (int f = threadIdx.x; f < a.HD; f += blockDim.x) {
+        const int h = f / a.D;
+        float sl = 0.f, sr = 0.f;
+        for (int v = blockIdx.x; v < a.n_nodes; v += gridDim.x) {
+            float x;
+            if constexpr (sizeof(T) == 2) {
+                x = __builtin_bit_cast(float, (uint32_t)static_cast<const uint16_t*>(a.x)[(size_t)v * a.HD + f] << 16);
+            } else {
+                x = static_cast<const float*>(a.x)[(size_t)v * a.HD + f];
+            }
+            sl = fmaf(a.d_el[(size_t)v * a.H + h], x, sl);
+            sr = fmaf(a.d_er[(size_t)v * a.H + h], x, sr);
+        }
+        partial[((size_t)blockIdx.x * 2 + 0) * a.HD + f] = sl;
+        partial[((size_t)blockIdx.x * 2 + 1) * a.HD + f] = sr;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
+                                                         float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
+    for (int f = threadIdx.x; f < HD; f += blockDim.x) {
+        float sl = 0.f, sr = 0.f;
+        for (int b = 0; b < nblocks; ++b) {
+            sl += partial[((size_t)b * 2 + 0) * HD + f];
+            sr += partial[((size_t)b * 2 + 1) * HD + f];
+        }
+        d_a_l[f] = sl;
+        d_a_r[f] = sr;
+    }
+}
+
+__device__ inline float block_sum_256(float v) {
+    __shared__ float red[256];
+    red[threadIdx.x] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(256) void k_sum_partial(const float* __restrict__ in, int64_t n, float* __restrict__ partial) {
+    float s = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) s += in[i];
+    const float t = block_sum_256(s);
+    if (threadIdx.x == 0) partial[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, float* __restrict__ out) {
+    const float t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.f);
+    if (threadIdx.x == 0) *out = t;
+}
+
+}  // namespace dfgnn

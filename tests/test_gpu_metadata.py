@@ -1,0 +1,50 @@
+"""Bit-exact checks of the GPU-built scheduling metadata against the integer oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2411_16127_amd as dfgnn
+from dfgnn_synth import tiny_graph, make_workload
+from dfgnn_synth.workloads import make_graph
+
+pytestmark = pytest.mark.gpu
+
+
+DEFAULT_T, DEFAULT_C = 1024, 512  # library defaults documented in include/dfgnn.h
+
+
+def check_metadata(graph, T, C):
+    g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(T, C))
+    T, C = T or DEFAULT_T, C or DEFAULT_C
+    csc = oracle.csc_transpose(graph.indptr, graph.indices)
+    rows = oracle.schedule(graph.indptr, T, C)
+    cols = oracle.schedule(csc["t_indptr"], T, C)
+    get = lambda name: g.query(name).cpu().numpy() if not name.startswith("n_") else g.query(name)
+    np.testing.assert_array_equal(get("t_indptr"), csc["t_indptr"])
+    np.testing.assert_array_equal(get("t_eid"), csc["t_eid"])
+    np.testing.assert_array_equal(get("t_indices"), csc["t_indices"])
+    assert get("n_super_rows") == rows["n_super"] and get("n_super_cols") == cols["n_super"]
+    np.testing.assert_array_equal(get("row_order"), rows["order"])
+    np.testing.assert_array_equal(get("col_order"), cols["order"])
+    if rows["n_super"]:
+        np.testing.assert_array_equal(get("row_chunk_ptr"), rows["chunk_ptr"])
+        np.testing.assert_array_equal(get("row_chunks").reshape(-1, 3), rows["chunks"])
+    else:
+        assert get("row_chunks").size == 0
+    if cols["n_super"]:
+        np.testing.assert_array_equal(get("col_chunk_ptr"), cols["chunk_ptr"])
+        np.testing.assert_array_equal(get("col_chunks").reshape(-1, 3), cols["chunks"])
+    g.close()
+
+
+@pytest.mark.parametrize("kind", ["random", "hub", "dups", "unsorted", "empty", "chain", "selfloop"])
+@pytest.mark.parametrize("T,C", [(4, 3), (8, 8), (1024, 512)])
+def test_tiny_graphs(kind, T, C):
+    check_metadata(tiny_graph(kind, seed=5, n=40), T, C)
+
+
+@pytest.mark.parametrize("name,shrink,T,C", [("cfg1", 1, 32, 16), ("cfg2", 1, 16, 8), ("cfg3", 1, 256, 100),
+                                             ("cfg3", 1, 0, 0), ("cfg4", 4, 1024, 512), ("cfg5", 64, 64, 64)])
+def test_workload_graphs(name, shrink, T, C):
+    # spans many sort tiles (4096 keys) with a ragged tail and several radix passes
+    check_metadata(make_graph(make_workload(name, shrink=shrink)), T, C)

@@ -1,0 +1,135 @@
+"""Element-by-element parity of the HIP path (through the C ABI) with the CPU oracle."""
+import numpy as np
+import pytest
+
+import paper_2411_16127_amd as dfgnn
+from dfgnn_synth import tiny_graph, complete_graph, make_workload, make_features
+from dfgnn_synth.workloads import make_graph, Workload
+from gpu_harness import run_gpu, run_oracle, compare_all
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workload(model, H, D, dtype="f32"):
+    scale = {"gt": 1.0 / np.sqrt(D), "gat": 1.0, "agnn": 1.3}[model]
+    return Workload("tiny", 90, model, H, D, dtype, float(scale))
+
+
+# (H, D) pairs: the compile-time geometries of the benchmark shapes and several run-time ones,
+# including a head count that leaves padded lanes (H=3)
+SHAPES_F32 = [(1, 64), (8, 16), (8, 8), (2, 4), (3, 8), (1, 16), (4, 32), (1, 256), (2, 128)]
+SHAPES_BF16 = [(8, 16), (1, 8), (3, 16), (2, 64), (1, 512)]
+
+
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
+@pytest.mark.parametrize("H,D", SHAPES_F32)
+@pytest.mark.parametrize("kind", ["random", "hub", "dups", "unsorted", "empty", "selfloop"])
+def test_tiny_graphs_f32(model, H, D, kind):
+    graph = tiny_graph(kind, seed=2, n=70)
+    w = small_workload(model, H, D)
+    feats = make_features(w, graph.n)
+    # threshold 8 / chunk 5: hub rows and columns go through the chunk + merge path with ragged chunks
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
+@pytest.mark.parametrize("H,D", SHAPES_BF16)
+def test_tiny_graphs_bf16(model, H, D):
+    graph = tiny_graph("hub", seed=3, n=70)
+    w = small_workload(model, H, D, "bf16")
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
+def test_complete_graph(model):
+    graph = complete_graph(67)  # every row has 67 neighbours: several unrolled rounds plus a ragged tail
+    w = small_workload(model, 2, 16)
+    feats = make_features(w, graph.n)
+    for sched in (None, dfgnn.SchedParams(32, 16)):
+        res, g = run_gpu(graph, w, feats, sched)
+        compare_all(res, run_oracle(graph, w, feats), w)
+        g.close()
+
+
+def test_split_rows_match_unsplit_rows():
+    """The chunk + merge path and the one-wave-per-row path give the same numbers (to rounding)."""
+    graph = make_graph(make_workload("cfg1"))
+    w = make_workload("cfg1")
+    feats = make_features(w, graph.n)
+    a, g1 = run_gpu(graph, w, feats, dfgnn.SchedParams(1 << 30, 1 << 30))
+    b, g2 = run_gpu(graph, w, feats, dfgnn.SchedParams(16, 8))
+    assert g1.query("n_super_rows") == 0 and g2.query("n_super_rows") > 10
+    for key in a:
+        np.testing.assert_allclose(a[key], b[key], rtol=2e-5, atol=2e-6)
+    g1.close(); g2.close()
+
+
+def test_large_scores_are_stable():
+    graph = tiny_graph("hub", seed=4, n=70)
+    w = small_workload("gt", 1, 64)
+    feats = make_features(w, graph.n)
+    feats["q"] = feats["q"] * np.float32(40.0)  # scores of order +-500
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+def test_results_are_bitwise_reproducible():
+    graph = make_graph(make_workload("cfg3", shrink=16))
+    w = make_workload("cfg3", shrink=16)
+    feats = make_features(w, graph.n)
+    a, g = run_gpu(graph, w, feats, dfgnn.SchedParams(64, 32))
+    b, _ = run_gpu(graph, w, feats, g=g)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    g.close()
+
+
+# ------------------------------------------------------------------ the five workloads, reduced in size
+@pytest.mark.parametrize("name,shrink,T,C", [("cfg1", 1, 0, 0), ("cfg1", 1, 64, 32), ("cfg2", 8, 0, 0),
+                                             ("cfg3", 8, 0, 0), ("cfg3", 8, 128, 64), ("cfg4", 16, 0, 0),
+                                             ("cfg5", 256, 0, 0), ("cfg5", 256, 96, 40)])
+def test_workloads_reduced(name, shrink, T, C):
+    w = make_workload(name, shrink=shrink)
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(T, C) if T else None)
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4"])
+def test_workloads_full_size(name):
+    w = make_workload(name)
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats)  # default scheduling parameters, as the benchmark runs it
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+def test_cfg5_full_size_sampled():
+    """123M edges: the oracle evaluates sampled nodes one by one (rows for O / dQ, and every row that a
+    sampled node feeds for its dK / dV), the GPU runs the whole graph."""
+    w = make_workload("cfg5")
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats)
+    deg = graph.degrees()
+    rng = np.random.default_rng(77)
+    sample = np.unique(np.concatenate([rng.choice(graph.n, 48, replace=False), np.argsort(deg)[-3:],
+                                       np.argsort(deg)[:2]]))
+    out_deg = np.bincount(graph.indices, minlength=graph.n)
+    light = sample[out_deg[sample] < 400]  # columns whose feeding rows the oracle can afford
+    rows_of_edges = graph.rows_of_edges()
+    feed = np.unique(rows_of_edges[np.isin(graph.indices, light)])
+    ref = run_oracle(graph, w, feats, rows=sample, backward_rows=np.union1d(sample, feed))
+    compare_all(res, ref, w, rows=sample, keys=["out", "row_max", "row_sum", "d_x"])
+    compare_all(res, ref, w, rows=light, keys=["d_k", "d_v"])
+    g.close()
