@@ -57,7 +57,7 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
 // workspace layout (float offsets turned into pointers)
 // ---------------------------------------------------------------------------------------------
 struct Workspace {
-    size_t node_a, node_b, stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, reduce, total;
+    size_t node_a, node_b, stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, total;
 };
 
 static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward) {
@@ -76,6 +76,7 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
     if (backward) {
         W.stats = take(N * H * (L->model == DFGNN_GT ? 2 : 4));
         W.part_v1 = take(chunks * HD);
+        W.part_s2 = take(chunks * H);
         W.d_el = take(gat ? N * H : 0);
         W.d_er = take(gat ? N * H : 0);
         W.g_row = take(agnn ? N * HD : 0);
@@ -96,6 +97,7 @@ static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward)
     if (backward) {
         a.stats = (float*)(b + W.stats);
         a.part_v1 = (float*)(b + W.part_v1);
+        a.part_s2 = (float*)(b + W.part_s2);
         a.d_el = (float*)(b + W.d_el);
         a.d_er = (float*)(b + W.d_er);
         a.g_row = (float*)(b + W.g_row);

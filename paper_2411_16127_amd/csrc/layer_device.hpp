@@ -161,6 +161,7 @@ struct Args {
     float* part_v1;    // [chunks, HD]
     float* part_s0;    // [chunks, H]
     float* part_s1;    // [chunks, H]
+    float* part_s2;    // [chunks, H]
 };
 
 // Lane geometry: LPE lanes per neighbour row, LPH lanes per head (0 = run-time), element type T.
@@ -288,17 +289,26 @@ template <class G, int U> struct SoftmaxAcc {
     }
 };
 
-// Row-side quantities every backward row pass starts from: delta = dO_i . O_i per head (equal to
-// sum_j p_ij dP_ij) and lse2 = log2 of the softmax denominator including the maximum.
+// Row-side quantities every backward row pass starts from: lse2 = log2 of the softmax denominator
+// including the maximum, and delta_i = sum_j p_ij dP_ij per head.
+//   fp32 tensors: delta_i = dO_i . O_i (the same number, read off the forward output);
+//   bf16 tensors: O was rounded to bf16, which would put a 2^-9 relative error into delta, so the
+//   pass accumulates dsum = sum_j p_ij dP_ij itself and uses  sum_j p (dP - delta) y_j
+//   = sum_j p dP y_j - delta sum_j p y_j  to finish in one sweep (kExact).
 template <class G> struct RowBackwardBase {
     static constexpr int VEC = G::VEC;
+    static constexpr bool kExact = sizeof(typename G::T) == 2;
     float g[VEC];  // dO_i
-    float delta, lse2;
+    float delta, lse2, dsum;
     __device__ void init_row(const Args& a, const Ctx& c) {
-        float o[VEC];
         load_row<G>(a.d_out, c, g);
-        load_row<G>(a.out, c, o);
-        delta = head_sum<G::LPH>(dotv<VEC>(g, o), a.lph);
+        dsum = 0.f;
+        delta = 0.f;
+        if constexpr (!kExact) {
+            float o[VEC];
+            load_row<G>(a.out, c, o);
+            delta = head_sum<G::LPH>(dotv<VEC>(g, o), a.lph);
+        }
         float mx = 0.f, sm = 1.f;
         if (c.active) {
             mx = a.row_max[(size_t)c.node * a.H + c.h];
@@ -347,12 +357,13 @@ template <class G, int U> struct GtFwd {
 // dQ_i = scale sum_j dS_ij k_j with dS_ij = p_ij (dO_i.v_j - delta_i)   (Appendix B; fused chain of Sec. 4.3)
 template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
-    float q[VEC], dq[VEC];
+    static constexpr bool kExact = RowBackwardBase<G>::kExact;
+    float q[VEC], dq[VEC], pk[VEC];  // pk = sum_j p k_j (kExact only)
     u32x4 K[U], V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, q);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; }
+        for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; pk[i] = 0.f; }
         this->init_row(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
@@ -368,17 +379,34 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
             const float s = head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph);
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
-            const float ds = p * (dp - this->delta);
+            if constexpr (kExact) {
+                const float t = p * dp;
+                this->dsum += t;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) dq[i] = fmaf(ds, kf[i], dq[i]);
+                for (int i = 0; i < VEC; ++i) { dq[i] = fmaf(t, kf[i], dq[i]); pk[i] = fmaf(p, kf[i], pk[i]); }
+            } else {
+                const float ds = p * (dp - this->delta);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) dq[i] = fmaf(ds, kf[i], dq[i]);
+            }
         }
     }
     __device__ void combine_slots(const Args&, const Ctx&) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dq[i] = slot_sum<G::LPE>(dq[i]);
+        if constexpr (kExact) {
+            this->dsum = slot_sum<G::LPE>(this->dsum);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) pk[i] = slot_sum<G::LPE>(pk[i]);
+        }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g == 0 && c.active) store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dq);
+        if (c.g != 0 || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dq);
+        if constexpr (kExact) {
+            store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, pk);
+            if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
+        }
     }
     __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
         if (!c.active) return;
@@ -386,9 +414,20 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dq[i] += t[i];
+        if constexpr (kExact) {
+            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) pk[i] += t[i];
+            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+        }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (c.g != 0 || !c.active) return;
+        if constexpr (kExact) {
+            this->delta = this->dsum;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) dq[i] -= this->delta * pk[i];
+        }
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = a.scale * dq[i];
@@ -502,12 +541,14 @@ template <class G, int U> struct GatFwd {
 // d_el_i = sum_j dS_ij LeakyReLU'(z_ij)
 template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
-    float el2, d_el;
+    static constexpr bool kExact = RowBackwardBase<G>::kExact;
+    float el2, d_el, pl;  // pl = sum_j p LeakyReLU'(z) (kExact only)
     u32x4 V[U];
     float Er[U];
     __device__ void init(const Args& a, const Ctx& c) {
         el2 = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
         d_el = 0.f;
+        pl = 0.f;
         this->init_row(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
@@ -522,19 +563,46 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float z = el2 + Er[u];
             const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - this->lse2) : 0.f;
-            const float ds = p * (dp - this->delta);
-            d_el += ds * (z > 0.f ? 1.f : a.neg_slope);
+            const float slope = z > 0.f ? 1.f : a.neg_slope;
+            if constexpr (kExact) {
+                const float t = p * dp;
+                this->dsum += t;
+                d_el = fmaf(t, slope, d_el);
+                pl = fmaf(p, slope, pl);
+            } else {
+                d_el = fmaf(p * (dp - this->delta), slope, d_el);
+            }
         }
     }
-    __device__ void combine_slots(const Args&, const Ctx&) { d_el = slot_sum<G::LPE>(d_el); }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+        d_el = slot_sum<G::LPE>(d_el);
+        if constexpr (kExact) {
+            pl = slot_sum<G::LPE>(pl);
+            this->dsum = slot_sum<G::LPE>(this->dsum);
+        }
+    }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g == 0 && c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_el;
+        if (c.g != 0 || !c.head0) return;
+        a.part_s0[(size_t)item * a.H + c.h] = d_el;
+        if constexpr (kExact) {
+            a.part_s1[(size_t)item * a.H + c.h] = pl;
+            a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
+        }
     }
     __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (c.active) d_el += a.part_s0[(size_t)chunk * a.H + c.h];
+        if (!c.active) return;
+        d_el += a.part_s0[(size_t)chunk * a.H + c.h];
+        if constexpr (kExact) {
+            pl += a.part_s1[(size_t)chunk * a.H + c.h];
+            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+        }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (c.g != 0 || !c.head0) return;
+        if constexpr (kExact) {
+            this->delta = this->dsum;
+            d_el -= this->delta * pl;
+        }
         const size_t nh = (size_t)c.node * a.H + c.h;
         a.d_el[nh] = d_el;
         f32x4 st = {el2, this->lse2, this->delta, 0.f};
@@ -649,16 +717,18 @@ template <class G, int U> struct AgnnFwd {
 // row side: g_i = beta sum_j dS_ij xhat_j ;  dbeta_i = sum_j dS_ij cos_ij
 template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
-    float xh[VEC], ga[VEC];
-    float rn, dbeta;
+    static constexpr bool kExact = RowBackwardBase<G>::kExact;
+    float xh[VEC], ga[VEC], px[VEC];  // px = sum_j p xhat_j (kExact only)
+    float rn, dbeta, pc;              // pc = sum_j p cos_ij (kExact only)
     u32x4 V[U];
     float Rn[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, xh);
         rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
         dbeta = 0.f;
+        pc = 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; }
+        for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; px[i] = 0.f; }
         this->init_row(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
@@ -673,22 +743,45 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * Rn[u];
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - this->lse2) : 0.f;
-            const float ds = p * (dp - this->delta);
-            dbeta = fmaf(ds, cs, dbeta);
-            const float w = ds * Rn[u];
+            if constexpr (kExact) {
+                const float t = p * dp;
+                this->dsum += t;
+                dbeta = fmaf(t, cs, dbeta);
+                pc = fmaf(p, cs, pc);
+                const float w1 = t * Rn[u], w2 = p * Rn[u];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, vf[i], ga[i]);
+                for (int i = 0; i < VEC; ++i) { ga[i] = fmaf(w1, vf[i], ga[i]); px[i] = fmaf(w2, vf[i], px[i]); }
+            } else {
+                const float ds = p * (dp - this->delta);
+                dbeta = fmaf(ds, cs, dbeta);
+                const float w = ds * Rn[u];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, vf[i], ga[i]);
+            }
         }
     }
     __device__ void combine_slots(const Args&, const Ctx&) {
         dbeta = slot_sum<G::LPE>(dbeta);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) ga[i] = slot_sum<G::LPE>(ga[i]);
+        if constexpr (kExact) {
+            pc = slot_sum<G::LPE>(pc);
+            this->dsum = slot_sum<G::LPE>(this->dsum);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) px[i] = slot_sum<G::LPE>(px[i]);
+        }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
         if (c.g != 0 || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, ga);
-        if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = dbeta;
+        if constexpr (kExact) store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, px);
+        if (c.head0) {
+            a.part_s0[(size_t)item * a.H + c.h] = dbeta;
+            if constexpr (kExact) {
+                a.part_s1[(size_t)item * a.H + c.h] = pc;
+                a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
+            }
+        }
     }
     __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
         if (!c.active) return;
@@ -697,9 +790,22 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) ga[i] += t[i];
         dbeta += a.part_s0[(size_t)chunk * a.H + c.h];
+        if constexpr (kExact) {
+            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) px[i] += t[i];
+            pc += a.part_s1[(size_t)chunk * a.H + c.h];
+            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+        }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (c.g != 0 || !c.active) return;
+        if constexpr (kExact) {
+            this->delta = this->dsum;
+            dbeta -= this->delta * pc;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) ga[i] -= this->delta * px[i];
+        }
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = a.scale * ga[i];

@@ -67,24 +67,38 @@ def run_oracle(graph, w, feats, rows=None, backward_rows=None):
     return ref
 
 
-def assert_close(name, got, ref, dtype, rows=None):
+def _rms(ref):
+    fin = ref[np.isfinite(ref)]
+    return float(np.sqrt(np.mean(np.square(fin)))) if fin.size else 0.0
+
+
+def tolerance(name, ref, dtype):
+    """(rtol, atol, floor): bound = atol + rtol * max(|ref|, floor).
+
+    Node tensors and statistics of fp32 layers: the stated 1e-4 / 1e-5, element by element.
+    Parameter gradients (d_a_l, d_a_r, d_scale) are sums of signed terms over all nodes and edges; their
+    fp32 error scales with the size of the terms, not of the (partly cancelled) result, so the relative
+    part is taken against the rms of the gradient vector when an element is smaller than that.
+    bf16 layers: 2e-2 relative plus 2e-2 * rms(ref) absolute.
+    """
+    if dtype == "bf16":
+        return BF16_RTOL, BF16_RTOL * _rms(ref), 0.0
+    if name in ("d_a_l", "d_a_r", "d_scale"):
+        return F32_RTOL, F32_ATOL, _rms(ref)
+    return F32_RTOL, F32_ATOL, 0.0
+
+
+def assert_close(name, got, ref, dtype, rows=None, tol=None):
     got = np.asarray(got, dtype=np.float64).reshape(ref.shape)
     if rows is not None:
         got, ref = got[rows], ref[rows]
-    stat = name in ("row_max", "row_sum", "d_a_l", "d_a_r", "d_scale")
-    if dtype == "bf16" and not stat:
-        rtol = BF16_RTOL
-        atol = BF16_RTOL * float(np.sqrt(np.mean(np.square(ref[np.isfinite(ref)])))) if ref.size else 0.0
-    else:
-        rtol, atol = F32_RTOL, F32_ATOL
-        if dtype == "bf16":  # statistics / parameter gradients of a bf16 layer are fp32 but see rounded inputs
-            rtol, atol = BF16_RTOL, BF16_RTOL * float(np.sqrt(np.mean(np.square(ref[np.isfinite(ref)])))) if ref.size else 0.0
+    rtol, atol, floor = tol or tolerance(name, ref, dtype)
     inf = np.isinf(ref)
     assert np.array_equal(inf, np.isinf(got)), f"{name}: infinities differ"
     assert np.array_equal(np.sign(ref[inf]), np.sign(got[inf])), f"{name}: infinity signs differ"
     assert np.all(np.isfinite(got[~inf])), f"{name}: non-finite values"
     err = np.abs(got[~inf] - ref[~inf])
-    bound = atol + rtol * np.abs(ref[~inf])
+    bound = atol + rtol * np.maximum(np.abs(ref[~inf]), floor)
     bad = err > bound
     if np.any(bad):
         worst = np.argmax(err - bound)
@@ -92,8 +106,8 @@ def assert_close(name, got, ref, dtype, rows=None):
                              f"ref={ref[~inf][worst]:.6e} got={got[~inf][worst]:.6e} bound={bound[worst]:.3e}")
 
 
-def compare_all(res, ref, w, rows=None, keys=None):
+def compare_all(res, ref, w, rows=None, keys=None, tol=None):
     names = keys or [k for k in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v", "d_a_l", "d_a_r", "d_scale") if k in ref]
     for name in names:
         per_node = name in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v")
-        assert_close(name, res[name], ref[name], w.dtype, rows if per_node else None)
+        assert_close(name, res[name], ref[name], w.dtype, rows if per_node else None, tol)

@@ -75,7 +75,11 @@ def test_large_scores_are_stable():
     feats = make_features(w, graph.n)
     feats["q"] = feats["q"] * np.float32(40.0)  # scores of order +-500
     res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
-    compare_all(res, run_oracle(graph, w, feats), w)
+    for key, val in res.items():
+        assert np.all(np.isfinite(val) | np.isneginf(val)), key
+    # a score of magnitude 500 carries an fp32 rounding error of ~3e-5 in the exponent, so the attention
+    # weights are only good to ~1e-4 relative; gradients (which cancel) are checked ten times looser
+    compare_all(res, run_oracle(graph, w, feats), w, tol=(1e-3, 1e-4, 0.0))
     g.close()
 
 
