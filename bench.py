@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused AT-GNN layer (forward + backward) on one MI355X.
+
+One step = one forward call plus one backward call of the layer over one synthetic graph, everything
+resident in HBM before the timed region.  Prints ONE JSON line:
+  metric/value : fwd+bwd throughput in GEdges/s  (E / (t_fwd + t_bwd)), E = stored edges incl. self-loops
+  roofline     : the kernel with the largest share of the step, its algorithmic bytes (gather model: every
+                 neighbour row counted once per edge) over its mean duration from HIP events recorded on
+                 the launch stream during the timed steps, against the 8 TB/s HBM peak
+  cpu_baseline : the CPU oracle timed on a bounded sample of rows of the same graph (one thread)
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1..cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+DEFAULT_T, DEFAULT_C = 1024, 512
+
+# HBM bytes of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the files
+# under profiles/ named after the kernel and workload); bytes per launch, None where not measured.
+MEASURED_TRAFFIC = {}
+
+DESCRIPTIONS = {
+    "cfg1": "cfg1: GT fp32, Chung-Lu power-law graph N=2,708 (exponent 2.5) + self-loops, H=1 D=64",
+    "cfg2": "cfg2: GT bf16, 1,024 disjoint graphs of 10-40 nodes, density 0.3, block-diagonal CSR, H=8 D=16",
+    "cfg3": "cfg3: GAT fp32, Chung-Lu power-law graph N=169,343 (exponent 2.2) + self-loops, H=8 D=8",
+    "cfg4": "cfg4: AGNN fp32, N=1,000,000 uniform edges (mean degree 8) + 16 hubs x 200,000 in-edges, H=1 D=64",
+    "cfg5": "cfg5: GT fp32, Chung-Lu power-law graph N=2,449,029, ~122.5M edges (exponent 2.1) + self-loops, H=8 D=16",
+}
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(w, graph, T: int):
+    """Bytes each kernel must move if no neighbour row were ever reused from cache (gather model).
+
+    R = bytes of one node row, s = 4*H bytes of one fp32 scalar per head.  Per-edge and per-node figures
+    per pass; the direct kernels cover the rows / columns below the super threshold, the chunk kernels
+    the rest.
+    """
+    b = 4 if w.dtype == "f32" else 2
+    R, s = w.H * w.D * b, 4 * w.H
+    per = {  # pass: (per edge, per node)
+        "gt": {"fwd": (2 * R + 4, 2 * R + 2 * s + 4), "bwd_row": (2 * R + 4, 4 * R + 4 * s + 4),
+               "bwd_col": (2 * R + 2 * s + 4, 4 * R + 4)},
+        "gat": {"fwd": (R + s + 4, R + 3 * s + 4), "bwd_row": (R + s + 4, 2 * R + 6 * s + 4),
+                "bwd_col": (R + 3 * s + 4, 2 * R + 3 * s + 4)},
+        "agnn": {"fwd": (R + s + 4, 2 * R + 3 * s + 4), "bwd_row": (R + s + 4, 4 * R + 4 * s + 4),
+                 "bwd_col": (2 * R + 3 * s + 4, 3 * R + s + 4)},
+    }[w.model]
+    deg = graph.degrees()
+    out_deg = np.bincount(graph.indices, minlength=graph.n)
+    res = {}
+    for name, d in (("fwd", deg), ("bwd_row", deg), ("bwd_col", out_deg)):
+        sup = d >= T
+        e_sup, n_sup = int(d[sup].sum()), int(sup.sum())
+        pe, pn = per[name]
+        res[name + "_direct"] = pe * (int(d.sum()) - e_sup) + pn * (graph.n - n_sup)
+        res[name + "_chunk"] = pe * e_sup
+        res[name + "_merge"] = pn * n_sup
+    if w.model == "gat":
+        res["node_terms"] = graph.n * (R + 2 * s)
+        res["param_reduce"] = graph.n * (R + 2 * s)
+    if w.model == "agnn":
+        res["node_terms"] = graph.n * (R + s)
+        res["param_reduce"] = graph.n * s
+    return res
+
+
+def sample_subproblem(graph, feats, target_edges: int, seed: int):
+    """Random rows of the graph (whole neighbourhoods) until ~target_edges edges, relabelled compactly.
+
+    The sampled rows keep their neighbour lists; nodes that only appear as neighbours become empty rows.
+    """
+    from dfgnn_synth import from_edge_list
+    rng = np.random.default_rng(seed)
+    deg = graph.degrees()
+    order = rng.permutation(graph.n)
+    take = int(np.searchsorted(np.cumsum(deg[order]), target_edges)) + 1
+    rows = np.sort(order[:take])
+    starts, ends = graph.indptr[rows].astype(np.int64), graph.indptr[rows + 1].astype(np.int64)
+    pos = np.concatenate([np.arange(a, b_) for a, b_ in zip(starts, ends)]) if rows.size else np.empty(0, np.int64)
+    src = graph.indices[pos].astype(np.int64)
+    dst = np.repeat(rows, (ends - starts))
+    nodes, inv = np.unique(np.concatenate([rows, src]), return_inverse=True)
+    new_rows = inv[:rows.size]
+    new_src = inv[rows.size:]
+    new_dst = np.repeat(new_rows, (ends - starts))
+    sub = from_edge_list(nodes.size, new_src, new_dst, sort=False)
+    sub_feats = {k: (v[nodes] if v.ndim == 3 else v) for k, v in feats.items()}
+    return sub, sub_feats, rows, new_rows, int(src.size)
+
+
+def cpu_baseline(w, graph, feats, target_edges: int):
+    import oracle
+    sub, sf, rows, new_rows, n_edges = sample_subproblem(graph, feats, target_edges, seed=w.seed + 7)
+    L = oracle.Layer(w.model, w.H, w.D, scale=w.scale, neg_slope=w.neg_slope, eps=w.eps)
+    kw = dict(x=sf["q"] if w.model == "gt" else sf["feat"], k=sf.get("k"), v=sf.get("v"), a_l=sf.get("a_l"),
+              a_r=sf.get("a_r"))
+    kw = {k: (None if v is None else np.asarray(v, dtype=np.float64)) for k, v in kw.items()}
+    g64 = np.asarray(sf["d_out"], dtype=np.float64)
+    oracle.build_oracle()
+    t0 = time.perf_counter()
+    fw = oracle.forward(L, sub.indptr, sub.indices, **kw)
+    t1 = time.perf_counter()
+    bw = oracle.backward(L, sub.indptr, sub.indices, d_out=g64, **kw)
+    t2 = time.perf_counter()
+    secs = t2 - t0
+    info = {"value": n_edges / secs / 1e9, "unit": "GEdges/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rows.size} random rows with their whole neighbourhoods ({n_edges} edges) of the same graph, "
+                      f"fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, fp64, one thread of {os.cpu_count()} host cores"}
+    return info, (rows, new_rows, fw, bw)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--super-threshold", type=int, default=0)
+    ap.add_argument("--chunk-edges", type=int, default=0)
+    ap.add_argument("--cpu-edges", type=int, default=0, help="edges in the CPU-baseline sample (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-kernel HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2411_16127_amd as dfgnn
+    from dfgnn_synth import make_workload, make_features
+    from dfgnn_synth.workloads import make_graph
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    w = make_workload(args.workload)
+    t0 = time.perf_counter()
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    log(f"{w.name}: N={graph.n} E={graph.nnz} generated in {time.perf_counter() - t0:.1f} s")
+
+    sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges)
+    T = args.super_threshold or DEFAULT_T
+    C = args.chunk_edges or DEFAULT_C
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
+    x = dev(feats["q"] if w.model == "gt" else feats["feat"])
+    k = dev(feats["k"]) if w.model == "gt" else None
+    v = dev(feats["v"]) if w.model == "gt" else None
+    a_l = torch.from_numpy(feats["a_l"]).cuda() if w.model == "gat" else None
+    a_r = torch.from_numpy(feats["a_r"]).cuda() if w.model == "gat" else None
+    d_out = dev(feats["d_out"])
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = dfgnn.Graph(graph.indptr, graph.indices, sched)
+    torch.cuda.synchronize()
+    preprocess_ms = (time.perf_counter() - t0) * 1e3
+    log(f"graph_create (scheduler + CSC, incl. upload): {preprocess_ms:.1f} ms; super rows {g.query('n_super_rows')}, "
+        f"super cols {g.query('n_super_cols')}")
+
+    L = dfgnn.Layer(w.model, w.H, w.D, dtype=w.dtype, scale=w.scale, neg_slope=w.neg_slope, eps=w.eps)
+    N, H = graph.n, w.H
+    out = torch.empty_like(x)
+    row_max = torch.empty((N, H), dtype=torch.float32, device="cuda")
+    row_sum = torch.empty((N, H), dtype=torch.float32, device="cuda")
+    d_x = torch.empty_like(x)
+    d_k = torch.empty_like(x) if w.model == "gt" else None
+    d_v = torch.empty_like(x) if w.model == "gt" else None
+    d_a_l = torch.empty((H, w.D), dtype=torch.float32, device="cuda") if w.model == "gat" else None
+    d_a_r = torch.empty((H, w.D), dtype=torch.float32, device="cuda") if w.model == "gat" else None
+    d_scale = torch.empty(1, dtype=torch.float32, device="cuda") if w.model == "agnn" else None
+    fwd_b, bwd_b = dfgnn.workspace_bytes(g.handle, L)
+    ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        dfgnn.forward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+
+    def bwd():
+        dfgnn.backward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l, d_a_r,
+                       d_scale, ws, ws.numel(), stream)
+
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+
+    # separate fwd / bwd split (not the headline number): events around each call
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(stream); fwd(); ev[1].record(stream); bwd(); ev[2].record(stream)
+    torch.cuda.synchronize()
+    fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+
+    # ---- timed region: exactly K steps, with per-kernel HIP events on the launch stream ----
+    dfgnn.timing_enable(not args.no_kernel_events)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernels = {} if args.no_kernel_events else dfgnn.timing_collect()
+    dfgnn.timing_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    gedges = graph.nnz / (ms_per_step * 1e-3) / 1e9
+    log(f"{ms_per_step:.3f} ms/step (fwd {fwd_ms:.3f} + bwd {bwd_ms:.3f}), {gedges:.3f} GEdges/s")
+
+    model_bytes = algorithmic_bytes(w, graph, T)
+    kern = {}
+    for label, (ms, launches) in kernels.items():
+        avg = ms / max(launches, 1)
+        kb = model_bytes.get(label)
+        kern[label] = {"avg_ms": round(avg, 4), "launches_per_step": launches / args.steps,
+                       "algorithmic_GB": None if kb is None else round(kb / 1e9, 4),
+                       "GBps": None if kb is None or avg <= 0 else round(kb / 1e9 / (avg * 1e-3), 1)}
+    roofline = None
+    if kern:
+        dom = max(kern, key=lambda n: kern[n]["avg_ms"] * kern[n]["launches_per_step"])
+        achieved = kern[dom]["GBps"]
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": None if achieved is None else round(achieved / HBM_PEAK_GBPS, 4),
+                    "traffic": MEASURED_TRAFFIC.get((w.name, dom)),
+                    "algorithmic_bytes_per_launch": model_bytes.get(dom), "avg_ms": kern[dom]["avg_ms"]}
+    total_model = sum(model_bytes.values())
+
+    result = {
+        "metric": "fused AT-GNN layer fwd+bwd GEdges/s at 1 GPU; achieved HBM GB/s vs peak",
+        "value": round(gedges, 4), "unit": "GEdges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": DESCRIPTIONS[w.name], "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
+                   "super_threshold": T, "chunk_edges": C, "stands_in_for": w.stands_in_for},
+        "roofline": roofline,
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "preprocess_ms": round(preprocess_ms, 2),
+        "step_algorithmic_GB": round(total_model / 1e9, 3),
+        "step_effective_GBps": round(total_model / 1e9 / (ms_per_step * 1e-3), 1),
+        "kernels": kern,
+    }
+
+    if not args.no_cpu_baseline:
+        target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 3000000, "cfg5": 2000000}[w.name]
+        info, (rows, new_rows, fw, bw) = cpu_baseline(w, graph, feats, target)
+        # the sampled rows double as a parity spot check of the buffers that were just timed
+        got = out[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        ref = fw["out"][new_rows]
+        tol = (1e-5 + 1e-4 * np.abs(ref)) if w.dtype == "f32" else 2e-2 * (np.abs(ref) + np.sqrt(np.mean(ref ** 2)))
+        info["sample_parity_ok"] = bool(np.all(np.abs(got - ref) <= tol))
+        info["gpu_over_cpu"] = round(gedges / info["value"], 1)
+        info["value"] = float(f"{info['value']:.6g}")
+        result["cpu_baseline"] = info
+        log(f"oracle: {info['value']:.5f} GEdges/s on 1 core; sample parity ok = {info['sample_parity_ok']}")
+    print(json.dumps(result), flush=True)
+    g.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -105,30 +105,33 @@ def _normal(seed: int, stream: int, shape, std: float = 1.0) -> np.ndarray:
     return x
 
 
-def make_features(w: Workload, n: int, seed: Optional[int] = None) -> Dict[str, np.ndarray]:
+def make_features(w: Workload, n: int, seed: Optional[int] = None, threads: int = 4) -> Dict[str, np.ndarray]:
     """Node tensors [n, H, D] float32 (bf16 workloads: values already rounded to bf16).
 
     GT: q, k, v;  GAT: feat (=Wh), a_l, a_r [H, D] fp32;  AGNN: feat (=h).
-    'd_out' is the upstream gradient dL/dO.
+    'd_out' is the upstream gradient dL/dO.  Every tensor has its own random stream, so the values do
+    not depend on `threads` (tensors are drawn concurrently).
     """
+    from concurrent.futures import ThreadPoolExecutor
+
     s = w.seed if seed is None else seed
     shape = (n, w.H, w.D)
-    f: Dict[str, np.ndarray] = {}
     if w.model == "gt":
-        f["q"] = _normal(s + 1, 0, shape)
-        f["k"] = _normal(s + 1, 1, shape)
-        f["v"] = _normal(s + 1, 2, shape)
+        jobs = {"q": (s + 1, 0, shape, 1.0), "k": (s + 1, 1, shape, 1.0), "v": (s + 1, 2, shape, 1.0)}
     elif w.model == "gat":
-        f["feat"] = _normal(s + 1, 0, shape)
-        f["a_l"] = _normal(s + 1, 1, (w.H, w.D), std=0.1)
-        f["a_r"] = _normal(s + 1, 2, (w.H, w.D), std=0.1)
+        jobs = {"feat": (s + 1, 0, shape, 1.0), "a_l": (s + 1, 1, (w.H, w.D), 0.1), "a_r": (s + 1, 2, (w.H, w.D), 0.1)}
     elif w.model == "agnn":
-        f["feat"] = _normal(s + 1, 0, shape)
+        jobs = {"feat": (s + 1, 0, shape, 1.0)}
     else:
         raise ValueError(w.model)
-    f["d_out"] = _normal(s + 2, 0, shape)
-    if w.dtype == "bf16":
-        for key in ("q", "k", "v", "feat", "d_out"):
-            if key in f:
-                f[key] = round_to_bf16(f[key])
-    return f
+    jobs["d_out"] = (s + 2, 0, shape, 1.0)
+
+    def draw(item):
+        key, (seed_, stream, shp, std) = item
+        x = _normal(seed_, stream, shp, std)
+        if w.dtype == "bf16" and key in ("q", "k", "v", "feat", "d_out"):
+            x = round_to_bf16(x)
+        return key, x
+
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
+        return dict(pool.map(draw, jobs.items()))

@@ -154,6 +154,20 @@ int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const voi
                    const void* d_out, void* d_x, void* d_k, void* d_v, float* d_a_l, float* d_a_r, float* d_scale,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Optional per-kernel timing for benchmarks (the measurement protocol of Sec. 5.2 reports kernel time).
+ * dfgnn_timing_enable(1) makes every later layer call record a pair of HIP events around each kernel
+ * it launches, on the stream of that call; dfgnn_timing_enable(0) stops it.  Either call discards
+ * what was recorded.  Process-wide switch, not thread-safe; off by default (no events, no overhead).
+ * dfgnn_timing_collect waits for the recorded events, sums the elapsed milliseconds per kernel label
+ * into the caller's host arrays (at most max_labels entries; labels are static strings owned by the
+ * library), stores the number of labels in *n_labels and clears the record list.  At most 65536
+ * launches are recorded between two collects; later ones are not timed.
+ * Errors: EINVAL (NULL), EWORKSPACE (more labels than max_labels), EHIP.
+ */
+int dfgnn_timing_enable(int enable);
+int dfgnn_timing_collect(int max_labels, const char** labels, double* total_ms, int64_t* launches, int* n_labels);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,5 +21,7 @@ from .binding import (  # noqa: F401
     workspace_bytes,
     forward,
     backward,
+    timing_enable,
+    timing_collect,
     QUERY,
 )

@@ -90,7 +90,10 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
         L.dfgnn_backward.argtypes = [vp, vp] + [vp] * 15 + [vp, sz, vp]
-        for name in ("dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
+        L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
+        L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
+        for name in ("dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -191,6 +194,20 @@ def backward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_o
                                 _ptr(row_max), _ptr(row_sum), _ptr(d_out), _ptr(d_x), _ptr(d_k), _ptr(d_v),
                                 _ptr(d_a_l), _ptr(d_a_r), _ptr(d_scale), _ptr(workspace), workspace_bytes_,
                                 _stream(stream)), "dfgnn_backward")
+
+
+def timing_enable(enable: bool) -> None:
+    _check(lib().dfgnn_timing_enable(1 if enable else 0), "dfgnn_timing_enable")
+
+
+def timing_collect(max_labels: int = 64) -> Dict[str, Tuple[float, int]]:
+    """{kernel label: (total milliseconds, launches)} since the last collect / enable."""
+    labels = (ctypes.c_char_p * max_labels)()
+    ms = (ctypes.c_double * max_labels)()
+    launches = (ctypes.c_int64 * max_labels)()
+    n = ctypes.c_int()
+    _check(lib().dfgnn_timing_collect(max_labels, labels, ms, launches, ctypes.byref(n)), "dfgnn_timing_collect")
+    return {labels[i].decode(): (ms[i], launches[i]) for i in range(n.value)}
 
 
 class Graph:

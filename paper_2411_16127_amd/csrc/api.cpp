@@ -1,8 +1,10 @@
 // Status strings, thread-local error text and version of libdfgnn.
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
+#include <vector>
 
-#include "../../include/dfgnn.h"
+#include "common.hpp"
 
 namespace dfgnn {
 static thread_local char g_error[512] = "";
@@ -14,7 +16,65 @@ void set_error(const char* fmt, ...) {
     va_end(ap);
 }
 void clear_error() { g_error[0] = '\0'; }
+
+// ---- optional per-kernel timing -------------------------------------------------------------------
+namespace {
+struct TimingRecord { const char* label; hipEvent_t start, stop; };
+bool g_timing = false;
+std::vector<TimingRecord> g_records;  // used records: [0, g_used)
+size_t g_used = 0;
+constexpr size_t kMaxRecords = 1 << 16;
+}  // namespace
+
+KernelTimer::KernelTimer(const char* label, hipStream_t st) : slot(-1), stream(st) {
+    if (!g_timing || g_used >= kMaxRecords) return;
+    if (g_used == g_records.size()) {
+        TimingRecord r{label, nullptr, nullptr};
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+        g_records.push_back(r);
+    }
+    slot = (int)g_used++;
+    g_records[slot].label = label;
+    (void)hipEventRecord(g_records[slot].start, stream);
+}
+KernelTimer::~KernelTimer() {
+    if (slot >= 0) (void)hipEventRecord(g_records[slot].stop, stream);
+}
 }  // namespace dfgnn
+
+extern "C" int dfgnn_timing_enable(int enable) {
+    dfgnn::clear_error();
+    dfgnn::g_timing = enable != 0;
+    dfgnn::g_used = 0;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_timing_collect(int max_labels, const char** labels, double* total_ms, int64_t* launches, int* n_labels) {
+    using namespace dfgnn;
+    clear_error();
+    DFGNN_REQUIRE(n_labels != nullptr && (max_labels == 0 || (labels && total_ms && launches)), DFGNN_EINVAL,
+                  "NULL argument");
+    int n = 0;
+    for (size_t r = 0; r < g_used; ++r) {
+        DFGNN_HIP(hipEventSynchronize(g_records[r].stop));
+        float ms = 0.f;
+        DFGNN_HIP(hipEventElapsedTime(&ms, g_records[r].start, g_records[r].stop));
+        int k = 0;
+        while (k < n && std::strcmp(labels[k], g_records[r].label) != 0) ++k;
+        if (k == n) {
+            DFGNN_REQUIRE(n < max_labels, DFGNN_EWORKSPACE, "more than %d distinct kernel labels", max_labels);
+            labels[n] = g_records[r].label;
+            total_ms[n] = 0.0;
+            launches[n] = 0;
+            ++n;
+        }
+        total_ms[k] += ms;
+        launches[k] += 1;
+    }
+    g_used = 0;
+    *n_labels = n;
+    return DFGNN_OK;
+}
 
 extern "C" const char* dfgnn_status_string(int status) {
     switch (status) {

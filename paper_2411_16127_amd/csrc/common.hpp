@@ -51,6 +51,14 @@ struct MetaLayout {
 };
 MetaLayout meta_layout(int64_t N, int64_t E, int T, int C);
 
+// Optional per-kernel timing (dfgnn_timing_enable): a pair of HIP events around a launch.
+struct KernelTimer {
+    KernelTimer(const char* label, hipStream_t st);
+    ~KernelTimer();
+    int slot;
+    hipStream_t stream;
+};
+
 }  // namespace dfgnn
 
 // The opaque handle of the ABI.

@@ -112,7 +112,7 @@ static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kW
 
 // chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
 template <class G, template <class, int> class PassT>
-static void run_pass(const dfgnn_graph* g, bool columns, Args a, hipStream_t st) {
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[3], hipStream_t st) {
     a.ptr = columns ? g->t_indptr : g->indptr;
     a.idx = columns ? g->t_indices : g->indices;
     a.order = columns ? g->col_order : g->row_order;
@@ -125,16 +125,19 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, hipStream_t st)
     if (n_chunks > 0) {
         a.first = 0;
         a.n_items = n_chunks;
+        KernelTimer t(labels[0], st);
         hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, true>), dim3(blocks_for(n_chunks)), block, 0, st, a);
     }
     if (n_direct > 0) {
         a.first = n_super;
         a.n_items = (int)n_direct;
+        KernelTimer t(labels[1], st);
         hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, false>), dim3(blocks_for(n_direct)), block, 0, st, a);
     }
     if (n_super > 0) {
         a.first = 0;
         a.n_items = n_super;
+        KernelTimer t(labels[2], st);
         hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
     }
 }
@@ -142,19 +145,24 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, hipStream_t st)
 template <class G, bool IS_GAT> static void run_node_terms(const Args& a, hipStream_t st) {
     if (a.n_nodes <= 0) return;
     const int64_t waves = ((int64_t)a.n_nodes + G::EPW - 1) / G::EPW;
+    KernelTimer t("node_terms", st);
     hipLaunchKernelGGL((k_node_terms<G, IS_GAT>), dim3(blocks_for(waves)), dim3(64 * kWavesPerBlock), 0, st, a);
 }
 
+static const char* const kFwdLabels[3] = {"fwd_chunk", "fwd_direct", "fwd_merge"};
+static const char* const kRowLabels[3] = {"bwd_row_chunk", "bwd_row_direct", "bwd_row_merge"};
+static const char* const kColLabels[3] = {"bwd_col_chunk", "bwd_col_direct", "bwd_col_merge"};
+
 template <class G> static void run_forward(const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
     switch (model) {
-    case DFGNN_GT: run_pass<G, GtFwd>(g, false, a, st); break;
+    case DFGNN_GT: run_pass<G, GtFwd>(g, false, a, kFwdLabels, st); break;
     case DFGNN_GAT:
         run_node_terms<G, true>(a, st);
-        run_pass<G, GatFwd>(g, false, a, st);
+        run_pass<G, GatFwd>(g, false, a, kFwdLabels, st);
         break;
     default:
         run_node_terms<G, false>(a, st);
-        run_pass<G, AgnnFwd>(g, false, a, st);
+        run_pass<G, AgnnFwd>(g, false, a, kFwdLabels, st);
         break;
     }
 }
@@ -164,23 +172,29 @@ static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* 
                          float* d_scale, hipStream_t st) {
     switch (model) {
     case DFGNN_GT:
-        run_pass<G, GtBwdRow>(g, false, a, st);
-        run_pass<G, GtBwdCol>(g, true, a, st);
+        run_pass<G, GtBwdRow>(g, false, a, kRowLabels, st);
+        run_pass<G, GtBwdCol>(g, true, a, kColLabels, st);
         break;
     case DFGNN_GAT:
         run_node_terms<G, true>(a, st);
-        run_pass<G, GatBwdRow>(g, false, a, st);
-        run_pass<G, GatBwdCol>(g, true, a, st);
-        hipLaunchKernelGGL((k_gat_param_partial<typename G::T>), dim3(kReduceBlocks), dim3(256), 0, st, a, reduce_tmp);
-        hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+        run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
+        run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
+        {
+            KernelTimer t("param_reduce", st);
+            hipLaunchKernelGGL((k_gat_param_partial<typename G::T>), dim3(kReduceBlocks), dim3(256), 0, st, a, reduce_tmp);
+            hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+        }
         break;
     default:
         run_node_terms<G, false>(a, st);
-        run_pass<G, AgnnBwdRow>(g, false, a, st);
-        run_pass<G, AgnnBwdCol>(g, true, a, st);
-        hipLaunchKernelGGL(k_sum_partial, dim3(kReduceBlocks), dim3(256), 0, st, a.dbeta_row,
-                           (int64_t)a.n_nodes * a.H, reduce_tmp);
-        hipLaunchKernelGGL(k_sum_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, d_scale);
+        run_pass<G, AgnnBwdRow>(g, false, a, kRowLabels, st);
+        run_pass<G, AgnnBwdCol>(g, true, a, kColLabels, st);
+        {
+            KernelTimer t("param_reduce", st);
+            hipLaunchKernelGGL(k_sum_partial, dim3(kReduceBlocks), dim3(256), 0, st, a.dbeta_row,
+                               (int64_t)a.n_nodes * a.H, reduce_tmp);
+            hipLaunchKernelGGL(k_sum_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, d_scale);
+        }
         break;
     }
 }
