@@ -29,7 +29,15 @@ DEFAULT_T, DEFAULT_C = 1024, 512
 
 # HBM bytes of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the files
 # under profiles/ named after the kernel and workload); bytes per launch, None where not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/gt_cfg5_kernels.md: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB per launch
+    ("cfg5", "fwd_direct"): 90842197260,
+    ("cfg5", "bwd_row_direct"): 93862436486,
+    ("cfg5", "bwd_col_direct"): 104432953790,
+    ("cfg5", "fwd_chunk"): 33313583775,
+    ("cfg5", "bwd_row_chunk"): 33388595746,
+    ("cfg5", "bwd_col_chunk"): 37572955442,
+}
 
 DESCRIPTIONS = {
     "cfg1": "cfg1: GT fp32, Chung-Lu power-law graph N=2,708 (exponent 2.5) + self-loops, H=1 D=64",
@@ -136,6 +144,8 @@ def main() -> int:
     ap.add_argument("--cpu-edges", type=int, default=0, help="edges in the CPU-baseline sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-kernel HIP events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (scale reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -150,6 +160,14 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_each_way": src.numel() * 4, "launches": 5}))
+        return 0
     w = make_workload(args.workload)
     t0 = time.perf_counter()
     graph = make_graph(w)
