@@ -47,8 +47,9 @@ typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
  * Degree-aware scheduling parameters.  The switch between one fused node-parallel pass and an
  * edge-parallel treatment of super nodes (Sec. 3, Sec. 4.2 "SDDMM") is taken per row here: a row with
  * at least super_threshold neighbours is cut into chunks of chunk_edges edges whose partial softmax
- * statistics are merged in a second pass.  0 selects the library default for either field
- * (super_threshold 1024, chunk_edges 512).
+ * statistics are merged in a second pass.  0 selects the library default for either field:
+ * chunk_edges = E / 16384 rounded up to a power of two and clamped to [64, 512] (E = edges of the
+ * graph), super_threshold = 2 * chunk_edges.  The values in use can be read with dfgnn_graph_query.
  */
 typedef struct {
     int32_t super_threshold;
@@ -62,7 +63,8 @@ typedef struct {
     int32_t dtype;   /* dfgnn_dtype of node tensors (inputs, outputs and their gradients) */
     int32_t H;       /* heads */
     int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
-                        of two (vec = 4 for fp32, 8 for bf16) and H*D/vec <= 64 */
+                        of two (vec = 4 for fp32, 8 for bf16), H*D/vec <= 64, and one node tensor
+                        (N*H*D elements) must stay below 4 GiB */
     float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT: ignored */
     float neg_slope; /* GAT: LeakyReLU slope (derivative at 0 is neg_slope) */
     float eps;       /* AGNN: lower clamp of the feature norm */
@@ -83,7 +85,9 @@ typedef enum {
     DFGNN_Q_COL_CHUNK_PTR = 7, /* [n_super_cols + 1] */
     DFGNN_Q_COL_CHUNKS = 8,    /* [n_col_chunks * 3] (column, begin, end) CSC entry ranges */
     DFGNN_Q_N_SUPER_ROWS = 9,  /* count only (d_ptr = NULL) */
-    DFGNN_Q_N_SUPER_COLS = 10  /* count only */
+    DFGNN_Q_N_SUPER_COLS = 10, /* count only */
+    DFGNN_Q_SUPER_THRESHOLD = 11, /* count only: the super_threshold in use */
+    DFGNN_Q_CHUNK_EDGES = 12      /* count only: the chunk_edges in use */
 } dfgnn_query;
 
 const char* dfgnn_status_string(int status);

@@ -12,8 +12,6 @@
 
 namespace dfgnn {
 
-constexpr int kDefaultSuperThreshold = 1024;
-constexpr int kDefaultChunkEdges = 512;
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -70,4 +68,7 @@ struct dfgnn_graph {
     int32_t *row_order, *col_order, *t_indptr, *t_indices, *t_eid;
     int32_t *row_chunk_ptr, *row_chunks, *col_chunk_ptr, *col_chunks;
     int32_t n_super_rows, n_row_chunks, n_super_cols, n_col_chunks;
+    // [k] = position in row_order / col_order of the first entry with sort key >= k (key 0 = super,
+    // key 33 - b = bit_length(degree) b); [35] = N
+    int32_t row_bucket_ptr[36], col_bucket_ptr[36];
 };

@@ -221,7 +221,7 @@ static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32
 // ------------------------------------------------------------------------------------------------
 // scheduler kernels
 // ------------------------------------------------------------------------------------------------
-enum { CNT_SUPER_ROWS = 0, CNT_ROW_CHUNKS = 1, CNT_SUPER_COLS = 2, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_TOTAL = 16 };
+enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
 
 __global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -248,15 +248,16 @@ __global__ void k_degree_keys(const int* __restrict__ ptr, int n, int T, uint32_
     keys[i] = deg >= T ? 0u : (uint32_t)(33 - (32 - __clz(deg)));
 }
 
-// number of leading zero keys in the sorted key array
-__global__ void k_count_zero_keys(const uint32_t* __restrict__ sorted, int n, int* out) {
-    if (blockIdx.x || threadIdx.x) return;
+// out[k] = position of the first key >= k in the sorted key array, k = 0..35
+__global__ void k_bucket_ptr(const uint32_t* __restrict__ sorted, int n, int* __restrict__ out) {
+    const int k = threadIdx.x;
+    if (blockIdx.x || k >= 36) return;
     int lo = 0, hi = n;
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if (sorted[mid] == 0u) lo = mid + 1; else hi = mid;
+        if (sorted[mid] < (uint32_t)k) lo = mid + 1; else hi = mid;
     }
-    *out = lo;
+    out[k] = lo;
 }
 
 __global__ void k_chunk_counts(const int* __restrict__ order, const int* __restrict__ ptr, int n_super, int C,
@@ -353,25 +354,33 @@ static ScratchLayout scratch_layout(int64_t N, int64_t E, int T) {
     return L;
 }
 
-static int resolve_params(const dfgnn_sched_params* sched, int* T, int* C) {
-    *T = kDefaultSuperThreshold;
-    *C = kDefaultChunkEdges;
+// Defaults grow with the graph: a chunk should be long enough to amortise its start-up (>= 64 edges)
+// and short enough that the chunks of the super rows alone can fill the GPU (256 CUs x 4 SIMDs x
+// several wavefronts): chunk_edges = E / 16384 rounded up to a power of two, clamped to [64, 512];
+// super_threshold = 2 * chunk_edges.
+static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, int* C) {
+    int c = 64;
+    while (c < 512 && (int64_t)c * 16384 < E) c <<= 1;
+    *C = c;
+    *T = 0;
     if (sched) {
         for (int r : sched->reserved) DFGNN_REQUIRE(r == 0, DFGNN_EINVAL, "dfgnn_sched_params.reserved must be zero");
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
-        if (sched->super_threshold > 0) *T = sched->super_threshold;
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
+        if (sched->super_threshold > 0) *T = sched->super_threshold;
     }
+    if (*T == 0) *T = *C > (1 << 29) ? *C : 2 * *C;
     return DFGNN_OK;
 }
 
 // Row (or column) order and super chunks for one pointer array.
 static int build_schedule(const int* ptr, int64_t n, int T, int C, int* order, int* chunk_ptr, int* chunks,
-                          int* d_counters, int slot_super, int slot_chunks, char* scratch, const ScratchLayout& S,
-                          int* n_super_out, int* n_chunks_out, hipStream_t st) {
+                          int* d_counters, int slot_buckets, int slot_chunks, char* scratch, const ScratchLayout& S,
+                          int* n_super_out, int* n_chunks_out, int32_t (&bucket_ptr)[36], hipStream_t st) {
     *n_super_out = 0;
     *n_chunks_out = 0;
+    for (int& b : bucket_ptr) b = 0;
     if (n == 0) return DFGNN_OK;
     uint32_t* keys_a = (uint32_t*)(scratch + S.keys_a);
     uint32_t* keys_b = (uint32_t*)(scratch + S.keys_b);
@@ -384,10 +393,10 @@ static int build_schedule(const int* ptr, int64_t n, int T, int C, int* order, i
     const uint32_t* sorted = nullptr;
     int rc = radix_sort_pairs(keys_a, n, 6, keys_b, keys_a, order, vals, counts, scan_tmp, &sorted, st);
     if (rc != DFGNN_OK) return rc;
-    hipLaunchKernelGGL(k_count_zero_keys, dim3(1), dim3(64), 0, st, sorted, (int)n, d_counters + slot_super);
-    int n_super = 0;
-    DFGNN_HIP(hipMemcpyAsync(&n_super, d_counters + slot_super, sizeof(int), hipMemcpyDeviceToHost, st));
+    hipLaunchKernelGGL(k_bucket_ptr, dim3(1), dim3(64), 0, st, sorted, (int)n, d_counters + slot_buckets);
+    DFGNN_HIP(hipMemcpyAsync(bucket_ptr, d_counters + slot_buckets, 36 * sizeof(int), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
+    const int n_super = bucket_ptr[1];
     *n_super_out = n_super;
     if (n_super == 0) return DFGNN_OK;
     hipLaunchKernelGGL(k_chunk_counts, dim3((unsigned)((n_super + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
@@ -416,7 +425,7 @@ extern "C" int dfgnn_graph_meta_bytes(int64_t N, int64_t E, const dfgnn_sched_pa
     DFGNN_REQUIRE(N < (int64_t)INT32_MAX - (1 << 20) && E < (int64_t)INT32_MAX - (1 << 20), DFGNN_EUNSUPPORTED,
                   "graph too large for int32 indexing");
     int T, C;
-    int rc = resolve_params(sched, &T, &C);
+    int rc = resolve_params(sched, E, &T, &C);
     if (rc != DFGNN_OK) return rc;
     if (meta_bytes) *meta_bytes = meta_layout(N, E, T, C).total;
     if (scratch_bytes) *scratch_bytes = scratch_layout(N, E, T).total;
@@ -440,7 +449,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     DFGNN_REQUIRE(scratch_bytes >= need_scratch, DFGNN_EWORKSPACE, "scratch buffer has %zu bytes, needs %zu",
                   scratch_bytes, need_scratch);
     int T, C;
-    rc = resolve_params(sched, &T, &C);
+    rc = resolve_params(sched, E, &T, &C);
     if (rc != DFGNN_OK) return rc;
 
     hipStream_t st = (hipStream_t)stream;
@@ -478,8 +487,8 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     }
 
     // rows: order and chunks
-    rc = build_schedule(d_indptr, N, T, C, g.row_order, g.row_chunk_ptr, g.row_chunks, d_counters, CNT_SUPER_ROWS,
-                        CNT_ROW_CHUNKS, scratch, S, &g.n_super_rows, &g.n_row_chunks, st);
+    rc = build_schedule(d_indptr, N, T, C, g.row_order, g.row_chunk_ptr, g.row_chunks, d_counters, CNT_ROW_BUCKETS,
+                        CNT_ROW_CHUNKS, scratch, S, &g.n_super_rows, &g.n_row_chunks, g.row_bucket_ptr, st);
     if (rc != DFGNN_OK) return rc;
 
     // CSC transpose: stable sort of CSR positions by source id
@@ -501,8 +510,8 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     }
 
     // columns: order and chunks
-    rc = build_schedule(g.t_indptr, N, T, C, g.col_order, g.col_chunk_ptr, g.col_chunks, d_counters, CNT_SUPER_COLS,
-                        CNT_COL_CHUNKS, scratch, S, &g.n_super_cols, &g.n_col_chunks, st);
+    rc = build_schedule(g.t_indptr, N, T, C, g.col_order, g.col_chunk_ptr, g.col_chunks, d_counters, CNT_COL_BUCKETS,
+                        CNT_COL_CHUNKS, scratch, S, &g.n_super_cols, &g.n_col_chunks, g.col_bucket_ptr, st);
     if (rc != DFGNN_OK) return rc;
     DFGNN_HIP(hipStreamSynchronize(st));
 
@@ -535,6 +544,8 @@ extern "C" int dfgnn_graph_query(const dfgnn_graph* g, int what, const void** d_
     case DFGNN_Q_COL_CHUNKS: p = g->col_chunks; c = 3 * (int64_t)g->n_col_chunks; break;
     case DFGNN_Q_N_SUPER_ROWS: c = g->n_super_rows; break;
     case DFGNN_Q_N_SUPER_COLS: c = g->n_super_cols; break;
+    case DFGNN_Q_SUPER_THRESHOLD: c = g->T; break;
+    case DFGNN_Q_CHUNK_EDGES: c = g->C; break;
     default: DFGNN_REQUIRE(false, DFGNN_EINVAL, "unknown query item %d", what);
     }
     if (d_ptr) *d_ptr = p;

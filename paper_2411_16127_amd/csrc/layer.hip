@@ -112,7 +112,7 @@ static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kW
 
 // chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
 template <class G, template <class, int> class PassT>
-static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[3], hipStream_t st) {
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st) {
     a.ptr = columns ? g->t_indptr : g->indptr;
     a.idx = columns ? g->t_indices : g->indices;
     a.order = columns ? g->col_order : g->row_order;
@@ -120,24 +120,35 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     a.chunk_ptr = columns ? g->col_chunk_ptr : g->row_chunk_ptr;
     const int n_super = columns ? g->n_super_cols : g->n_super_rows;
     const int n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
-    const int64_t n_direct = g->N - n_super;
-    const dim3 block(64 * kWavesPerBlock);
-    if (n_chunks > 0) {
-        a.first = 0;
-        a.n_items = n_chunks;
-        KernelTimer t(labels[0], st);
-        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, true>), dim3(blocks_for(n_chunks)), block, 0, st, a);
+    // rows with fewer than EPW * U neighbours (less than one load round of a whole wavefront) go to the
+    // slot-per-row kernel; they are the tail of the degree-ordered list
+    const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
+    int64_t first_small = g->N;
+    if (G::EPW > 1) {
+        int lg = 0;
+        while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
+        first_small = bucket[33 - lg];
+        if (first_small < n_super) first_small = n_super;
     }
-    if (n_direct > 0) {
-        a.first = n_super;
-        a.n_items = (int)n_direct;
-        KernelTimer t(labels[1], st);
-        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll, false>), dim3(blocks_for(n_direct)), block, 0, st, a);
+    const int64_t n_direct = first_small - n_super;
+    const int64_t n_small = g->N - first_small;
+    a.n_chunks = n_chunks;
+    a.blocks_chunk = (int)blocks_for(n_chunks);
+    a.n_direct = (int)n_direct;
+    a.blocks_direct = (int)blocks_for(n_direct);
+    a.first_direct = n_super;
+    a.n_small = (int)n_small;
+    a.first_small = (int)first_small;
+    const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
+    const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
+    const dim3 block(64 * kWavesPerBlock);
+    if (total > 0) {
+        KernelTimer t(labels[0], st);
+        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll>), dim3(total), block, 0, st, a);
     }
     if (n_super > 0) {
-        a.first = 0;
         a.n_items = n_super;
-        KernelTimer t(labels[2], st);
+        KernelTimer t(labels[1], st);
         hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
     }
 }
@@ -149,9 +160,9 @@ template <class G, bool IS_GAT> static void run_node_terms(const Args& a, hipStr
     hipLaunchKernelGGL((k_node_terms<G, IS_GAT>), dim3(blocks_for(waves)), dim3(64 * kWavesPerBlock), 0, st, a);
 }
 
-static const char* const kFwdLabels[3] = {"fwd_chunk", "fwd_direct", "fwd_merge"};
-static const char* const kRowLabels[3] = {"bwd_row_chunk", "bwd_row_direct", "bwd_row_merge"};
-static const char* const kColLabels[3] = {"bwd_col_chunk", "bwd_col_direct", "bwd_col_merge"};
+static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
+static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
+static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
 
 template <class G> static void run_forward(const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
     switch (model) {
@@ -181,7 +192,7 @@ static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* 
         run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
         {
             KernelTimer t("param_reduce", st);
-            hipLaunchKernelGGL((k_gat_param_partial<typename G::T>), dim3(kReduceBlocks), dim3(256), 0, st, a, reduce_tmp);
+            hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
             hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
         }
         break;
@@ -229,13 +240,19 @@ static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo
     DFGNN_REQUIRE(L->reserved[0] == 0, DFGNN_EINVAL, "dfgnn_layer.reserved must be zero");
     int rc = pick_geometry(L, geo);
     if (rc != DFGNN_OK) return rc;
-    DFGNN_REQUIRE((int64_t)g->N * L->H * L->D < ((int64_t)1 << 40), DFGNN_EUNSUPPORTED, "node tensor too large");
+    const int64_t elem = L->dtype == DFGNN_F32 ? 4 : 2;
+    DFGNN_REQUIRE((int64_t)g->N * L->H * L->D * elem < ((int64_t)1 << 32) - 4096, DFGNN_EUNSUPPORTED,
+                  "node tensor of %lld bytes: gathers use 32-bit byte offsets, tensors must stay below 4 GiB",
+                  (long long)((int64_t)g->N * L->H * L->D * elem));
     if (L->model == DFGNN_AGNN) DFGNN_REQUIRE(L->eps > 0.f, DFGNN_EINVAL, "AGNN eps must be positive");
     return DFGNN_OK;
 }
 
 static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, const Geometry& geo) {
     a.n_nodes = (int)g->N;
+    a.row_bytes = (uint32_t)(L->H * L->D * (L->dtype == DFGNN_F32 ? 4 : 2));
+    a.tensor_bytes = (uint32_t)((uint64_t)g->N * a.row_bytes);
+    a.nh_bytes = (uint32_t)((uint64_t)g->N * L->H * 4u);
     a.H = L->H;
     a.D = L->D;
     a.HD = L->H * L->D;

@@ -69,6 +69,27 @@ template <> struct Elem<bf16_t> {
     }
 };
 
+// Gathers go through buffer loads: a 32-bit byte offset per lane against a base held in scalar
+// registers, with the hardware range check returning zeros past the end of the tensor.  An absent
+// neighbour (index -1) wraps to an offset beyond any tensor (tensors are kept below 4 GiB), so tail
+// rounds need no per-lane branches.
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+__device__ inline rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ inline u32x4 buf_load16(rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+__device__ inline f32x4 buf_load_f32x4(rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+__device__ inline f32x2 buf_load_f32x2(rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0));
+}
+__device__ inline float buf_load_f32(rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+}
+
 template <typename T> __device__ inline u32x4 load_raw(const void* base, size_t elem_offset) {
     return *reinterpret_cast<const u32x4*>(static_cast<const T*>(base) + elem_offset);
 }
@@ -135,9 +156,14 @@ struct Args {
     const int* order;
     const int* chunks;
     const int* chunk_ptr;
-    int first;    // direct pass: items are order[first + w]
-    int n_items;  // waves that have work
+    int n_chunks, blocks_chunk;             // chunk items (super rows), and the workgroups that hold them
+    int n_direct, blocks_direct;            // whole-row items: order[first_direct + item]
+    int n_small, first_small, first_direct; // short rows: order[first_small + r], one per edge slot
+    int n_items;                            // merge kernel: super rows
     int n_nodes;
+    uint32_t row_bytes;     // bytes of one node row
+    uint32_t tensor_bytes;  // bytes of one node tensor (< 4 GiB)
+    uint32_t nh_bytes;      // bytes of one [N, H] fp32 array
     // shape and constants
     int H, D, HD, lph;
     float c_score;  // GT scale*log2(e); AGNN beta*log2(e); GAT log2(e)
@@ -174,7 +200,17 @@ struct Ctx {
     int lane, c, g, f0, h, node;
     bool active;  // this lane's features exist (f0 < HD)
     bool head0;   // first lane of its head
+    bool writer;  // this lane stores results: edge slot 0 when the wave shares one row, every live slot otherwise
+    uint32_t fbyte;  // byte offset of this lane's features inside a node row
+    uint32_t hbyte;  // byte offset of this lane's head inside a [.., H] fp32 record
     size_t off;   // node*HD + f0
+};
+
+// Where a lane reads chunk partials: lanes without features of their own read feature 0 / head 0, so
+// the merge loop has no per-lane branch (its loads can overlap); such lanes never store anything.
+struct PartialIndex {
+    int f0, h;
+    __device__ explicit PartialIndex(const Ctx& c) : f0(c.active ? c.f0 : 0), h(c.h) {}
 };
 
 template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int node) {
@@ -188,6 +224,9 @@ template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int n
     c.head0 = c.active && (c.f0 % a.D) == 0;
     c.node = node;
     c.off = (size_t)node * a.HD + c.f0;
+    c.writer = c.g == 0;
+    c.fbyte = (uint32_t)c.f0 * (uint32_t)sizeof(typename G::T);
+    c.hbyte = (uint32_t)c.h * 4u;
     return c;
 }
 
@@ -200,10 +239,20 @@ template <class G> __device__ inline void load_row(const void* base, const Ctx& 
     }
 }
 
+// neighbour row j of a node tensor (zeros for j = -1)
 template <class G> __device__ inline u32x4 gather_raw(const void* base, const Args& a, const Ctx& c, int j) {
-    u32x4 z = {0u, 0u, 0u, 0u};
-    if (j >= 0 && c.active) z = load_raw<typename G::T>(base, (size_t)j * a.HD + c.f0);
-    return z;
+    return buf_load16(make_rsrc(base, a.tensor_bytes), (uint32_t)j * a.row_bytes + c.fbyte);
+}
+// entry (j, head) of an [N, H] fp32 array (zero for j = -1)
+__device__ inline float gather_f32(const float* base, const Args& a, const Ctx& c, int j) {
+    return buf_load_f32(make_rsrc(base, a.nh_bytes), (uint32_t)j * (uint32_t)(a.H * 4) + c.hbyte);
+}
+// packed row statistics of (i, head): 2 or 4 floats per record (zeros for i = -1)
+__device__ inline f32x2 gather_stats2(const Args& a, const Ctx& c, int i) {
+    return buf_load_f32x2(make_rsrc(a.stats, a.nh_bytes * 2u), (uint32_t)i * (uint32_t)(a.H * 8) + c.hbyte * 2u);
+}
+__device__ inline f32x4 gather_stats4(const Args& a, const Ctx& c, int i) {
+    return buf_load_f32x4(make_rsrc(a.stats, a.nh_bytes * 4u), (uint32_t)i * (uint32_t)(a.H * 16) + c.hbyte * 4u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -261,22 +310,22 @@ template <class G, int U> struct SoftmaxAcc {
         }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) const {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, acc);
         if (c.head0) {
             a.part_s0[(size_t)item * a.H + c.h] = m;
             a.part_s1[(size_t)item * a.H + c.h] = l;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float ao[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, ao);
         merge(a.part_s0[(size_t)chunk * a.H + c.h], a.part_s1[(size_t)chunk * a.H + c.h], ao);
     }
     // O = acc / l; statistics back in natural-log units
     __device__ void finalize(const Args& a, const Ctx& c) const {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         const float inv = l > 0.f ? 1.f / l : 0.f;
         float o[VEC];
 #pragma unroll
@@ -401,15 +450,15 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dq);
         if constexpr (kExact) {
             store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, pk);
             if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float t[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
 #pragma unroll
@@ -422,7 +471,7 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         if constexpr (kExact) {
             this->delta = this->dsum;
 #pragma unroll
@@ -455,9 +504,7 @@ template <class G, int U> struct GtBwdCol {
     __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
         Q[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        f32x2 z = {0.f, 0.f};
-        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x2*>(a.stats + 2 * ((size_t)i * a.H + c.h));
-        St[u] = z;
+        St[u] = gather_stats2(a, c, i);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
@@ -481,12 +528,12 @@ template <class G, int U> struct GtBwdCol {
         for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dv[i] = slot_sum<G::LPE>(dv[i]); }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
         store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dv);
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float t0[VEC], t1[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
         load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
@@ -494,7 +541,7 @@ template <class G, int U> struct GtBwdCol {
         for (int i = 0; i < VEC; ++i) { dk[i] += t0[i]; dv[i] += t1[i]; }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = a.scale * dk[i];
@@ -520,7 +567,7 @@ template <class G, int U> struct GatFwd {
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
         V[u] = gather_raw<G>(a.x, a, c, j);
-        Er[u] = (j >= 0 && c.active) ? a.node_b[(size_t)j * a.H + c.h] : 0.f;
+        Er[u] = gather_f32(a.node_b, a, c, j);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
@@ -553,7 +600,7 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
         V[u] = gather_raw<G>(a.x, a, c, j);
-        Er[u] = (j >= 0 && c.active) ? a.node_b[(size_t)j * a.H + c.h] : 0.f;
+        Er[u] = gather_f32(a.node_b, a, c, j);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
@@ -582,15 +629,15 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.head0) return;
+        if (!c.writer || !c.head0) return;
         a.part_s0[(size_t)item * a.H + c.h] = d_el;
         if constexpr (kExact) {
             a.part_s1[(size_t)item * a.H + c.h] = pl;
             a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         d_el += a.part_s0[(size_t)chunk * a.H + c.h];
         if constexpr (kExact) {
             pl += a.part_s1[(size_t)chunk * a.H + c.h];
@@ -598,7 +645,7 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
-        if (c.g != 0 || !c.head0) return;
+        if (!c.writer || !c.head0) return;
         if constexpr (kExact) {
             this->delta = this->dsum;
             d_el -= this->delta * pl;
@@ -626,9 +673,7 @@ template <class G, int U> struct GatBwdCol {
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x4*>(a.stats + 4 * ((size_t)i * a.H + c.h));
-        St[u] = z;
+        St[u] = gather_stats4(a, c, i);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
@@ -650,12 +695,12 @@ template <class G, int U> struct GatBwdCol {
         for (int i = 0; i < VEC; ++i) dwh[i] = slot_sum<G::LPE>(dwh[i]);
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dwh);
         if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_er;
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float t[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
 #pragma unroll
@@ -663,7 +708,7 @@ template <class G, int U> struct GatBwdCol {
         d_er += a.part_s0[(size_t)chunk * a.H + c.h];
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         const size_t nh = (size_t)c.node * a.H + c.h;
         const float del = a.d_el[nh];
         float al[VEC], ar[VEC], o[VEC];
@@ -694,7 +739,7 @@ template <class G, int U> struct AgnnFwd {
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
         V[u] = gather_raw<G>(a.x, a, c, j);
-        Rn[u] = (j >= 0 && c.active) ? a.node_a[(size_t)j * a.H + c.h] : 0.f;
+        Rn[u] = gather_f32(a.node_a, a, c, j);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
@@ -733,7 +778,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
         V[u] = gather_raw<G>(a.x, a, c, j);
-        Rn[u] = (j >= 0 && c.active) ? a.node_a[(size_t)j * a.H + c.h] : 0.f;
+        Rn[u] = gather_f32(a.node_a, a, c, j);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
@@ -772,7 +817,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, ga);
         if constexpr (kExact) store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, px);
         if (c.head0) {
@@ -783,8 +828,8 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             }
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float t[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
 #pragma unroll
@@ -799,7 +844,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         if constexpr (kExact) {
             this->delta = this->dsum;
             dbeta -= this->delta * pc;
@@ -836,9 +881,7 @@ template <class G, int U> struct AgnnBwdCol {
     __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
         Xi[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        if (i >= 0 && c.active) z = *reinterpret_cast<const f32x4*>(a.stats + 4 * ((size_t)i * a.H + c.h));
-        St[u] = z;
+        St[u] = gather_stats4(a, c, i);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
@@ -863,12 +906,12 @@ template <class G, int U> struct AgnnBwdCol {
         for (int i = 0; i < VEC; ++i) { val[i] = slot_sum<G::LPE>(val[i]); ga[i] = slot_sum<G::LPE>(ga[i]); }
     }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, val);
         store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, ga);
     }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) {
-        if (!c.active) return;
+    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+        const PartialIndex c(c0);
         float t0[VEC], t1[VEC];
         load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
         load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
@@ -889,7 +932,7 @@ template <class G, int U> struct AgnnBwdCol {
         const float proj = head_sum<G::LPH>(dotv<VEC>(gt, xh), a.lph);
         const float nrm2 = head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph);
         const bool clamped = !(sqrtf(nrm2) > a.eps);
-        if (c.g != 0 || !c.active) return;
+        if (!c.writer || !c.active) return;
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = (clamped ? gt[i] * rn : rn * (gt[i] - proj * xh[i])) + val[i];
@@ -911,22 +954,24 @@ __device__ inline void load_indices(const Args& a, const Ctx& c, int base, int e
     }
 }
 
-// One wavefront per work item; PARTIAL: items are chunks of super rows and results go to the workspace.
+// A whole wavefront on one work item.  PARTIAL: the item is a chunk of a super row and its result goes
+// to the workspace; otherwise the item is a whole row and the wavefront finishes it.
 template <class G, template <class, int> class PassT, int U, bool PARTIAL>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = blockIdx.x * kWavesPerBlock + wave;
-    if (item >= a.n_items) return;
+__device__ inline void wave_item(const Args& a, int item, int lane) {
     int node, eb, ee;
     if (PARTIAL) {
         node = a.chunks[3 * item];
         eb = a.chunks[3 * item + 1];
         ee = a.chunks[3 * item + 2];
     } else {
-        node = a.order[a.first + item];
+        node = a.order[a.first_direct + item];
         eb = a.ptr[node];
         ee = a.ptr[node + 1];
     }
+    // the whole wavefront works on one item: keep its bounds in scalar registers
+    node = __builtin_amdgcn_readfirstlane(node);
+    eb = __builtin_amdgcn_readfirstlane(eb);
+    ee = __builtin_amdgcn_readfirstlane(ee);
     const Ctx c = make_ctx<G>(a, lane, node);
     PassT<G, U> p;
     p.init(a, c);
@@ -947,19 +992,79 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
     else p.finalize(a, c);
 }
 
-// One wavefront per super row / column: sums (or, for the forward pass, softmax-merges) the partial
-// results of its chunks in chunk order and finishes the row exactly as the direct pass would.
+// Rows shorter than one load round of a whole wavefront: every edge slot (LPE lanes) owns a row of
+// its own, so a wavefront finishes 64/LPE rows at once and nothing has to be merged across slots.
+// Rows come from the degree-ordered list, so the slots of a wavefront have similar trip counts.
+template <class G, template <class, int> class PassT, int U>
+__device__ inline void wave_small_rows(const Args& a, int item, int lane) {
+    const int r = item * G::EPW + lane / G::LPE;
+    const bool live = r < a.n_small;
+    const int node = a.order[a.first_small + (live ? r : 0)];
+    const int eb = live ? a.ptr[node] : 0;
+    const int ee = live ? a.ptr[node + 1] : 0;
+    Ctx c = make_ctx<G>(a, lane, node);
+    c.writer = live;
+    PassT<G, U> p;
+    p.init(a, c);
+    int j[U], jn[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) j[u] = eb + u < ee ? a.idx[eb + u] : -1;
+    for (int pos = eb; __any(pos < ee); pos += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) jn[u] = pos + U + u < ee ? a.idx[pos + U + u] : -1;
+        if (__all(pos + U <= ee)) p.template consume<true>(a, c, j);
+        else p.template consume<false>(a, c, j);
+#pragma unroll
+        for (int u = 0; u < U; ++u) j[u] = jn[u];
+    }
+    p.finalize(a, c);
+}
+
+// One launch per pass.  Workgroups are handed out in the order of their work: first the chunks of
+// super rows (edge-parallel split), then whole rows by descending degree class (node-parallel, one
+// wavefront each), then the short rows, one per edge slot.  Each of the 4 wavefronts of a workgroup
+// works alone; the kind of work depends only on blockIdx, so a wavefront never diverges on it.
+template <class G, template <class, int> class PassT, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int b = blockIdx.x;
+    if (b < a.blocks_chunk) {
+        const int item = b * kWavesPerBlock + wave;
+        if (item < a.n_chunks) wave_item<G, PassT, U, true>(a, item, lane);
+        return;
+    }
+    b -= a.blocks_chunk;
+    if (b < a.blocks_direct) {
+        const int item = b * kWavesPerBlock + wave;
+        if (item < a.n_direct) wave_item<G, PassT, U, false>(a, item, lane);
+        return;
+    }
+    b -= a.blocks_direct;
+    if constexpr (G::EPW > 1) {
+        const int item = b * kWavesPerBlock + wave;
+        if (item * G::EPW < a.n_small) wave_small_rows<G, PassT, U>(a, item, lane);
+    }
+}
+
+// One wavefront per super row / column: the edge slots take the row's chunks round-robin and sum (or,
+// for the forward pass, softmax-merge) their partial results, the slots are combined as in the direct
+// pass, and the row is finished exactly as the direct pass would.  Summation order is fixed.
 template <class G, template <class, int> class PassT, int U>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int s = blockIdx.x * kWavesPerBlock + wave;
     if (s >= a.n_items) return;
-    const int node = a.order[s];
-    const int c0 = a.chunk_ptr[s], c1 = a.chunk_ptr[s + 1];
+    const int node = __builtin_amdgcn_readfirstlane(a.order[s]);
+    const int c0 = __builtin_amdgcn_readfirstlane(a.chunk_ptr[s]);
+    const int c1 = __builtin_amdgcn_readfirstlane(a.chunk_ptr[s + 1]);
     const Ctx c = make_ctx<G>(a, lane, node);
     PassT<G, U> p;
     p.init(a, c);
-    for (int ch = c0; ch < c1; ++ch) p.add_partial(a, c, ch);
+#pragma unroll 8
+    for (int ch = c0 + c.g; ch < c1; ch += G::EPW) p.add_partial(a, c, ch);
+    p.combine_slots(a, c);
     p.finalize(a, c);
 }
 
@@ -1000,37 +1105,63 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_node_terms(const Args a
 // ---------------------------------------------------------------------------------------------
 constexpr int kReduceBlocks = 256;
 
-// stage 1 of da_l[h,d] = sum_v d_el[v,h] Wh[v,h,d] and da_r likewise: block b takes nodes b, b+B, ...
-template <typename T>
-__global__ __launch_bounds__(256) void k_gat_param_partial(const Args a, float* __restrict__ partial) {
-    for (int f = threadIdx.x; f < a.HD; f += blockDim.x) {
-        const int h = f / a.D;
-        float sl = 0.f, sr = 0.f;
-        for (int v = blockIdx.x; v < a.n_nodes; v += gridDim.x) {
-            float x;
-            if constexpr (sizeof(T) == 2) {
-                x = __builtin_bit_cast(float, (uint32_t)static_cast<const uint16_t*>(a.x)[(size_t)v * a.HD + f] << 16);
-            } else {
-                x = static_cast<const float*>(a.x)[(size_t)v * a.HD + f];
+// stage 1 of da_l[h,d] = sum_v d_el[v,h] Wh[v,h,d] and da_r likewise.  Same lane geometry as the passes:
+// an edge slot reads one node row per step; wave w of the grid takes node groups w, w + W, ...;
+// one partial per workgroup.
+template <class G>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const Args a, float* __restrict__ partial) {
+    __shared__ float red[kWavesPerBlock][2][64 * G::VEC];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int waves = gridDim.x * kWavesPerBlock;
+    float sl[G::VEC], sr[G::VEC];
+#pragma unroll
+    for (int i = 0; i < G::VEC; ++i) { sl[i] = 0.f; sr[i] = 0.f; }
+    for (int base = (blockIdx.x * kWavesPerBlock + wave) * G::EPW; base < a.n_nodes; base += waves * G::EPW) {
+        const int v = base + lane / G::LPE;
+        if (v < a.n_nodes) {
+            const Ctx c = make_ctx<G>(a, lane, v);
+            if (c.active) {
+                float x[G::VEC];
+                load_row<G>(a.x, c, x);
+                const float del = a.d_el[(size_t)v * a.H + c.h], der = a.d_er[(size_t)v * a.H + c.h];
+#pragma unroll
+                for (int i = 0; i < G::VEC; ++i) { sl[i] = fmaf(del, x[i], sl[i]); sr[i] = fmaf(der, x[i], sr[i]); }
             }
-            sl = fmaf(a.d_el[(size_t)v * a.H + h], x, sl);
-            sr = fmaf(a.d_er[(size_t)v * a.H + h], x, sr);
         }
-        partial[((size_t)blockIdx.x * 2 + 0) * a.HD + f] = sl;
-        partial[((size_t)blockIdx.x * 2 + 1) * a.HD + f] = sr;
+    }
+#pragma unroll
+    for (int i = 0; i < G::VEC; ++i) { sl[i] = slot_sum<G::LPE>(sl[i]); sr[i] = slot_sum<G::LPE>(sr[i]); }
+    const int f0 = (lane % G::LPE) * G::VEC;
+    if (lane < G::LPE) {
+#pragma unroll
+        for (int i = 0; i < G::VEC; ++i) { red[wave][0][f0 + i] = sl[i]; red[wave][1][f0 + i] = sr[i]; }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < 2 * a.HD; t += blockDim.x) {
+        const int which = t / a.HD, f = t % a.HD;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) sum += red[w][which][f];
+        partial[((size_t)blockIdx.x * 2 + which) * a.HD + f] = sum;
     }
 }
 
 __global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
                                                          float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
-    for (int f = threadIdx.x; f < HD; f += blockDim.x) {
-        float sl = 0.f, sr = 0.f;
-        for (int b = 0; b < nblocks; ++b) {
-            sl += partial[((size_t)b * 2 + 0) * HD + f];
-            sr += partial[((size_t)b * 2 + 1) * HD + f];
+    // thread t: feature t % HD of (a_l | a_r); 4 interleaved partial sums give the loads some overlap
+    for (int t = threadIdx.x; t < 2 * HD; t += blockDim.x) {
+        const int which = t / HD, f = t % HD;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int b = 0;
+#pragma unroll 8
+        for (; b + 3 < nblocks; b += 4) {
+            s0 += partial[((size_t)(b + 0) * 2 + which) * HD + f];
+            s1 += partial[((size_t)(b + 1) * 2 + which) * HD + f];
+            s2 += partial[((size_t)(b + 2) * 2 + which) * HD + f];
+            s3 += partial[((size_t)(b + 3) * 2 + which) * HD + f];
         }
-        d_a_l[f] = sl;
-        d_a_r[f] = sr;
+        for (; b < nblocks; ++b) s0 += partial[((size_t)b * 2 + which) * HD + f];
+        (which ? d_a_r : d_a_l)[f] = (s0 + s1) + (s2 + s3);
     }
 }
 

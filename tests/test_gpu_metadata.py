@@ -10,12 +10,21 @@ from dfgnn_synth.workloads import make_graph
 pytestmark = pytest.mark.gpu
 
 
-DEFAULT_T, DEFAULT_C = 1024, 512  # library defaults documented in include/dfgnn.h
+def default_params(E):
+    """Defaults documented in include/dfgnn.h."""
+    c = 64
+    while c < 512 and c * 16384 < E:
+        c *= 2
+    return 2 * c, c
 
 
 def check_metadata(graph, T, C):
     g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(T, C))
-    T, C = T or DEFAULT_T, C or DEFAULT_C
+    if C == 0:
+        C = default_params(graph.nnz)[1]
+    if T == 0:
+        T = 2 * C
+    assert g.query("n_super_threshold") == T and g.query("n_chunk_edges") == C
     csc = oracle.csc_transpose(graph.indptr, graph.indices)
     rows = oracle.schedule(graph.indptr, T, C)
     cols = oracle.schedule(csc["t_indptr"], T, C)
