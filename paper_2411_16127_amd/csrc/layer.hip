@@ -57,7 +57,7 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
 // workspace layout (float offsets turned into pointers)
 // ---------------------------------------------------------------------------------------------
 struct Workspace {
-    size_t node_a, node_b, stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, total;
+    size_t stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, total;
 };
 
 static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward) {
@@ -68,8 +68,6 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
     const size_t chunks = backward ? (size_t)(g->n_row_chunks > g->n_col_chunks ? g->n_row_chunks : g->n_col_chunks)
                                    : (size_t)g->n_row_chunks;
     const bool gat = L->model == DFGNN_GAT, agnn = L->model == DFGNN_AGNN;
-    W.node_a = take(gat || agnn ? N * H : 0);
-    W.node_b = take(gat ? N * H : 0);
     W.part_v0 = take(chunks * HD);
     W.part_s0 = take(chunks * H);
     W.part_s1 = take(chunks * H);
@@ -89,8 +87,6 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
 
 static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward) {
     char* b = (char*)ws;
-    a.node_a = (float*)(b + W.node_a);
-    a.node_b = (float*)(b + W.node_b);
     a.part_v0 = (float*)(b + W.part_v0);
     a.part_s0 = (float*)(b + W.part_s0);
     a.part_s1 = (float*)(b + W.part_s1);
@@ -153,13 +149,6 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     }
 }
 
-template <class G, bool IS_GAT> static void run_node_terms(const Args& a, hipStream_t st) {
-    if (a.n_nodes <= 0) return;
-    const int64_t waves = ((int64_t)a.n_nodes + G::EPW - 1) / G::EPW;
-    KernelTimer t("node_terms", st);
-    hipLaunchKernelGGL((k_node_terms<G, IS_GAT>), dim3(blocks_for(waves)), dim3(64 * kWavesPerBlock), 0, st, a);
-}
-
 static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
 static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
 static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
@@ -168,11 +157,9 @@ template <class G> static void run_forward(const dfgnn_graph* g, int model, cons
     switch (model) {
     case DFGNN_GT: run_pass<G, GtFwd>(g, false, a, kFwdLabels, st); break;
     case DFGNN_GAT:
-        run_node_terms<G, true>(a, st);
         run_pass<G, GatFwd>(g, false, a, kFwdLabels, st);
         break;
     default:
-        run_node_terms<G, false>(a, st);
         run_pass<G, AgnnFwd>(g, false, a, kFwdLabels, st);
         break;
     }
@@ -187,7 +174,6 @@ static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* 
         run_pass<G, GtBwdCol>(g, true, a, kColLabels, st);
         break;
     case DFGNN_GAT:
-        run_node_terms<G, true>(a, st);
         run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
         run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
         {
@@ -197,7 +183,6 @@ static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* 
         }
         break;
     default:
-        run_node_terms<G, false>(a, st);
         run_pass<G, AgnnBwdRow>(g, false, a, kRowLabels, st);
         run_pass<G, AgnnBwdCol>(g, true, a, kColLabels, st);
         {
@@ -261,6 +246,7 @@ static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, con
     a.c_score = a.scale * kLog2e;
     a.neg_slope = L->neg_slope;
     a.eps = L->eps;
+    a.inv_eps = L->eps > 0.f ? 1.f / L->eps : 0.f;
 }
 
 }  // namespace dfgnn

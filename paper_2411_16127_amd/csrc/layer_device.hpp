@@ -168,7 +168,7 @@ struct Args {
     int H, D, HD, lph;
     float c_score;  // GT scale*log2(e); AGNN beta*log2(e); GAT log2(e)
     float scale;    // GT scale; AGNN beta
-    float neg_slope, eps;
+    float neg_slope, eps, inv_eps;
     // tensors in the layer dtype
     const void *x, *k, *v, *out, *d_out;
     void *o, *d_x, *d_k, *d_v;
@@ -176,8 +176,6 @@ struct Args {
     const float *a_l, *a_r, *row_max, *row_sum;
     float *o_max, *o_sum;
     // workspace
-    float* node_a;     // GAT: el*log2e [N,H]; AGNN: 1/max(|h|,eps) [N,H]
-    float* node_b;     // GAT: er*log2e [N,H]
     float* stats;      // per (row, head): GT {lse2, delta}; GAT {el2, lse2, delta, 0}; AGNN {rn, lse2, delta, 0}
     float* d_el;       // GAT [N,H]
     float* d_er;       // GAT [N,H]
@@ -213,6 +211,12 @@ struct PartialIndex {
     __device__ explicit PartialIndex(const Ctx& c) : f0(c.active ? c.f0 : 0), h(c.h) {}
 };
 
+// One chunk's partial results as loaded by a merge wavefront: up to two feature vectors and three
+// per-head scalars (each pass uses the ones it stored; chunks of an absent index are masked when folded).
+template <int VEC> struct PartialRegs {
+    float v0[VEC], v1[VEC], s0, s1, s2;
+};
+
 template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int node) {
     Ctx c;
     c.lane = lane;
@@ -242,10 +246,6 @@ template <class G> __device__ inline void load_row(const void* base, const Ctx& 
 // neighbour row j of a node tensor (zeros for j = -1)
 template <class G> __device__ inline u32x4 gather_raw(const void* base, const Args& a, const Ctx& c, int j) {
     return buf_load16(make_rsrc(base, a.tensor_bytes), (uint32_t)j * a.row_bytes + c.fbyte);
-}
-// entry (j, head) of an [N, H] fp32 array (zero for j = -1)
-__device__ inline float gather_f32(const float* base, const Args& a, const Ctx& c, int j) {
-    return buf_load_f32(make_rsrc(base, a.nh_bytes), (uint32_t)j * (uint32_t)(a.H * 4) + c.hbyte);
 }
 // packed row statistics of (i, head): 2 or 4 floats per record (zeros for i = -1)
 __device__ inline f32x2 gather_stats2(const Args& a, const Ctx& c, int i) {
@@ -317,11 +317,18 @@ template <class G, int U> struct SoftmaxAcc {
             a.part_s1[(size_t)item * a.H + c.h] = l;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
+        P.s1 = a.part_s1[(size_t)chunk * a.H + c.h];
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
         float ao[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, ao);
-        merge(a.part_s0[(size_t)chunk * a.H + c.h], a.part_s1[(size_t)chunk * a.H + c.h], ao);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ao[i] = w * P.v0[i];
+        merge(valid ? P.s0 : -INFINITY, w * P.s1, ao);
     }
     // O = acc / l; statistics back in natural-log units
     __device__ void finalize(const Args& a, const Ctx& c) const {
@@ -399,7 +406,8 @@ template <class G, int U> struct GtFwd {
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
 
@@ -457,17 +465,22 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
             if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        float t[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dq[i] += t[i];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
         if constexpr (kExact) {
-            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t);
+            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
+            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
+        }
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) pk[i] += t[i];
-            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+        for (int i = 0; i < VEC; ++i) dq[i] = fmaf(w, P.v0[i], dq[i]);
+        if constexpr (kExact) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) pk[i] = fmaf(w, P.v1[i], pk[i]);
+            this->dsum = fmaf(w, P.s2, this->dsum);
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
@@ -532,13 +545,15 @@ template <class G, int U> struct GtBwdCol {
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
         store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dv);
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        float t0[VEC], t1[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
-        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] += t0[i]; dv[i] += t1[i]; }
+        for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(w, P.v0[i], dk[i]); dv[i] = fmaf(w, P.v1[i], dv[i]); }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.active) return;
@@ -555,25 +570,40 @@ template <class G, int U> struct GtBwdCol {
 // =============================================================================================
 __device__ inline float leaky(float z, float slope) { return z > 0.f ? z : slope * z; }
 
+// this lane's slice of a [H, D] fp32 attention vector, times mul (zeros for lanes without features)
+template <class G> __device__ inline void load_attention(const float* v, const Ctx& c, float mul, float (&out)[G::VEC]) {
+#pragma unroll
+    for (int i = 0; i < G::VEC; ++i) out[i] = 0.f;
+    if (c.active) {
+        load_f32<G::VEC>(v + c.f0, out);
+#pragma unroll
+        for (int i = 0; i < G::VEC; ++i) out[i] *= mul;
+    }
+}
+
 template <class G, int U> struct GatFwd {
     static constexpr int VEC = G::VEC;
-    float el2;
+    float el2, ar2[VEC];  // el_i * log2e; this lane's slice of a_r * log2e
     SoftmaxAcc<G, U> sm;
     u32x4 V[U];
-    float Er[U];
+    // el_i comes from the row's own features and er_j from the gathered neighbour row (one dot product
+    // over the head's lanes), so no per-node scalar has to be gathered from memory
     __device__ void init(const Args& a, const Ctx& c) {
-        el2 = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        float x[VEC], al[VEC];
+        load_row<G>(a.x, c, x);
+        load_attention<G>(a.a_l, c, kLog2e, al);
+        load_attention<G>(a.a_r, c, kLog2e, ar2);
+        el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        Er[u] = gather_f32(a.node_b, a, c, j);
-    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            s[u] = leaky(el2 + Er[u], a.neg_slope);
+            float vf[VEC];
+            Elem<typename G::T>::unpack(V[u], vf);
+            s[u] = leaky(el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph), a.neg_slope);
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -581,7 +611,8 @@ template <class G, int U> struct GatFwd {
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
 
@@ -589,26 +620,26 @@ template <class G, int U> struct GatFwd {
 template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
     static constexpr bool kExact = RowBackwardBase<G>::kExact;
-    float el2, d_el, pl;  // pl = sum_j p LeakyReLU'(z) (kExact only)
+    float el2, ar2[VEC], d_el, pl;  // pl = sum_j p LeakyReLU'(z) (kExact only)
     u32x4 V[U];
-    float Er[U];
     __device__ void init(const Args& a, const Ctx& c) {
-        el2 = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        float x[VEC], al[VEC];
+        load_row<G>(a.x, c, x);
+        load_attention<G>(a.a_l, c, kLog2e, al);
+        load_attention<G>(a.a_r, c, kLog2e, ar2);
+        el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
         d_el = 0.f;
         pl = 0.f;
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        Er[u] = gather_f32(a.node_b, a, c, j);
-    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float z = el2 + Er[u];
+            const float z = el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - this->lse2) : 0.f;
             const float slope = z > 0.f ? 1.f : a.neg_slope;
             if constexpr (kExact) {
@@ -636,12 +667,20 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
             a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        d_el += a.part_s0[(size_t)chunk * a.H + c.h];
+        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
         if constexpr (kExact) {
-            pl += a.part_s1[(size_t)chunk * a.H + c.h];
-            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+            P.s1 = a.part_s1[(size_t)chunk * a.H + c.h];
+            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
+        }
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
+        d_el = fmaf(w, P.s0, d_el);
+        if constexpr (kExact) {
+            pl = fmaf(w, P.s1, pl);
+            this->dsum = fmaf(w, P.s2, this->dsum);
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
@@ -666,7 +705,9 @@ template <class G, int U> struct GatBwdCol {
     f32x4 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, wh);
-        er2 = c.active ? a.node_b[(size_t)c.node * a.H + c.h] : 0.f;
+        float ar[VEC];
+        load_attention<G>(a.a_r, c, kLog2e, ar);
+        er2 = head_sum<G::LPH>(dotv<VEC>(wh, ar), a.lph);
         d_er = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dwh[i] = 0.f;
@@ -699,13 +740,16 @@ template <class G, int U> struct GatBwdCol {
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dwh);
         if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_er;
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        float t[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) dwh[i] += t[i];
-        d_er += a.part_s0[(size_t)chunk * a.H + c.h];
+        for (int i = 0; i < VEC; ++i) dwh[i] = fmaf(w, P.v0[i], dwh[i]);
+        d_er = fmaf(w, P.s0, d_er);
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.active) return;
@@ -724,30 +768,32 @@ template <class G, int U> struct GatBwdCol {
 // =============================================================================================
 // AGNN (Sec. 5.1): s_ij = beta * cos(h_i, h_j); aggregated value is the raw feature row
 // =============================================================================================
+// 1 / max(|h|, eps) from the squared norm.  The norm of a neighbour is taken from its gathered row
+// (one more dot product over the head's lanes) instead of being gathered as a 4-byte scalar, which
+// would cost a whole memory sector per edge.
+__device__ inline float inv_norm(float n2, float inv_eps) { return fminf(__builtin_amdgcn_rsqf(n2), inv_eps); }
+
 template <class G, int U> struct AgnnFwd {
     static constexpr int VEC = G::VEC;
     float x2[VEC];
     SoftmaxAcc<G, U> sm;
     u32x4 V[U];
-    float Rn[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, x2);
-        const float rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        const float rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(x2, x2), a.lph), a.inv_eps);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        Rn[u] = gather_f32(a.node_a, a, c, j);
-    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
-            s[u] = head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * Rn[u];
+            const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
+            s[u] = head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * rnj;
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -755,7 +801,8 @@ template <class G, int U> struct AgnnFwd {
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void add_partial(const Args& a, const Ctx& c, int chunk) { sm.add_partial(a, c, chunk); }
+    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
 
@@ -766,26 +813,23 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     float xh[VEC], ga[VEC], px[VEC];  // px = sum_j p xhat_j (kExact only)
     float rn, dbeta, pc;              // pc = sum_j p cos_ij (kExact only)
     u32x4 V[U];
-    float Rn[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, xh);
-        rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(xh, xh), a.lph), a.inv_eps);
         dbeta = 0.f;
         pc = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; px[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        Rn[u] = gather_f32(a.node_a, a, c, j);
-    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
-            const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * Rn[u];
+            const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
+            const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * rnj;
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - this->lse2) : 0.f;
             if constexpr (kExact) {
@@ -793,13 +837,13 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
                 this->dsum += t;
                 dbeta = fmaf(t, cs, dbeta);
                 pc = fmaf(p, cs, pc);
-                const float w1 = t * Rn[u], w2 = p * Rn[u];
+                const float w1 = t * rnj, w2 = p * rnj;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { ga[i] = fmaf(w1, vf[i], ga[i]); px[i] = fmaf(w2, vf[i], px[i]); }
             } else {
                 const float ds = p * (dp - this->delta);
                 dbeta = fmaf(ds, cs, dbeta);
-                const float w = ds * Rn[u];
+                const float w = ds * rnj;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, vf[i], ga[i]);
             }
@@ -828,19 +872,26 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             }
         }
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        float t[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) ga[i] += t[i];
-        dbeta += a.part_s0[(size_t)chunk * a.H + c.h];
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
         if constexpr (kExact) {
-            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t);
+            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
+            P.s1 = a.part_s1[(size_t)chunk * a.H + c.h];
+            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
+        }
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) px[i] += t[i];
-            pc += a.part_s1[(size_t)chunk * a.H + c.h];
-            this->dsum += a.part_s2[(size_t)chunk * a.H + c.h];
+        for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, P.v0[i], ga[i]);
+        dbeta = fmaf(w, P.s0, dbeta);
+        if constexpr (kExact) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) px[i] = fmaf(w, P.v1[i], px[i]);
+            pc = fmaf(w, P.s1, pc);
+            this->dsum = fmaf(w, P.s2, this->dsum);
         }
     }
     __device__ void finalize(const Args& a, const Ctx& c) {
@@ -874,7 +925,7 @@ template <class G, int U> struct AgnnBwdCol {
     f32x4 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, hj);
-        rn = c.active ? a.node_a[(size_t)c.node * a.H + c.h] : 0.f;
+        rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph), a.inv_eps);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
     }
@@ -910,13 +961,15 @@ template <class G, int U> struct AgnnBwdCol {
         store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, val);
         store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, ga);
     }
-    __device__ void add_partial(const Args& a, const Ctx& c0, int chunk) {
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
         const PartialIndex c(c0);
-        float t0[VEC], t1[VEC];
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, t0);
-        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, t1);
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) { val[i] += t0[i]; ga[i] += t1[i]; }
+        for (int i = 0; i < VEC; ++i) { val[i] = fmaf(w, P.v0[i], val[i]); ga[i] = fmaf(w, P.v1[i], ga[i]); }
     }
     // all lanes of the wave must call this (it reduces over the head's lanes)
     __device__ void finalize(const Args& a, const Ctx& c) {
@@ -1062,42 +1115,21 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     const Ctx c = make_ctx<G>(a, lane, node);
     PassT<G, U> p;
     p.init(a, c);
-#pragma unroll 8
-    for (int ch = c0 + c.g; ch < c1; ch += G::EPW) p.add_partial(a, c, ch);
+    // kMergeBatch chunks per edge slot are loaded before any is folded in (absent ones read the row's
+    // first chunk and are masked), so the loop has no per-lane branch and its loads overlap
+    constexpr int kMergeBatch = 8;
+    for (int base = c0; base < c1; base += G::EPW * kMergeBatch) {
+        PartialRegs<G::VEC> P[kMergeBatch];
+#pragma unroll
+        for (int m = 0; m < kMergeBatch; ++m) {
+            const int ch = base + m * G::EPW + c.g;
+            p.load_partial(a, c, ch < c1 ? ch : c0, P[m]);
+        }
+#pragma unroll
+        for (int m = 0; m < kMergeBatch; ++m) p.fold_partial(P[m], base + m * G::EPW + c.g < c1);
+    }
     p.combine_slots(a, c);
     p.finalize(a, c);
-}
-
-// Per-node score terms: GAT el = a_l.Wh, er = a_r.Wh (times log2 e); AGNN 1 / max(|h|, eps).
-// One edge slot (LPE lanes) per node.
-template <class G, bool IS_GAT>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_node_terms(const Args a) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int g = lane / G::LPE;
-    const int node = (blockIdx.x * kWavesPerBlock + wave) * G::EPW + g;
-    const bool live = node < a.n_nodes;
-    const Ctx c = make_ctx<G>(a, lane, live ? node : 0);
-    float x[G::VEC];
-    load_row<G>(a.x, c, x);
-    if (IS_GAT) {
-        float al[G::VEC], ar[G::VEC];
-        if (c.active) {
-            load_f32<G::VEC>(a.a_l + c.f0, al);
-            load_f32<G::VEC>(a.a_r + c.f0, ar);
-        } else {
-#pragma unroll
-            for (int i = 0; i < G::VEC; ++i) { al[i] = 0.f; ar[i] = 0.f; }
-        }
-        const float el = head_sum<G::LPH>(dotv<G::VEC>(x, al), a.lph);
-        const float er = head_sum<G::LPH>(dotv<G::VEC>(x, ar), a.lph);
-        if (live && c.head0) {
-            a.node_a[(size_t)node * a.H + c.h] = el * kLog2e;
-            a.node_b[(size_t)node * a.H + c.h] = er * kLog2e;
-        }
-    } else {
-        const float n2 = head_sum<G::LPH>(dotv<G::VEC>(x, x), a.lph);
-        if (live && c.head0) a.node_a[(size_t)node * a.H + c.h] = 1.f / fmaxf(sqrtf(n2), a.eps);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1116,17 +1148,23 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
     float sl[G::VEC], sr[G::VEC];
 #pragma unroll
     for (int i = 0; i < G::VEC; ++i) { sl[i] = 0.f; sr[i] = 0.f; }
-    for (int base = (blockIdx.x * kWavesPerBlock + wave) * G::EPW; base < a.n_nodes; base += waves * G::EPW) {
-        const int v = base + lane / G::LPE;
-        if (v < a.n_nodes) {
-            const Ctx c = make_ctx<G>(a, lane, v);
-            if (c.active) {
-                float x[G::VEC];
-                load_row<G>(a.x, c, x);
-                const float del = a.d_el[(size_t)v * a.H + c.h], der = a.d_er[(size_t)v * a.H + c.h];
+    constexpr int B = 4;  // node rows requested per edge slot before the first is used
+    const int stride = waves * G::EPW;
+    for (int base = (blockIdx.x * kWavesPerBlock + wave) * G::EPW; base < a.n_nodes; base += stride * B) {
+        float x[B][G::VEC], del[B], der[B];
 #pragma unroll
-                for (int i = 0; i < G::VEC; ++i) { sl[i] = fmaf(del, x[i], sl[i]); sr[i] = fmaf(der, x[i], sr[i]); }
-            }
+        for (int k = 0; k < B; ++k) {
+            const int v = base + k * stride + lane / G::LPE;
+            const bool live = v < a.n_nodes;
+            const Ctx c = make_ctx<G>(a, lane, live ? v : 0);
+            load_row<G>(a.x, c, x[k]);
+            del[k] = live ? a.d_el[(size_t)c.node * a.H + c.h] : 0.f;
+            der[k] = live ? a.d_er[(size_t)c.node * a.H + c.h] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < B; ++k) {
+#pragma unroll
+            for (int i = 0; i < G::VEC; ++i) { sl[i] = fmaf(del[k], x[k][i], sl[i]); sr[i] = fmaf(der[k], x[k][i], sr[i]); }
         }
     }
 #pragma unroll
@@ -1148,20 +1186,18 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
 
 __global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
                                                          float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
-    // thread t: feature t % HD of (a_l | a_r); 4 interleaved partial sums give the loads some overlap
+    // thread t: feature t % HD of (a_l | a_r); partials are loaded 16 at a time, then added in order
     for (int t = threadIdx.x; t < 2 * HD; t += blockDim.x) {
         const int which = t / HD, f = t % HD;
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-        int b = 0;
-#pragma unroll 8
-        for (; b + 3 < nblocks; b += 4) {
-            s0 += partial[((size_t)(b + 0) * 2 + which) * HD + f];
-            s1 += partial[((size_t)(b + 1) * 2 + which) * HD + f];
-            s2 += partial[((size_t)(b + 2) * 2 + which) * HD + f];
-            s3 += partial[((size_t)(b + 3) * 2 + which) * HD + f];
+        float sum = 0.f;
+        for (int b = 0; b < nblocks; b += 16) {
+            float v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v[k] = b + k < nblocks ? partial[((size_t)(b + k) * 2 + which) * HD + f] : 0.f;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) sum += v[k];
         }
-        for (; b < nblocks; ++b) s0 += partial[((size_t)b * 2 + which) * HD + f];
-        (which ? d_a_r : d_a_l)[f] = (s0 + s1) + (s2 + s3);
+        (which ? d_a_r : d_a_l)[f] = sum;
     }
 }
 
