@@ -28,7 +28,12 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the files
 # under profiles/ named after the kernel and workload); bytes per launch, None where not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB per launch, see profiles/{gt_cfg5,agnn_cfg4,gat_cfg3}_kernels.md
+    ("cfg5", "fwd"): 123947976742, ("cfg5", "bwd_row"): 127038693664, ("cfg5", "bwd_col"): 141934625417,
+    ("cfg4", "fwd"): 3487725190, ("cfg4", "bwd_row"): 4058192884, ("cfg4", "bwd_col"): 5937769964,
+    ("cfg3", "fwd"): 475563043, ("cfg3", "bwd_row"): 590671964, ("cfg3", "bwd_col"): 760792584,
+}
 
 DESCRIPTIONS = {
     "cfg1": "cfg1: GT fp32, Chung-Lu power-law graph N=2,708 (exponent 2.5) + self-loops, H=1 D=64",
