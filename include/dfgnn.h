@@ -21,6 +21,7 @@
  *  - Every function returns a dfgnn_status; nothing throws or aborts across this boundary.  On any
  *    error no output buffer has defined contents.  dfgnn_last_error() gives a thread-local detail text.
  *  - Outputs are overwritten, never accumulated into.
+ *  - A graph with N = 0 is legal: layer calls then touch no node tensor (their pointers may be NULL).
  */
 #ifndef DFGNN_H
 #define DFGNN_H

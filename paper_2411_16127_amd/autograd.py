@@ -1,0 +1,67 @@
+"""torch.autograd wrapper of the fused layer: the graph-convolution call a model's nn.Module makes
+(the "graph convolution API" of Sec. 3).  Argument marshalling only: forward and backward run in
+libdfgnn through the C ABI; saved tensors are the inputs, the output and the softmax statistics."""
+from __future__ import annotations
+
+import torch
+
+from .binding import Graph, Layer
+
+
+class _FusedConv(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, graph: Graph, layer: Layer, x, k, v, a_l, a_r):
+        x, k, v = (None if t is None else t.contiguous() for t in (x, k, v))
+        out, row_max, row_sum = graph.forward(layer, x, k, v, a_l, a_r)
+        ctx.graph, ctx.layer = graph, layer
+        ctx.save_for_backward(*(t for t in (x, k, v, a_l, a_r, out, row_max, row_sum) if t is not None))
+        ctx.has = tuple(t is not None for t in (x, k, v, a_l, a_r))
+        return out
+
+    @staticmethod
+    def backward(ctx, d_out):
+        saved = list(ctx.saved_tensors)
+        x, k, v, a_l, a_r = (saved.pop(0) if h else None for h in ctx.has)
+        out, row_max, row_sum = saved
+        g = ctx.graph.backward(ctx.layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out.contiguous())
+        return (None, None, g["d_x"], g.get("d_k"), g.get("d_v"), g.get("d_a_l"), g.get("d_a_r"))
+
+
+def gt_conv(graph: Graph, q, k, v, scale=None):
+    """Graph-transformer convolution: softmax over in-neighbours of scale * q_i.k_j, applied to v.  [N,H,D]."""
+    H, D = q.shape[1], q.shape[2]
+    layer = Layer("gt", H, D, dtype="bf16" if q.dtype == torch.bfloat16 else "f32",
+                  scale=float(D) ** -0.5 if scale is None else float(scale))
+    return _FusedConv.apply(graph, layer, q, k, v, None, None)
+
+
+def gat_conv(graph: Graph, wh, a_l, a_r, neg_slope: float = 0.2):
+    """GAT convolution on projected features Wh [N,H,D] with attention vectors a_l, a_r [H,D] (fp32)."""
+    H, D = wh.shape[1], wh.shape[2]
+    layer = Layer("gat", H, D, dtype="bf16" if wh.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    return _FusedConv.apply(graph, layer, wh, None, None, a_l.contiguous(), a_r.contiguous())
+
+
+class _AgnnConv(torch.autograd.Function):
+    """AGNN needs the gradient of the scalar beta, which is a layer field rather than a tensor argument."""
+
+    @staticmethod
+    def forward(ctx, graph: Graph, h, beta, eps: float):
+        layer = Layer("agnn", h.shape[1], h.shape[2], dtype="bf16" if h.dtype == torch.bfloat16 else "f32",
+                      scale=float(beta.detach().float().cpu()), eps=eps)
+        h = h.contiguous()
+        out, row_max, row_sum = graph.forward(layer, h)
+        ctx.graph, ctx.layer = graph, layer
+        ctx.save_for_backward(h, out, row_max, row_sum, beta)
+        return out
+
+    @staticmethod
+    def backward(ctx, d_out):
+        h, out, row_max, row_sum, beta = ctx.saved_tensors
+        g = ctx.graph.backward(ctx.layer, h, None, None, None, None, out, row_max, row_sum, d_out.contiguous())
+        return None, g["d_x"], g["d_scale"].to(beta.dtype).reshape(beta.shape), None
+
+
+def agnn_conv(graph: Graph, h, beta, eps: float = 1e-12):
+    """AGNN convolution: softmax of beta * cos(h_i, h_j), applied to h.  beta: 0-d or 1-element tensor."""
+    return _AgnnConv.apply(graph, h, beta, eps)

@@ -272,6 +272,7 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
     const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT;
+    if (graph->N == 0) return DFGNN_OK;  // nothing to compute; node tensors have no elements and may be NULL
     DFGNN_REQUIRE(x && out && row_max && row_sum, DFGNN_EINVAL, "x / out / row_max / row_sum is NULL");
     DFGNN_REQUIRE(!gt || (k && v), DFGNN_EINVAL, "GT needs k and v");
     DFGNN_REQUIRE(gt || (!k && !v), DFGNN_EINVAL, "k and v must be NULL unless the model is GT");
@@ -284,8 +285,6 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, forward needs %zu",
                   workspace_bytes, W.total);
-    if (graph->N == 0) return DFGNN_OK;
-
     Args a{};
     fill_common(a, graph, layer, geo);
     a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
@@ -306,6 +305,14 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
     const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN;
+    if (graph->N == 0) {  // no nodes: node tensors have no elements and may be NULL; parameter gradients are zero
+        if (gat && d_a_l && d_a_r) {
+            DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
+            DFGNN_HIP(hipMemsetAsync(d_a_r, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
+        }
+        if (agnn && d_scale) DFGNN_HIP(hipMemsetAsync(d_scale, 0, sizeof(float), (hipStream_t)stream));
+        return DFGNN_OK;
+    }
     DFGNN_REQUIRE(x && out && row_max && row_sum && d_out && d_x, DFGNN_EINVAL,
                   "x / out / row_max / row_sum / d_out / d_x is NULL");
     DFGNN_REQUIRE(!gt || (k && v && d_k && d_v), DFGNN_EINVAL, "GT needs k, v, d_k and d_v");
@@ -324,14 +331,6 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, backward needs %zu",
                   workspace_bytes, W.total);
     hipStream_t st = (hipStream_t)stream;
-    if (graph->N == 0) {
-        if (gat) {
-            DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, st));
-            DFGNN_HIP(hipMemsetAsync(d_a_r, 0, sizeof(float) * layer->H * layer->D, st));
-        }
-        if (agnn) DFGNN_HIP(hipMemsetAsync(d_scale, 0, sizeof(float), st));
-        return DFGNN_OK;
-    }
 
     Args a{};
     fill_common(a, graph, layer, geo);
