@@ -127,6 +127,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--super-threshold", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
+    ap.add_argument("--no-short-rows", action="store_true", help="ablation: one wavefront for every row below the super threshold")
     ap.add_argument("--cpu-edges", type=int, default=0, help="edges in the CPU-baseline sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-kernel HIP events")
@@ -160,7 +161,7 @@ def main() -> int:
     feats = make_features(w, graph.n)
     log(f"{w.name}: N={graph.n} E={graph.nnz} generated in {time.perf_counter() - t0:.1f} s")
 
-    sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges)
+    sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges, 1 if args.no_short_rows else 0)
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])

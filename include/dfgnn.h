@@ -55,8 +55,14 @@ typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
 typedef struct {
     int32_t super_threshold;
     int32_t chunk_edges;
-    int32_t reserved[6]; /* must be 0 */
+    int32_t flags;       /* DFGNN_SCHED_* bits; 0 = default behaviour */
+    int32_t reserved[5]; /* must be 0 */
 } dfgnn_sched_params;
+
+/* Ablation switch: rows shorter than one load round of a wavefront are normally mapped one per
+ * edge slot (several rows per wavefront); with this bit every row below super_threshold gets a whole
+ * wavefront.  Results are the same up to rounding order. */
+#define DFGNN_SCHED_NO_SHORT_ROWS 1
 
 /* One layer call's model description. */
 typedef struct {

@@ -30,7 +30,8 @@ class DfgnnError(RuntimeError):
 
 
 class _CSched(ctypes.Structure):
-    _fields_ = [("super_threshold", ctypes.c_int32), ("chunk_edges", ctypes.c_int32), ("reserved", ctypes.c_int32 * 6)]
+    _fields_ = [("super_threshold", ctypes.c_int32), ("chunk_edges", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 5)]
 
 
 class _CLayer(ctypes.Structure):
@@ -43,9 +44,10 @@ class _CLayer(ctypes.Structure):
 class SchedParams:
     super_threshold: int = 0  # 0 = library default
     chunk_edges: int = 0
+    flags: int = 0            # 1 = no short-row mapping (ablation)
 
     def _c(self) -> _CSched:
-        return _CSched(self.super_threshold, self.chunk_edges, (ctypes.c_int32 * 6)())
+        return _CSched(self.super_threshold, self.chunk_edges, self.flags, (ctypes.c_int32 * 5)())
 
 
 @dataclass

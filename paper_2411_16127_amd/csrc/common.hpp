@@ -62,7 +62,7 @@ struct KernelTimer {
 // The opaque handle of the ABI.
 struct dfgnn_graph {
     int64_t N, E;
-    int T, C;
+    int T, C, flags;
     const int32_t* indptr;
     const int32_t* indices;
     int32_t *row_order, *col_order, *t_indptr, *t_indices, *t_eid;

@@ -358,7 +358,7 @@ static ScratchLayout scratch_layout(int64_t N, int64_t E, int T) {
 // and short enough that the chunks of the super rows alone can fill the GPU (256 CUs x 4 SIMDs x
 // several wavefronts): chunk_edges = E / 16384 rounded up to a power of two, clamped to [64, 512];
 // super_threshold = 2 * chunk_edges.
-static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, int* C) {
+static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, int* C, int* flags = nullptr) {
     int c = 64;
     while (c < 512 && (int64_t)c * 16384 < E) c <<= 1;
     *C = c;
@@ -367,8 +367,11 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
         for (int r : sched->reserved) DFGNN_REQUIRE(r == 0, DFGNN_EINVAL, "dfgnn_sched_params.reserved must be zero");
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
+        DFGNN_REQUIRE((sched->flags & ~DFGNN_SCHED_NO_SHORT_ROWS) == 0, DFGNN_EINVAL, "unknown scheduling flag 0x%x",
+                      sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;
+        if (flags) *flags = sched->flags;
     }
     if (*T == 0) *T = *C > (1 << 29) ? *C : 2 * *C;
     return DFGNN_OK;
@@ -448,8 +451,8 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     DFGNN_REQUIRE(meta_bytes >= need_meta, DFGNN_EWORKSPACE, "metadata buffer has %zu bytes, needs %zu", meta_bytes, need_meta);
     DFGNN_REQUIRE(scratch_bytes >= need_scratch, DFGNN_EWORKSPACE, "scratch buffer has %zu bytes, needs %zu",
                   scratch_bytes, need_scratch);
-    int T, C;
-    rc = resolve_params(sched, E, &T, &C);
+    int T, C, flags = 0;
+    rc = resolve_params(sched, E, &T, &C, &flags);
     if (rc != DFGNN_OK) return rc;
 
     hipStream_t st = (hipStream_t)stream;
@@ -459,7 +462,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     char* scratch = (char*)d_scratch;
 
     dfgnn_graph g{};
-    g.N = N; g.E = E; g.T = T; g.C = C;
+    g.N = N; g.E = E; g.T = T; g.C = C; g.flags = flags;
     g.indptr = d_indptr; g.indices = d_indices;
     g.row_order = (int*)(meta + M.row_order);
     g.col_order = (int*)(meta + M.col_order);

@@ -120,7 +120,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     // slot-per-row kernel; they are the tail of the degree-ordered list
     const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
     int64_t first_small = g->N;
-    if (G::EPW > 1) {
+    if (G::EPW > 1 && !(g->flags & DFGNN_SCHED_NO_SHORT_ROWS)) {
         int lg = 0;
         while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
         first_small = bucket[33 - lg];
