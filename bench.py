@@ -65,6 +65,9 @@ def algorithmic_bytes(w, graph):
                  "bwd_col": (2 * R + 3 * s + 4, 3 * R + s + 4)},
     }[w.model]
     res = {name: pe * graph.nnz + pn * graph.n for name, (pe, pn) in per.items()}
+    # dense-tile kernels for batches of small graphs do the work of the same passes in one launch each
+    res["dense_fwd"] = res["fwd"]
+    res["dense_bwd"] = res["bwd_row"] + res["bwd_col"]
     if w.model == "gat":
         res["node_terms"] = graph.n * (R + 2 * s)
         res["param_reduce"] = graph.n * (R + 2 * s)
@@ -128,6 +131,11 @@ def main() -> int:
     ap.add_argument("--super-threshold", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
     ap.add_argument("--no-short-rows", action="store_true", help="ablation: one wavefront for every row below the super threshold")
+    ap.add_argument("--no-dense-batch", action="store_true", help="ablation: general kernels also for batches of small graphs")
+    ap.add_argument("--force-dense-batch", action="store_true", help="dense-tile batch kernels whenever they apply")
+    ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
+                    help="override a field of the workload (e.g. n_graphs=2048, n_min=60, density=0.5, H=4, D=32); "
+                         "the result is then a variant, named in config.workload")
     ap.add_argument("--cpu-edges", type=int, default=0, help="edges in the CPU-baseline sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-kernel HIP events")
@@ -155,13 +163,19 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_each_way": src.numel() * 4, "launches": 5}))
         return 0
-    w = make_workload(args.workload)
+    overrides = {}
+    for item in args.set:
+        key, val = item.split("=", 1)
+        overrides[key] = type(getattr(make_workload(args.workload), key))(val)
+    w = make_workload(args.workload, **overrides)
     t0 = time.perf_counter()
     graph = make_graph(w)
     feats = make_features(w, graph.n)
     log(f"{w.name}: N={graph.n} E={graph.nnz} generated in {time.perf_counter() - t0:.1f} s")
 
-    sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges, 1 if args.no_short_rows else 0)
+    sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges,
+                              (1 if args.no_short_rows else 0) | (2 if args.no_dense_batch else 0) |
+                              (4 if args.force_dense_batch else 0))
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])
@@ -173,7 +187,7 @@ def main() -> int:
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    g = dfgnn.Graph(graph.indptr, graph.indices, sched)
+    g = dfgnn.Graph(graph.indptr, graph.indices, sched, batch_ptr=graph.batch_ptr)
     torch.cuda.synchronize()
     preprocess_ms = (time.perf_counter() - t0) * 1e3
     T, C = g.query("n_super_threshold"), g.query("n_chunk_edges")
@@ -262,7 +276,7 @@ def main() -> int:
         "value": round(gedges, 4), "unit": "GEdges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
-        "config": {"workload": DESCRIPTIONS[w.name], "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
+        "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
                    "super_threshold": T, "chunk_edges": C, "stands_in_for": w.stands_in_for},
         "roofline": roofline,
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "preprocess_ms": round(preprocess_ms, 2),

@@ -63,6 +63,10 @@ typedef struct {
  * edge slot (several rows per wavefront); with this bit every row below super_threshold gets a whole
  * wavefront.  Results are the same up to rounding order. */
 #define DFGNN_SCHED_NO_SHORT_ROWS 1
+/* Ablation switch: do not use the dense-tile kernels for batches of small graphs (dfgnn_graph_set_batch). */
+#define DFGNN_SCHED_NO_DENSE_BATCH 2
+/* Use the dense-tile kernels whenever they apply, also below the edges-per-graph count from which they pay. */
+#define DFGNN_SCHED_FORCE_DENSE_BATCH 4
 
 /* One layer call's model description. */
 typedef struct {
@@ -94,7 +98,8 @@ typedef enum {
     DFGNN_Q_N_SUPER_ROWS = 9,  /* count only (d_ptr = NULL) */
     DFGNN_Q_N_SUPER_COLS = 10, /* count only */
     DFGNN_Q_SUPER_THRESHOLD = 11, /* count only: the super_threshold in use */
-    DFGNN_Q_CHUNK_EDGES = 12      /* count only: the chunk_edges in use */
+    DFGNN_Q_CHUNK_EDGES = 12,     /* count only: the chunk_edges in use */
+    DFGNN_Q_BATCH_DENSE = 13      /* count only: 1 if the dense-tile batch kernels apply to this graph */
 } dfgnn_query;
 
 const char* dfgnn_status_string(int status);
@@ -127,6 +132,22 @@ int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d
                        const dfgnn_sched_params* sched, void* d_meta, size_t meta_bytes, void* d_scratch,
                        size_t scratch_bytes, void* stream);
 int dfgnn_graph_destroy(dfgnn_graph* graph);
+
+/*
+ * Batched small graphs (the batch-graph workloads of Sec. 5.1: many small graphs processed as one
+ * block-diagonal graph).  d_batch_ptr [n_graphs + 1] (device int32, caller-owned, must stay valid while
+ * the handle is used) holds the first node of every graph: graph b owns nodes
+ * [batch_ptr[b], batch_ptr[b+1]).  The call checks on the GPU that the pointer array starts at 0, ends at
+ * N and does not decrease, and that no edge connects two graphs (EINVAL otherwise), and records for each
+ * row the adjacency bits inside its graph.  If every graph has at most 64 nodes and no repeated edge,
+ * and the batch averages at least 400 edges per graph (below that the general kernels are faster),
+ * GT layers in bf16 with D = 16 or 32 are then computed by dense-tile kernels: one wavefront per
+ * (graph, head) stages the head's Q, K, V once into LDS and forms the masked score block with MFMA, so
+ * every node row is read once per graph instead of once per edge; results agree with the general path to
+ * bf16 rounding.  Other layers, and graphs that do not qualify, use the general kernels unchanged.
+ * Passing (NULL, 0) forgets the batch structure.  Synchronises `stream`.
+ */
+int dfgnn_graph_set_batch(dfgnn_graph* graph, const int32_t* d_batch_ptr, int64_t n_graphs, void* stream);
 int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, int64_t* count);
 
 /*

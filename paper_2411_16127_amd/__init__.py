@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     graph_meta_bytes,
     graph_create,
     graph_destroy,
+    graph_set_batch,
     graph_query,
     workspace_bytes,
     forward,

@@ -19,7 +19,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 QUERY = {
     "row_order": 0, "row_chunk_ptr": 1, "row_chunks": 2, "t_indptr": 3, "t_indices": 4, "t_eid": 5,
     "col_order": 6, "col_chunk_ptr": 7, "col_chunks": 8, "n_super_rows": 9, "n_super_cols": 10,
-    "n_super_threshold": 11, "n_chunk_edges": 12,
+    "n_super_threshold": 11, "n_chunk_edges": 12, "n_batch_dense": 13,
 }
 
 
@@ -44,7 +44,7 @@ class _CLayer(ctypes.Structure):
 class SchedParams:
     super_threshold: int = 0  # 0 = library default
     chunk_edges: int = 0
-    flags: int = 0            # 1 = no short-row mapping (ablation)
+    flags: int = 0            # bits: 1 = no short-row mapping, 2 = no dense-tile batch kernels, 4 = dense-tile kernels whenever they apply
 
     def _c(self) -> _CSched:
         return _CSched(self.super_threshold, self.chunk_edges, self.flags, (ctypes.c_int32 * 5)())
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_graph_meta_bytes.argtypes = [i64, i64, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, vp, sz, vp, sz, vp]
         L.dfgnn_graph_destroy.argtypes = [vp]
+        L.dfgnn_graph_set_batch.argtypes = [vp, vp, i64, vp]
         L.dfgnn_graph_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
@@ -96,7 +97,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
-        for name in ("dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
+        for name in ("dfgnn_graph_set_batch", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -162,6 +163,10 @@ def graph_create(N: int, E: int, d_indptr, d_indices, sched: Optional[SchedParam
     return handle
 
 
+def graph_set_batch(handle, d_batch_ptr, n_graphs: int, stream=None) -> None:
+    _check(lib().dfgnn_graph_set_batch(handle, _ptr(d_batch_ptr), n_graphs, _stream(stream)), "dfgnn_graph_set_batch")
+
+
 def graph_destroy(handle) -> None:
     _check(lib().dfgnn_graph_destroy(handle), "dfgnn_graph_destroy")
 
@@ -216,7 +221,8 @@ def timing_collect(max_labels: int = 64) -> Dict[str, Tuple[float, int]]:
 class Graph:
     """Owns the device buffers of one graph (CSR arrays, metadata) and its library handle."""
 
-    def __init__(self, indptr, indices, sched: Optional[SchedParams] = None, device="cuda:0", stream=None):
+    def __init__(self, indptr, indices, sched: Optional[SchedParams] = None, device="cuda:0", stream=None,
+                 batch_ptr=None):
         import torch
         self.device = torch.device(device)
         self.indptr = torch.as_tensor(indptr, dtype=torch.int32).to(self.device).contiguous()
@@ -230,6 +236,10 @@ class Graph:
         self.handle = graph_create(self.N, self.E, self.indptr, self.indices, sched, self.meta, meta_b, scratch,
                                    scratch_b, stream)
         del scratch
+        self.batch_ptr = None
+        if batch_ptr is not None:
+            self.batch_ptr = torch.as_tensor(batch_ptr, dtype=torch.int32).to(self.device).contiguous()
+            graph_set_batch(self.handle, self.batch_ptr, int(self.batch_ptr.numel() - 1), stream)
         self._ws: Dict[tuple, object] = {}
 
     def close(self) -> None:

@@ -221,7 +221,7 @@ static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32
 // ------------------------------------------------------------------------------------------------
 // scheduler kernels
 // ------------------------------------------------------------------------------------------------
-enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
+enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_BATCH = 9, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
 
 __global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -329,6 +329,7 @@ MetaLayout meta_layout(int64_t N, int64_t E, int T, int C) {
     L.col_chunk_ptr = take(super_capacity(E, T) + 1);
     L.col_chunks = take(3 * chunk_capacity(E, T, C));
     L.counters = take(CNT_TOTAL);
+    L.adj_mask = take(2 * N);
     L.total = off;
     return L;
 }
@@ -367,7 +368,7 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
         for (int r : sched->reserved) DFGNN_REQUIRE(r == 0, DFGNN_EINVAL, "dfgnn_sched_params.reserved must be zero");
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
-        DFGNN_REQUIRE((sched->flags & ~DFGNN_SCHED_NO_SHORT_ROWS) == 0, DFGNN_EINVAL, "unknown scheduling flag 0x%x",
+        DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH)) == 0, DFGNN_EINVAL, "unknown scheduling flag 0x%x",
                       sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;
@@ -474,6 +475,8 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     g.col_chunk_ptr = (int*)(meta + M.col_chunk_ptr);
     g.col_chunks = (int*)(meta + M.col_chunks);
     int* d_counters = (int*)(meta + M.counters);
+    g.counters = d_counters;
+    g.adj_mask = (unsigned long long*)(meta + M.adj_mask);
 
     const int tpb = 256;
     DFGNN_HIP(hipMemsetAsync(d_counters, 0, CNT_TOTAL * sizeof(int), st));
@@ -524,6 +527,92 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     return DFGNN_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// block-diagonal batches of small graphs
+// ------------------------------------------------------------------------------------------------
+namespace dfgnn {
+enum { BATCH_BAD_PTR = 1, BATCH_CROSS_EDGE = 2, BATCH_TOO_LARGE = 4, BATCH_DUPLICATE = 8 };
+
+__global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int n_nodes, int max_nodes, int* flags) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g > n_graphs) return;
+    int bad = 0;
+    const int p = bp[g];
+    if (g == 0 && p != 0) bad |= BATCH_BAD_PTR;
+    if (g == n_graphs && p != n_nodes) bad |= BATCH_BAD_PTR;
+    if (p < 0 || p > n_nodes) bad |= BATCH_BAD_PTR;
+    if (g < n_graphs) {
+        const int sz = bp[g + 1] - p;
+        if (sz < 0) bad |= BATCH_BAD_PTR;
+        if (sz > max_nodes) bad |= BATCH_TOO_LARGE;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+// one thread per node: the adjacency bits of its row relative to the first node of its graph
+__global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const int* __restrict__ indptr,
+                              const int* __restrict__ indices, int n_nodes, int max_nodes,
+                              unsigned long long* __restrict__ adj_mask, int* flags) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_nodes) return;
+    int lo = 0, hi = n_graphs;  // last graph whose first node is <= i
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (bp[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int first = bp[lo], last = bp[lo + 1];
+    const bool small = last - first <= max_nodes;
+    unsigned long long mask = 0ull;
+    int bad = 0;
+    for (int e = indptr[i]; e < indptr[i + 1]; ++e) {
+        const int j = indices[e];
+        if (j < first || j >= last) { bad |= BATCH_CROSS_EDGE; continue; }
+        if (small) {
+            const unsigned long long bit = 1ull << (j - first);
+            if (mask & bit) bad |= BATCH_DUPLICATE;
+            mask |= bit;
+        }
+    }
+    adj_mask[i] = mask;
+    if (bad) atomicOr(flags, bad);
+}
+}  // namespace dfgnn
+
+extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr, int64_t n_graphs, void* stream) {
+    clear_error();
+    DFGNN_REQUIRE(g != nullptr, DFGNN_EINVAL, "graph is NULL");
+    g->batch_dense = false;
+    g->batch_ptr = nullptr;
+    g->n_graphs = 0;
+    if (d_batch_ptr == nullptr && n_graphs == 0) return DFGNN_OK;  // forget the batch structure
+    DFGNN_REQUIRE(d_batch_ptr != nullptr && n_graphs >= 0 && n_graphs <= g->N + 1, DFGNN_EINVAL,
+                  "batch_ptr is NULL or n_graphs = %lld is out of range", (long long)n_graphs);
+    DFGNN_REQUIRE(n_graphs > 0 || g->N == 0, DFGNN_EINVAL, "a graph with nodes needs at least one batch entry");
+    hipStream_t st = (hipStream_t)stream;
+    int* flags = g->counters + CNT_BATCH;
+    const int tpb = 256;
+    const int max_nodes = 64;
+    DFGNN_HIP(hipMemsetAsync(flags, 0, sizeof(int), st));
+    hipLaunchKernelGGL(k_batch_check_ptr, dim3((unsigned)((n_graphs + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, d_batch_ptr,
+                       (int)n_graphs, (int)g->N, max_nodes, flags);
+    int host_flags = 0;
+    DFGNN_HIP(hipMemcpyAsync(&host_flags, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+    DFGNN_HIP(hipStreamSynchronize(st));
+    DFGNN_REQUIRE(!(host_flags & BATCH_BAD_PTR), DFGNN_EINVAL,
+                  "batch_ptr must start at 0, end at N and be non-decreasing");
+    if (g->N > 0) {
+        hipLaunchKernelGGL(k_batch_masks, dim3((unsigned)((g->N + tpb - 1) / tpb)), dim3(tpb), 0, st, d_batch_ptr,
+                           (int)n_graphs, g->indptr, g->indices, (int)g->N, max_nodes, g->adj_mask, flags);
+        DFGNN_HIP(hipMemcpyAsync(&host_flags, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+        DFGNN_HIP(hipStreamSynchronize(st));
+    }
+    DFGNN_REQUIRE(!(host_flags & BATCH_CROSS_EDGE), DFGNN_EINVAL, "an edge connects nodes of different graphs of the batch");
+    g->batch_ptr = d_batch_ptr;
+    g->n_graphs = n_graphs;
+    g->batch_dense = !(host_flags & (BATCH_TOO_LARGE | BATCH_DUPLICATE));
+    return DFGNN_OK;
+}
+
 extern "C" int dfgnn_graph_destroy(dfgnn_graph* graph) {
     clear_error();
     delete graph;
@@ -549,6 +638,7 @@ extern "C" int dfgnn_graph_query(const dfgnn_graph* g, int what, const void** d_
     case DFGNN_Q_N_SUPER_COLS: c = g->n_super_cols; break;
     case DFGNN_Q_SUPER_THRESHOLD: c = g->T; break;
     case DFGNN_Q_CHUNK_EDGES: c = g->C; break;
+    case DFGNN_Q_BATCH_DENSE: c = g->batch_dense ? 1 : 0; break;
     default: DFGNN_REQUIRE(false, DFGNN_EINVAL, "unknown query item %d", what);
     }
     if (d_ptr) *d_ptr = p;

@@ -280,6 +280,12 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     DFGNN_REQUIRE(gat || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+    if (dense_batch_supported(graph, layer)) {
+        rc = dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream);
+        if (rc != DFGNN_OK) return rc;
+        DFGNN_HIP(hipGetLastError());
+        return DFGNN_OK;
+    }
     const Workspace W = workspace_layout(graph, layer, false);
     DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
     DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
@@ -325,6 +331,12 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&
                       aligned16(d_k) && aligned16(d_v) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+    if (dense_batch_supported(graph, layer)) {
+        rc = dense_gt_backward(graph, layer, x, k, v, row_max, row_sum, d_out, d_x, d_k, d_v, (hipStream_t)stream);
+        if (rc != DFGNN_OK) return rc;
+        DFGNN_HIP(hipGetLastError());
+        return DFGNN_OK;
+    }
     const Workspace W = workspace_layout(graph, layer, true);
     DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
     DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");

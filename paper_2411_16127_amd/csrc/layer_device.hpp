@@ -1184,7 +1184,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
     }
 }
 
-__global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
                                                          float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
     // thread t: feature t % HD of (a_l | a_r); partials are loaded 16 at a time, then added in order
     for (int t = threadIdx.x; t < 2 * HD; t += blockDim.x) {
@@ -1215,14 +1215,14 @@ __device__ inline float block_sum_256(float v) {
     return r;
 }
 
-__global__ __launch_bounds__(256) void k_sum_partial(const float* __restrict__ in, int64_t n, float* __restrict__ partial) {
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_partial(const float* __restrict__ in, int64_t n, float* __restrict__ partial) {
     float s = 0.f;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) s += in[i];
     const float t = block_sum_256(s);
     if (threadIdx.x == 0) partial[blockIdx.x] = t;
 }
 
-__global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, float* __restrict__ out) {
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, float* __restrict__ out) {
     const float t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.f);
     if (threadIdx.x == 0) *out = t;
 }

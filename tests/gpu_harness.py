@@ -30,12 +30,14 @@ def oracle_layer(w):
     return oracle.Layer(w.model, w.H, w.D, scale=w.scale, neg_slope=w.neg_slope, eps=w.eps)
 
 
-def run_gpu(graph, w, feats, sched=None, g=None):
-    """Forward + backward on the GPU; returns dict of float64 numpy arrays and the Graph object."""
+def run_gpu(graph, w, feats, sched=None, g=None, use_batch=True):
+    """Forward + backward on the GPU; returns dict of float64 numpy arrays and the Graph object.
+
+    A block-diagonal batch (graph.batch_ptr) is announced to the library unless use_batch is False."""
     import torch
     own = g is None
     if own:
-        g = dfgnn.Graph(graph.indptr, graph.indices, sched)
+        g = dfgnn.Graph(graph.indptr, graph.indices, sched, batch_ptr=graph.batch_ptr if use_batch else None)
     L = gpu_layer(w)
     f32 = lambda name: None if name not in feats else torch.from_numpy(feats[name]).cuda()
     x = to_device(feats["q"] if w.model == "gt" else feats["feat"], w.dtype)
