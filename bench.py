@@ -132,6 +132,8 @@ def main() -> int:
     ap.add_argument("--chunk-edges", type=int, default=0)
     ap.add_argument("--no-short-rows", action="store_true", help="ablation: one wavefront for every row below the super threshold")
     ap.add_argument("--no-dense-batch", action="store_true", help="ablation: general kernels also for batches of small graphs")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one step (forward + backward) into a HIP graph and replay it K times in the timed region")
     ap.add_argument("--force-dense-batch", action="store_true", help="dense-tile batch kernels whenever they apply")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
                     help="override a field of the workload (e.g. n_graphs=2048, n_min=60, density=0.5, H=4, D=32); "
@@ -230,12 +232,30 @@ def main() -> int:
     # Per-kernel HIP events are recorded by the library on the launch stream.  Two event records per kernel
     # cost microseconds of host and queue time, which would distort steps that themselves take tens of
     # microseconds: for such workloads the events are recorded in a second pass of K steps instead.
-    events_inline = (not args.no_kernel_events) and (fwd_ms + bwd_ms) >= 1.0
+    events_inline = (not args.no_kernel_events) and (fwd_ms + bwd_ms) >= 1.0 and not args.hip_graph
+    replay = None
+    if args.hip_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        cg = torch.cuda.CUDAGraph()
+        main_stream, stream = stream, side
+        with torch.cuda.stream(side):
+            fwd(); bwd()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(cg, stream=side):
+                fwd(); bwd()
+        stream = main_stream
+        torch.cuda.synchronize()
+        replay = cg.replay
+        replay()
     dfgnn.timing_enable(events_inline)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        fwd(); bwd()
+        if replay:
+            replay()
+        else:
+            fwd(); bwd()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     kernels = dfgnn.timing_collect() if events_inline else {}
@@ -282,7 +302,7 @@ def main() -> int:
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "preprocess_ms": round(preprocess_ms, 2),
         "step_algorithmic_GB": round(total_model / 1e9, 3),
         "step_effective_GBps": round(total_model / 1e9 / (ms_per_step * 1e-3), 1),
-        "kernel_events": events_where,
+        "kernel_events": events_where, "launch": "hip graph replay" if args.hip_graph else "eager",
         "kernels": kern,
     }
 
