@@ -65,7 +65,7 @@ typedef struct {
 #define DFGNN_SCHED_NO_SHORT_ROWS 1
 /* Ablation switch: do not use the dense-tile kernels for batches of small graphs (dfgnn_graph_set_batch). */
 #define DFGNN_SCHED_NO_DENSE_BATCH 2
-/* Use the dense-tile kernels whenever they apply, also below the edges-per-graph count from which they pay. */
+/* Use the dense-tile kernels whenever they apply, also below the tile fill from which they pay. */
 #define DFGNN_SCHED_FORCE_DENSE_BATCH 4
 
 /* One layer call's model description. */
@@ -135,19 +135,27 @@ int dfgnn_graph_destroy(dfgnn_graph* graph);
 
 /*
  * Batched small graphs (the batch-graph workloads of Sec. 5.1: many small graphs processed as one
- * block-diagonal graph).  d_batch_ptr [n_graphs + 1] (device int32, caller-owned, must stay valid while
- * the handle is used) holds the first node of every graph: graph b owns nodes
- * [batch_ptr[b], batch_ptr[b+1]).  The call checks on the GPU that the pointer array starts at 0, ends at
- * N and does not decrease, and that no edge connects two graphs (EINVAL otherwise), and records for each
- * row the adjacency bits inside its graph.  If every graph has at most 64 nodes and no repeated edge,
- * and the batch averages at least 400 edges per graph (below that the general kernels are faster),
- * GT layers in bf16 with D = 16 or 32 are then computed by dense-tile kernels: one wavefront per
- * (graph, head) stages the head's Q, K, V once into LDS and forms the masked score block with MFMA, so
- * every node row is read once per graph instead of once per edge; results agree with the general path to
- * bf16 rounding.  Other layers, and graphs that do not qualify, use the general kernels unchanged.
- * Passing (NULL, 0) forgets the batch structure.  Synchronises `stream`.
+ * block-diagonal graph).  d_batch_ptr [n_graphs + 1] (device int32, caller-owned) holds the first node of
+ * every graph: graph b owns nodes [batch_ptr[b], batch_ptr[b+1]).  d_batch is a device buffer of at
+ * least dfgnn_graph_batch_bytes(N, n_graphs) bytes, 256-byte aligned; it and d_batch_ptr must stay valid
+ * while the handle is used.  The call checks on the GPU that the pointer array starts at 0, ends at N and
+ * does not decrease and that no edge connects two graphs (EINVAL otherwise), and records for each row
+ * and each column its adjacency bits inside its graph.
+ * If no edge is repeated, GT layers are then computed by dense-tile kernels when that pays, i.e. when the
+ * 16 x 16 score tiles of the graphs are full enough (edges / (256 x number of tiles) at least about 0.22
+ * for bf16 and 0.33 for fp32; below that the general kernels are faster):
+ *   bf16, D = 16 or 32, graphs of at most 64 nodes: one wavefront per (graph, head) stages the head's
+ *     Q, K, V once into LDS and forms the masked score block with MFMA;
+ *   fp32, D = 16, 32 or 64, graphs of at most 512 nodes: one wavefront per (graph, head, 16 rows)
+ *     streams over the graph's column tiles with fp32 MFMA.
+ * Every node row is then read once per graph (or once per row tile) instead of once per edge; results
+ * agree with the general path to rounding.  Other layers, and batches that do not qualify, use the
+ * general kernels unchanged.  Passing (NULL, 0, NULL, 0) forgets the batch structure.  Synchronises
+ * `stream`.  Errors: EINVAL, EWORKSPACE, EHIP.
  */
-int dfgnn_graph_set_batch(dfgnn_graph* graph, const int32_t* d_batch_ptr, int64_t n_graphs, void* stream);
+int dfgnn_graph_batch_bytes(int64_t N, int64_t n_graphs, size_t* batch_bytes);
+int dfgnn_graph_set_batch(dfgnn_graph* graph, const int32_t* d_batch_ptr, int64_t n_graphs, void* d_batch,
+                          size_t batch_bytes, void* stream);
 int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, int64_t* count);
 
 /*

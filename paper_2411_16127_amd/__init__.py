@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     graph_create,
     graph_destroy,
     graph_set_batch,
+    graph_batch_bytes,
     graph_query,
     workspace_bytes,
     forward,

@@ -89,7 +89,8 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_graph_meta_bytes.argtypes = [i64, i64, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, vp, sz, vp, sz, vp]
         L.dfgnn_graph_destroy.argtypes = [vp]
-        L.dfgnn_graph_set_batch.argtypes = [vp, vp, i64, vp]
+        L.dfgnn_graph_set_batch.argtypes = [vp, vp, i64, vp, sz, vp]
+        L.dfgnn_graph_batch_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
         L.dfgnn_graph_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
@@ -97,7 +98,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
-        for name in ("dfgnn_graph_set_batch", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
+        for name in ("dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -163,8 +164,15 @@ def graph_create(N: int, E: int, d_indptr, d_indices, sched: Optional[SchedParam
     return handle
 
 
-def graph_set_batch(handle, d_batch_ptr, n_graphs: int, stream=None) -> None:
-    _check(lib().dfgnn_graph_set_batch(handle, _ptr(d_batch_ptr), n_graphs, _stream(stream)), "dfgnn_graph_set_batch")
+def graph_batch_bytes(N: int, n_graphs: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().dfgnn_graph_batch_bytes(N, n_graphs, ctypes.byref(b)), "dfgnn_graph_batch_bytes")
+    return b.value
+
+
+def graph_set_batch(handle, d_batch_ptr, n_graphs: int, d_batch, batch_bytes: int, stream=None) -> None:
+    _check(lib().dfgnn_graph_set_batch(handle, _ptr(d_batch_ptr), n_graphs, _ptr(d_batch), batch_bytes,
+                                       _stream(stream)), "dfgnn_graph_set_batch")
 
 
 def graph_destroy(handle) -> None:
@@ -239,7 +247,10 @@ class Graph:
         self.batch_ptr = None
         if batch_ptr is not None:
             self.batch_ptr = torch.as_tensor(batch_ptr, dtype=torch.int32).to(self.device).contiguous()
-            graph_set_batch(self.handle, self.batch_ptr, int(self.batch_ptr.numel() - 1), stream)
+            n_graphs = int(self.batch_ptr.numel() - 1)
+            nbytes = graph_batch_bytes(self.N, n_graphs)
+            self.batch_meta = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            graph_set_batch(self.handle, self.batch_ptr, n_graphs, self.batch_meta, nbytes, stream)
         self._ws: Dict[tuple, object] = {}
 
     def close(self) -> None:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfgnn.so")
-SOURCES = ["api.cpp", "graph.hip", "layer.hip", "dense_batch.hip"]
+SOURCES = ["api.cpp", "graph.hip", "layer.hip", "dense_batch.hip", "dense_batch_f32.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",
     # packed fp32 arithmetic is kept off for all device code

@@ -45,7 +45,7 @@ inline int64_t chunk_capacity(int64_t E, int T, int C) { return E / C + super_ca
 // Byte offsets of the arrays inside the caller's metadata buffer.
 struct MetaLayout {
     size_t row_order, col_order, t_indptr, t_indices, t_eid;
-    size_t row_chunk_ptr, row_chunks, col_chunk_ptr, col_chunks, counters, adj_mask, total;
+    size_t row_chunk_ptr, row_chunks, col_chunk_ptr, col_chunks, counters, total;
 };
 MetaLayout meta_layout(int64_t N, int64_t E, int T, int C);
 
@@ -71,19 +71,33 @@ struct dfgnn_graph {
     // [k] = position in row_order / col_order of the first entry with sort key >= k (key 0 = super,
     // key 33 - b = bit_length(degree) b); [35] = N
     int32_t row_bucket_ptr[36], col_bucket_ptr[36];
-    // block-diagonal batch of small graphs (dfgnn_graph_set_batch)
+    // block-diagonal batch of small graphs (dfgnn_graph_set_batch); arrays live in the caller's batch buffer
     const int32_t* batch_ptr;
     int64_t n_graphs;
-    unsigned long long* adj_mask;  // [N] adjacency bits of a row inside its graph (valid when batch_dense)
-    int32_t* counters;             // device scratch words inside the metadata buffer
-    bool batch_dense;              // every graph has <= 64 nodes and no repeated edge
+    int32_t* tile_ptr;               // [n_graphs + 1] first 16-node tile of every graph
+    int64_t n_tiles;
+    int64_t tile_pairs;              // sum over graphs of (tiles of the graph)^2: 16 x 16 score tiles a dense pass forms
+    int32_t max_graph_nodes;
+    int32_t mask_words;              // 64-bit words per row of the adjacency bit masks
+    unsigned long long* adj_mask;    // [N][mask_words] bit j: edge row <- (first node of the graph + j)
+    unsigned long long* adj_mask_t;  // [N][mask_words] bit i: edge (first node + i) <- column
+    int32_t* counters;               // device scratch words inside the metadata buffer
+    bool batch_dense;                // no repeated edge and every graph has at most 512 nodes
 };
 
 namespace dfgnn {
-bool dense_batch_supported(const dfgnn_graph* g, const dfgnn_layer* L);
+int dense_batch_kind(const dfgnn_graph* g, const dfgnn_layer* L);
 int dense_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v, void* out,
                      float* row_max, float* row_sum, hipStream_t st);
 int dense_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,
                       const float* row_max, const float* row_sum, const void* d_out, void* d_q, void* d_k, void* d_v,
                       hipStream_t st);
+int dense32_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v, void* out,
+                       float* row_max, float* row_sum, hipStream_t st);
+int dense32_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,
+                        const void* out, const float* row_max, const float* row_sum, const void* d_out, void* d_q,
+                        void* d_k, void* d_v, float* stats, hipStream_t st);
+constexpr int kDenseSmallNodes = 64;   // bf16 kernels: a whole graph head per wavefront
+constexpr int kDenseMaxGraphNodes = 512;
+constexpr int kDenseMaxWords = kDenseMaxGraphNodes / 64;
 }  // namespace dfgnn

@@ -20,7 +20,7 @@ namespace dfgnn {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kDenseMaxNodes = 64;       // nodes per graph the dense path covers (4 tiles of 16)
+constexpr int kDenseMaxNodes = kDenseSmallNodes;  // nodes per graph these kernels cover (4 tiles of 16)
 constexpr int kDenseTiles = kDenseMaxNodes / 16;
 constexpr int kTStride = kDenseMaxNodes + 8;  // row stride (elements) of transposed copies: breaks bank conflicts
 
@@ -31,7 +31,7 @@ struct DenseArgs {
     uint16_t *o, *d_q, *d_k, *d_v;
     const float *row_max, *row_sum;
     float *o_max, *o_sum;
-    int n_graphs, H, D, HD;
+    int n_graphs, H, D, HD, W;  // W: 64-bit words per mask row (only word 0 is used: graphs have <= 64 nodes)
     float c_score, scale;
 };
 
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_dense_gt_forward(const DenseArgs
 
     for (int it = 0; it < tiles; ++it) {
         const int i = it * 16 + l16;  // the query row this lane owns in the transposed score tile
-        const unsigned long long mask = i < n ? a.adj_mask[base + i] : 0ull;
+        const unsigned long long mask = i < n ? a.adj_mask[(size_t)(base + i) * a.W] : 0ull;
         float s[kDenseTiles][4];
         float m = -INFINITY;
 #pragma unroll
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_dense_gt_backward(const DenseArg
         unsigned long long mk = 0ull;
         if (i < n) {
             lse = a.row_max[(size_t)(base + i) * a.H + h] * kLog2e + fast_log2(a.row_sum[(size_t)(base + i) * a.H + h]);
-            mk = a.adj_mask[base + i];
+            mk = a.adj_mask[(size_t)(base + i) * a.W];
         }
         lse_s[wave][i] = lse;
         mask_s[wave][i] = mk;
@@ -338,15 +338,23 @@ __global__ __launch_bounds__(64 * WAVES) void k_dense_gt_backward(const DenseArg
     }
 }
 
-// The dense kernels cost the same whatever the density (all tile pairs of a graph are formed), the
-// gather kernels cost per edge: measured on MI355X the dense path wins from roughly 400 edges per graph
-// on (1.6x at 730, 3.5x at 3,850 edges per graph of 60-64 nodes) and loses below (0.8x at 230).
-constexpr int64_t kDenseMinEdgesPerGraph = 400;
+// The dense kernels form every 16 x 16 score tile of a graph whatever its density, the gather kernels pay
+// per edge, so what decides is how full the tiles are: fill = E / (256 * tile pairs).  Measured on MI355X
+// (profiles/dense_batch_study.md): the bf16 kernels win from a fill of about 0.22 (0.83x at 0.19, 1.6x at
+// 0.30, 3.6x at 0.94), the fp32 kernels, whose MFMA rate is 16 times lower, from about 0.33 (1.05x at
+// 0.31, 1.28x at 0.43).
+constexpr int64_t kDenseMinEdgesPerTileBf16 = 56;  // 0.22 * 256
+constexpr int64_t kDenseMinEdgesPerTileF32 = 85;   // 0.33 * 256
 
-bool dense_batch_supported(const dfgnn_graph* g, const dfgnn_layer* L) {
-    if (!g->batch_dense || (g->flags & DFGNN_SCHED_NO_DENSE_BATCH)) return false;
-    if (L->model != DFGNN_GT || L->dtype != DFGNN_BF16 || (L->D != 16 && L->D != 32)) return false;
-    return (g->flags & DFGNN_SCHED_FORCE_DENSE_BATCH) || g->E >= kDenseMinEdgesPerGraph * g->n_graphs;
+// 1: bf16 kernels of this file; 2: fp32 kernels (dense_batch_f32.hip); 0: general kernels
+int dense_batch_kind(const dfgnn_graph* g, const dfgnn_layer* L) {
+    if (!g->batch_dense || (g->flags & DFGNN_SCHED_NO_DENSE_BATCH) || L->model != DFGNN_GT) return 0;
+    const bool force = g->flags & DFGNN_SCHED_FORCE_DENSE_BATCH;
+    if (L->dtype == DFGNN_BF16 && (L->D == 16 || L->D == 32) && g->max_graph_nodes <= kDenseSmallNodes)
+        return (force || g->E >= kDenseMinEdgesPerTileBf16 * g->tile_pairs) ? 1 : 0;
+    if (L->dtype == DFGNN_F32 && (L->D == 16 || L->D == 32 || L->D == 64))
+        return (force || g->E >= kDenseMinEdgesPerTileF32 * g->tile_pairs) ? 2 : 0;
+    return 0;
 }
 
 static DenseArgs dense_args(const dfgnn_graph* g, const dfgnn_layer* L) {
@@ -354,6 +362,7 @@ static DenseArgs dense_args(const dfgnn_graph* g, const dfgnn_layer* L) {
     a.batch_ptr = g->batch_ptr;
     a.adj_mask = g->adj_mask;
     a.n_graphs = (int)g->n_graphs;
+    a.W = g->mask_words;
     a.H = L->H; a.D = L->D; a.HD = L->H * L->D;
     a.scale = L->scale;
     a.c_score = L->scale * kLog2e;

@@ -221,7 +221,7 @@ static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32
 // ------------------------------------------------------------------------------------------------
 // scheduler kernels
 // ------------------------------------------------------------------------------------------------
-enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_BATCH = 9, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
+enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_BATCH = 9, CNT_BATCH_MAX = 10, CNT_BATCH_PAIRS = 12, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
 
 __global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -329,7 +329,6 @@ MetaLayout meta_layout(int64_t N, int64_t E, int T, int C) {
     L.col_chunk_ptr = take(super_capacity(E, T) + 1);
     L.col_chunks = take(3 * chunk_capacity(E, T, C));
     L.counters = take(CNT_TOTAL);
-    L.adj_mask = take(2 * N);
     L.total = off;
     return L;
 }
@@ -476,7 +475,6 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     g.col_chunks = (int*)(meta + M.col_chunks);
     int* d_counters = (int*)(meta + M.counters);
     g.counters = d_counters;
-    g.adj_mask = (unsigned long long*)(meta + M.adj_mask);
 
     const int tpb = 256;
     DFGNN_HIP(hipMemsetAsync(d_counters, 0, CNT_TOTAL * sizeof(int), st));
@@ -533,7 +531,9 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
 namespace dfgnn {
 enum { BATCH_BAD_PTR = 1, BATCH_CROSS_EDGE = 2, BATCH_TOO_LARGE = 4, BATCH_DUPLICATE = 8 };
 
-__global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int n_nodes, int max_nodes, int* flags) {
+// per graph: pointer checks, largest graph, and the number of 16-node tiles (for the tile pointer)
+__global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int n_nodes, int* __restrict__ tiles,
+                                  int* flags, int* max_nodes, unsigned long long* tile_pairs) {
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g > n_graphs) return;
     int bad = 0;
@@ -541,18 +541,21 @@ __global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int 
     if (g == 0 && p != 0) bad |= BATCH_BAD_PTR;
     if (g == n_graphs && p != n_nodes) bad |= BATCH_BAD_PTR;
     if (p < 0 || p > n_nodes) bad |= BATCH_BAD_PTR;
+    int t = 0;
     if (g < n_graphs) {
         const int sz = bp[g + 1] - p;
         if (sz < 0) bad |= BATCH_BAD_PTR;
-        if (sz > max_nodes) bad |= BATCH_TOO_LARGE;
+        else { atomicMax(max_nodes, sz); t = (sz + 15) >> 4; atomicAdd(tile_pairs, (unsigned long long)t * t); }
     }
+    tiles[g] = t;
     if (bad) atomicOr(flags, bad);
 }
 
-// one thread per node: the adjacency bits of its row relative to the first node of its graph
-__global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const int* __restrict__ indptr,
-                              const int* __restrict__ indices, int n_nodes, int max_nodes,
-                              unsigned long long* __restrict__ adj_mask, int* flags) {
+// One thread per node: adjacency bits of its row (from the CSR) and of its column (from the CSC), both
+// relative to the first node of its graph, `words` 64-bit words each.
+__global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const int* __restrict__ ptr,
+                              const int* __restrict__ idx, int n_nodes, int words, unsigned long long* __restrict__ mask,
+                              int* flags) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_nodes) return;
     int lo = 0, hi = n_graphs;  // last graph whose first node is <= i
@@ -561,55 +564,114 @@ __global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const in
         if (bp[mid] <= i) lo = mid; else hi = mid;
     }
     const int first = bp[lo], last = bp[lo + 1];
-    const bool small = last - first <= max_nodes;
-    unsigned long long mask = 0ull;
+    unsigned long long w[kDenseMaxWords];
+#pragma unroll
+    for (int k = 0; k < kDenseMaxWords; ++k) w[k] = 0ull;
     int bad = 0;
-    for (int e = indptr[i]; e < indptr[i + 1]; ++e) {
-        const int j = indices[e];
+    for (int e = ptr[i]; e < ptr[i + 1]; ++e) {
+        const int j = idx[e];
         if (j < first || j >= last) { bad |= BATCH_CROSS_EDGE; continue; }
-        if (small) {
-            const unsigned long long bit = 1ull << (j - first);
-            if (mask & bit) bad |= BATCH_DUPLICATE;
-            mask |= bit;
+        const int rel = j - first;
+        if (rel < 64 * words) {
+            const unsigned long long bit = 1ull << (rel & 63);
+#pragma unroll
+            for (int k = 0; k < kDenseMaxWords; ++k) {
+                if (k == (rel >> 6)) {
+                    if (w[k] & bit) bad |= BATCH_DUPLICATE;
+                    w[k] |= bit;
+                }
+            }
         }
     }
-    adj_mask[i] = mask;
+    for (int k = 0; k < words; ++k) mask[(size_t)i * words + k] = w[k];
     if (bad) atomicOr(flags, bad);
+}
+
+struct BatchLayout {
+    size_t adj_mask, adj_mask_t, tile_ptr, scan_tmp, total;
+};
+static BatchLayout batch_layout(int64_t N, int64_t n_graphs) {
+    BatchLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1); return o; };
+    L.adj_mask = take((size_t)N * kDenseMaxWords * 8);
+    L.adj_mask_t = take((size_t)N * kDenseMaxWords * 8);
+    L.tile_ptr = take((size_t)(n_graphs + 2) * 4);
+    L.scan_tmp = take((size_t)(scan_blocks(n_graphs + 2) + 1) * 4);
+    L.total = off;
+    return L;
 }
 }  // namespace dfgnn
 
-extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr, int64_t n_graphs, void* stream) {
+extern "C" int dfgnn_graph_batch_bytes(int64_t N, int64_t n_graphs, size_t* batch_bytes) {
+    clear_error();
+    DFGNN_REQUIRE(N >= 0 && n_graphs >= 0 && batch_bytes != nullptr, DFGNN_EINVAL, "negative size or NULL");
+    *batch_bytes = batch_layout(N, n_graphs).total;
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr, int64_t n_graphs, void* d_batch,
+                                     size_t batch_bytes, void* stream) {
     clear_error();
     DFGNN_REQUIRE(g != nullptr, DFGNN_EINVAL, "graph is NULL");
     g->batch_dense = false;
     g->batch_ptr = nullptr;
     g->n_graphs = 0;
+    g->n_tiles = 0;
     if (d_batch_ptr == nullptr && n_graphs == 0) return DFGNN_OK;  // forget the batch structure
     DFGNN_REQUIRE(d_batch_ptr != nullptr && n_graphs >= 0 && n_graphs <= g->N + 1, DFGNN_EINVAL,
                   "batch_ptr is NULL or n_graphs = %lld is out of range", (long long)n_graphs);
     DFGNN_REQUIRE(n_graphs > 0 || g->N == 0, DFGNN_EINVAL, "a graph with nodes needs at least one batch entry");
+    const BatchLayout B = batch_layout(g->N, n_graphs);
+    DFGNN_REQUIRE(d_batch != nullptr && ((uintptr_t)d_batch % kAlign) == 0, DFGNN_EINVAL,
+                  "batch buffer is NULL or not 256-byte aligned");
+    DFGNN_REQUIRE(batch_bytes >= B.total, DFGNN_EWORKSPACE, "batch buffer has %zu bytes, needs %zu", batch_bytes, B.total);
     hipStream_t st = (hipStream_t)stream;
+    char* buf = (char*)d_batch;
     int* flags = g->counters + CNT_BATCH;
+    int* tile_ptr = (int*)(buf + B.tile_ptr);
     const int tpb = 256;
-    const int max_nodes = 64;
-    DFGNN_HIP(hipMemsetAsync(flags, 0, sizeof(int), st));
+    DFGNN_HIP(hipMemsetAsync(flags, 0, 6 * sizeof(int), st));  // flags, running maximum, (pad), 64-bit tile-pair count
+    unsigned long long* d_pairs = (unsigned long long*)(g->counters + CNT_BATCH_PAIRS);
     hipLaunchKernelGGL(k_batch_check_ptr, dim3((unsigned)((n_graphs + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, d_batch_ptr,
-                       (int)n_graphs, (int)g->N, max_nodes, flags);
-    int host_flags = 0;
-    DFGNN_HIP(hipMemcpyAsync(&host_flags, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+                       (int)n_graphs, (int)g->N, tile_ptr, flags, flags + 1, d_pairs);
+    int rc = exclusive_scan(tile_ptr, tile_ptr, n_graphs + 1, (int*)(buf + B.scan_tmp), st);
+    if (rc != DFGNN_OK) return rc;
+    int host[2] = {0, 0};
+    int n_tiles = 0;
+    DFGNN_HIP(hipMemcpyAsync(host, flags, 2 * sizeof(int), hipMemcpyDeviceToHost, st));
+    unsigned long long pairs = 0;
+    DFGNN_HIP(hipMemcpyAsync(&n_tiles, tile_ptr + n_graphs, sizeof(int), hipMemcpyDeviceToHost, st));
+    DFGNN_HIP(hipMemcpyAsync(&pairs, d_pairs, sizeof(pairs), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
-    DFGNN_REQUIRE(!(host_flags & BATCH_BAD_PTR), DFGNN_EINVAL,
-                  "batch_ptr must start at 0, end at N and be non-decreasing");
+    DFGNN_REQUIRE(!(host[0] & BATCH_BAD_PTR), DFGNN_EINVAL, "batch_ptr must start at 0, end at N and be non-decreasing");
+    const int max_nodes = host[1];
+    int words = (max_nodes + 63) / 64;
+    if (words < 1) words = 1;
+    const bool small_enough = max_nodes <= kDenseMaxGraphNodes;
+    if (words > kDenseMaxWords) words = kDenseMaxWords;  // larger graphs: masks are not used, edges are still checked
+    unsigned long long* mask = (unsigned long long*)(buf + B.adj_mask);
+    unsigned long long* mask_t = (unsigned long long*)(buf + B.adj_mask_t);
     if (g->N > 0) {
-        hipLaunchKernelGGL(k_batch_masks, dim3((unsigned)((g->N + tpb - 1) / tpb)), dim3(tpb), 0, st, d_batch_ptr,
-                           (int)n_graphs, g->indptr, g->indices, (int)g->N, max_nodes, g->adj_mask, flags);
-        DFGNN_HIP(hipMemcpyAsync(&host_flags, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+        const dim3 grid((unsigned)((g->N + tpb - 1) / tpb));
+        hipLaunchKernelGGL(k_batch_masks, grid, dim3(tpb), 0, st, d_batch_ptr, (int)n_graphs, g->indptr, g->indices,
+                           (int)g->N, words, mask, flags);
+        hipLaunchKernelGGL(k_batch_masks, grid, dim3(tpb), 0, st, d_batch_ptr, (int)n_graphs, g->t_indptr, g->t_indices,
+                           (int)g->N, words, mask_t, flags);
+        DFGNN_HIP(hipMemcpyAsync(host, flags, sizeof(int), hipMemcpyDeviceToHost, st));
         DFGNN_HIP(hipStreamSynchronize(st));
     }
-    DFGNN_REQUIRE(!(host_flags & BATCH_CROSS_EDGE), DFGNN_EINVAL, "an edge connects nodes of different graphs of the batch");
+    DFGNN_REQUIRE(!(host[0] & BATCH_CROSS_EDGE), DFGNN_EINVAL, "an edge connects nodes of different graphs of the batch");
     g->batch_ptr = d_batch_ptr;
     g->n_graphs = n_graphs;
-    g->batch_dense = !(host_flags & (BATCH_TOO_LARGE | BATCH_DUPLICATE));
+    g->tile_ptr = tile_ptr;
+    g->n_tiles = n_tiles;
+    g->tile_pairs = (int64_t)pairs;
+    g->max_graph_nodes = max_nodes;
+    g->mask_words = words;
+    g->adj_mask = mask;
+    g->adj_mask_t = mask_t;
+    g->batch_dense = small_enough && !(host[0] & BATCH_DUPLICATE);
     return DFGNN_OK;
 }
 

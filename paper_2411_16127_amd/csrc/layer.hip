@@ -280,8 +280,9 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     DFGNN_REQUIRE(gat || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
-    if (dense_batch_supported(graph, layer)) {
-        rc = dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream);
+    if (const int kind = dense_batch_kind(graph, layer)) {
+        rc = kind == 1 ? dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream)
+                       : dense32_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream);
         if (rc != DFGNN_OK) return rc;
         DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;
@@ -331,7 +332,8 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&
                       aligned16(d_k) && aligned16(d_v) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
-    if (dense_batch_supported(graph, layer)) {
+    const int dense_kind = dense_batch_kind(graph, layer);
+    if (dense_kind == 1) {
         rc = dense_gt_backward(graph, layer, x, k, v, row_max, row_sum, d_out, d_x, d_k, d_v, (hipStream_t)stream);
         if (rc != DFGNN_OK) return rc;
         DFGNN_HIP(hipGetLastError());
@@ -343,6 +345,13 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, backward needs %zu",
                   workspace_bytes, W.total);
     hipStream_t st = (hipStream_t)stream;
+    if (dense_kind == 2) {  // the row kernel hands {lse2, delta} to the column kernel through the workspace
+        rc = dense32_gt_backward(graph, layer, x, k, v, out, row_max, row_sum, d_out, d_x, d_k, d_v,
+                                 (float*)((char*)workspace + W.stats), st);
+        if (rc != DFGNN_OK) return rc;
+        DFGNN_HIP(hipGetLastError());
+        return DFGNN_OK;
+    }
 
     Args a{};
     fill_common(a, graph, layer, geo);

@@ -10,7 +10,7 @@ from gpu_harness import run_gpu, run_oracle, compare_all
 
 pytestmark = pytest.mark.gpu
 
-FORCE = dfgnn.SchedParams(flags=4)  # dense-tile kernels also below the edges-per-graph count from which they pay
+FORCE = dfgnn.SchedParams(flags=4)  # dense-tile kernels also below the tile fill from which they pay
 
 
 def gt_bf16(H, D):
@@ -56,20 +56,20 @@ def test_dense_and_general_paths_agree_on_cfg2():
     dense, g1 = run_gpu(graph, w, feats, sched=FORCE)
     general, g2 = run_gpu(graph, w, feats, use_batch=False)
     off, g3 = run_gpu(graph, w, feats, sched=dfgnn.SchedParams(flags=2))
-    auto, g4 = run_gpu(graph, w, feats)  # 230 edges per graph: below the count from which the dense kernels pay
+    auto, g4 = run_gpu(graph, w, feats)  # score tiles 19 % full: below the fill from which the dense kernels pay
     assert g1.query("n_batch_dense") == 1 and g2.query("n_batch_dense") == 0 and g3.query("n_batch_dense") == 1
     ref = run_oracle(graph, w, feats)
     for res in (dense, general, off, auto):
         compare_all(res, ref, w)
     for key in general:
         assert np.array_equal(general[key], off[key]), key   # the ablation flag really selects the general kernels
-        assert np.array_equal(general[key], auto[key]), key  # and so does the edges-per-graph rule here
+        assert np.array_equal(general[key], auto[key]), key  # and so does the tile-fill rule here
     assert any(not np.array_equal(general[key], dense[key]) for key in general)  # the forced run took the other path
     g1.close(); g2.close(); g3.close(); g4.close()
 
 
 def test_dense_path_is_chosen_for_dense_enough_batches():
-    graph = batched_small_graphs(64, 50, 64, 0.4, seed=6)  # ~1,300 edges per graph
+    graph = batched_small_graphs(64, 50, 64, 0.4, seed=6)  # score tiles ~35 % full
     w = gt_bf16(8, 16)
     feats = make_features(w, graph.n)
     auto, g1 = run_gpu(graph, w, feats)
@@ -92,19 +92,21 @@ def test_layers_outside_the_dense_path_still_use_the_general_kernels():
 
 
 def test_large_graphs_and_repeated_edges_switch_the_dense_path_off():
-    big = batched_small_graphs(6, 60, 90, 0.2, seed=2)  # some graphs exceed 64 nodes
+    big = batched_small_graphs(6, 60, 90, 0.2, seed=2)  # some graphs exceed 64 nodes: too large for the bf16 kernels
     w = gt_bf16(2, 16)
     feats = make_features(w, big.n)
-    res, g = run_gpu(big, w, feats)
-    assert g.query("n_batch_dense") == 0
+    res, g = run_gpu(big, w, feats, sched=FORCE)
+    general, g2 = run_gpu(big, w, feats, use_batch=False)
+    for key in res:
+        assert np.array_equal(res[key], general[key]), key  # the general kernels ran
     compare_all(res, run_oracle(big, w, feats), w)
-    g.close()
+    g.close(); g2.close()
     small = batched_small_graphs(6, 10, 20, 0.3, seed=2)
     rows = small.rows_of_edges()
     dup = from_edge_list(small.n, np.concatenate([small.indices, small.indices[:7]]),
                          np.concatenate([rows, rows[:7]]), batch_ptr=small.batch_ptr)
     feats = make_features(w, dup.n)
-    res, g = run_gpu(dup, w, feats)
+    res, g = run_gpu(dup, w, feats, sched=FORCE)
     assert g.query("n_batch_dense") == 0
     compare_all(res, run_oracle(dup, w, feats), w)
     g.close()
@@ -114,10 +116,13 @@ def test_set_batch_rejects_bad_input():
     graph = batched_small_graphs(5, 10, 20, 0.3, seed=3)
     g = dfgnn.Graph(graph.indptr, graph.indices)
     import torch
-    def status(bp):
+    nbytes = dfgnn.graph_batch_bytes(graph.n, 5)
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    def status(bp, nb=nbytes):
         t = torch.tensor(bp, dtype=torch.int32, device="cuda")
         with pytest.raises(dfgnn.DfgnnError) as e:
-            dfgnn.graph_set_batch(g.handle, t, len(bp) - 1)
+            dfgnn.graph_set_batch(g.handle, t, len(bp) - 1, buf, nb)
         return e.value.status
     good = graph.batch_ptr.tolist()
     assert status([1] + good[1:]) == 1                      # does not start at 0
@@ -125,9 +130,60 @@ def test_set_batch_rejects_bad_input():
     assert status([0, good[2], good[1]] + good[3:]) == 1    # decreases
     shifted = list(good); shifted[1] += 3                    # boundary cuts through a graph: edges cross
     assert status(shifted) == 1
+    assert status(good, nb=1024) == 3                         # batch buffer too small
     keep = torch.tensor(good, dtype=torch.int32, device="cuda")
-    dfgnn.graph_set_batch(g.handle, keep, len(good) - 1)     # the well-formed one is accepted afterwards
+    dfgnn.graph_set_batch(g.handle, keep, len(good) - 1, buf, nbytes)  # the well-formed one is accepted afterwards
     assert g.query("n_batch_dense") == 1
-    dfgnn.graph_set_batch(g.handle, None, 0)
+    dfgnn.graph_set_batch(g.handle, None, 0, None, 0)
     assert g.query("n_batch_dense") == 0
+    g.close()
+
+
+# ------------------------------------------------------------------ fp32 dense-tile path (graphs up to 512 nodes)
+def gt_f32(H, D):
+    return Workload("batch32", 93, "gt", H, D, "f32", float(D) ** -0.5)
+
+
+@pytest.mark.parametrize("H,D", [(8, 16), (1, 16), (3, 32), (2, 64)])
+@pytest.mark.parametrize("sizes,density", [((10, 40), 0.3), ((1, 5), 0.5), ((60, 70), 0.3), ((100, 130), 0.4),
+                                           ((250, 260), 0.05), ((500, 512), 0.02)])
+def test_dense_f32_matches_oracle(H, D, sizes, density):
+    graph = batched_small_graphs(9, sizes[0], sizes[1], density, seed=11)
+    w = gt_f32(H, D)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, sched=FORCE)
+    assert g.query("n_batch_dense") == 1
+    general, g2 = run_gpu(graph, w, feats, use_batch=False)
+    assert any(not np.array_equal(res[key], general[key]) for key in res)  # really a different path
+    ref = run_oracle(graph, w, feats)
+    compare_all(res, ref, w)
+    compare_all(general, ref, w)
+    g.close(); g2.close()
+
+
+def test_dense_f32_with_empty_rows():
+    rng = np.random.default_rng(14)
+    sizes = rng.integers(20, 150, size=12)
+    bp = np.concatenate([[0], np.cumsum(sizes)])
+    src, dst = [], []
+    for b in range(12):
+        adj = rng.random((sizes[b], sizes[b])) < 0.02
+        d, s = np.nonzero(adj)
+        src.append(s + bp[b]); dst.append(d + bp[b])
+    graph = from_edge_list(int(bp[-1]), np.concatenate(src), np.concatenate(dst), batch_ptr=bp)
+    assert (graph.degrees() == 0).sum() > 50
+    w = gt_f32(2, 16)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, sched=FORCE)
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
+def test_graphs_above_512_nodes_use_the_general_kernels():
+    graph = batched_small_graphs(3, 520, 530, 0.01, seed=2)
+    w = gt_f32(2, 16)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, sched=FORCE)
+    assert g.query("n_batch_dense") == 0
+    compare_all(res, run_oracle(graph, w, feats), w)
     g.close()
