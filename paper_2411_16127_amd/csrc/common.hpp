@@ -45,9 +45,9 @@ inline int64_t chunk_capacity(int64_t E, int T, int C) { return E / C + super_ca
 // Byte offsets of the arrays inside the caller's metadata buffer.
 struct MetaLayout {
     size_t row_order, col_order, t_indptr, t_indices, t_eid;
-    size_t row_chunk_ptr, row_chunks, col_chunk_ptr, col_chunks, counters, total;
+    size_t row_chunk_ptr, row_chunks, col_chunk_ptr, col_chunks, counters, edge_row, total;
 };
-MetaLayout meta_layout(int64_t N, int64_t E, int T, int C);
+MetaLayout meta_layout(int64_t N, int64_t E, int T, int C, int flags);
 
 // Optional per-kernel timing (dfgnn_timing_enable): a pair of HIP events around a launch.
 struct KernelTimer {
@@ -82,6 +82,7 @@ struct dfgnn_graph {
     unsigned long long* adj_mask;    // [N][mask_words] bit j: edge row <- (first node of the graph + j)
     unsigned long long* adj_mask_t;  // [N][mask_words] bit i: edge (first node + i) <- column
     int32_t* counters;               // device scratch words inside the metadata buffer
+    int32_t* edge_row;               // [E] destination row of every CSR position (only with SCORES_IN_MEMORY)
     bool batch_dense;                // no repeated edge and every graph has at most 512 nodes
 };
 

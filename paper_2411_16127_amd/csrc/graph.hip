@@ -303,7 +303,7 @@ __global__ void k_rows_of_positions(const int* __restrict__ t_eid, const int* __
                                     int* __restrict__ t_indices) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= e) return;
-    const int p = t_eid[t];
+    const int p = t_eid ? t_eid[t] : (int)t;  // no position list: the positions are 0..e-1 themselves
     int lo = 0, hi = n;  // invariant: indptr[lo] <= p < indptr[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -315,7 +315,7 @@ __global__ void k_rows_of_positions(const int* __restrict__ t_eid, const int* __
 // ------------------------------------------------------------------------------------------------
 // layout of the caller's buffers
 // ------------------------------------------------------------------------------------------------
-MetaLayout meta_layout(int64_t N, int64_t E, int T, int C) {
+MetaLayout meta_layout(int64_t N, int64_t E, int T, int C, int flags) {
     MetaLayout L{};
     size_t off = 0;
     auto take = [&](int64_t count) { size_t o = off; off += align_up((size_t)(count > 0 ? count : 1) * sizeof(int32_t)); return o; };
@@ -329,6 +329,7 @@ MetaLayout meta_layout(int64_t N, int64_t E, int T, int C) {
     L.col_chunk_ptr = take(super_capacity(E, T) + 1);
     L.col_chunks = take(3 * chunk_capacity(E, T, C));
     L.counters = take(CNT_TOTAL);
+    L.edge_row = take((flags & DFGNN_SCHED_SCORES_IN_MEMORY) ? E : 0);
     L.total = off;
     return L;
 }
@@ -367,8 +368,9 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
         for (int r : sched->reserved) DFGNN_REQUIRE(r == 0, DFGNN_EINVAL, "dfgnn_sched_params.reserved must be zero");
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
-        DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH)) == 0, DFGNN_EINVAL, "unknown scheduling flag 0x%x",
-                      sched->flags);
+        DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH |
+                                         DFGNN_SCHED_SCORES_IN_MEMORY)) == 0,
+                      DFGNN_EINVAL, "unknown scheduling flag 0x%x", sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;
         if (flags) *flags = sched->flags;
@@ -427,10 +429,10 @@ extern "C" int dfgnn_graph_meta_bytes(int64_t N, int64_t E, const dfgnn_sched_pa
     DFGNN_REQUIRE(N >= 0 && E >= 0, DFGNN_EINVAL, "negative graph size N=%lld E=%lld", (long long)N, (long long)E);
     DFGNN_REQUIRE(N < (int64_t)INT32_MAX - (1 << 20) && E < (int64_t)INT32_MAX - (1 << 20), DFGNN_EUNSUPPORTED,
                   "graph too large for int32 indexing");
-    int T, C;
-    int rc = resolve_params(sched, E, &T, &C);
+    int T, C, flags = 0;
+    int rc = resolve_params(sched, E, &T, &C, &flags);
     if (rc != DFGNN_OK) return rc;
-    if (meta_bytes) *meta_bytes = meta_layout(N, E, T, C).total;
+    if (meta_bytes) *meta_bytes = meta_layout(N, E, T, C, flags).total;
     if (scratch_bytes) *scratch_bytes = scratch_layout(N, E, T).total;
     return DFGNN_OK;
 }
@@ -456,7 +458,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     if (rc != DFGNN_OK) return rc;
 
     hipStream_t st = (hipStream_t)stream;
-    const MetaLayout M = meta_layout(N, E, T, C);
+    const MetaLayout M = meta_layout(N, E, T, C, flags);
     const ScratchLayout S = scratch_layout(N, E, T);
     char* meta = (char*)d_meta;
     char* scratch = (char*)d_scratch;
@@ -475,6 +477,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     g.col_chunks = (int*)(meta + M.col_chunks);
     int* d_counters = (int*)(meta + M.counters);
     g.counters = d_counters;
+    g.edge_row = (flags & DFGNN_SCHED_SCORES_IN_MEMORY) ? (int*)(meta + M.edge_row) : nullptr;
 
     const int tpb = 256;
     DFGNN_HIP(hipMemsetAsync(d_counters, 0, CNT_TOTAL * sizeof(int), st));
@@ -508,6 +511,9 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
                            (int)E, (int)N, g.t_indptr);
         hipLaunchKernelGGL(k_rows_of_positions, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid,
                            d_indptr, (int)N, (int)E, g.t_indices);
+        if (g.edge_row)  // COO row array of the CSR itself (edge-parallel comparator)
+            hipLaunchKernelGGL(k_rows_of_positions, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st,
+                               (const int*)nullptr, d_indptr, (int)N, (int)E, g.edge_row);
         DFGNN_HIP(hipGetLastError());
     } else {
         DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));

@@ -57,8 +57,13 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
 // workspace layout (float offsets turned into pointers)
 // ---------------------------------------------------------------------------------------------
 struct Workspace {
-    size_t stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, total;
+    size_t stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, scores, total;
 };
+
+// the two-kernel forward comparator applies (GT on the general kernels)
+static bool scores_in_memory(const dfgnn_graph* g, const dfgnn_layer* L) {
+    return (g->flags & DFGNN_SCHED_SCORES_IN_MEMORY) && L->model == DFGNN_GT && g->E > 0;
+}
 
 static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward) {
     Workspace W{};
@@ -81,6 +86,7 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
         W.dbeta_row = take(agnn ? N * H : 0);
         W.reduce = take(gat ? (size_t)kReduceBlocks * 2 * HD : (agnn ? (size_t)kReduceBlocks : 0));
     }
+    if (!backward && scores_in_memory(g, L)) W.scores = take((size_t)g->E * H);
     W.total = off;
     return W;
 }
@@ -90,6 +96,7 @@ static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward)
     a.part_v0 = (float*)(b + W.part_v0);
     a.part_s0 = (float*)(b + W.part_s0);
     a.part_s1 = (float*)(b + W.part_s1);
+    if (!backward && W.scores) a.scores = (float*)(b + W.scores);
     if (backward) {
         a.stats = (float*)(b + W.stats);
         a.part_v1 = (float*)(b + W.part_v1);
@@ -150,12 +157,25 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
 }
 
 static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
+static const char* const kStoredLabels[2] = {"fwd_softmax_spmm", "fwd_softmax_spmm_merge"};
 static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
 static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
 
 template <class G> static void run_forward(const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
     switch (model) {
-    case DFGNN_GT: run_pass<G, GtFwd>(g, false, a, kFwdLabels, st); break;
+    case DFGNN_GT:
+        if (a.scores) {  // comparator: scores through memory (Sec. 3, parallelism maximization fusion)
+            const int64_t per_wave = (int64_t)G::EPW * kUnroll * kScoreRounds;
+            {
+                KernelTimer t("fwd_scores", st);
+                hipLaunchKernelGGL((k_edge_scores<G, kUnroll>), dim3(blocks_for((g->E + per_wave - 1) / per_wave)),
+                                   dim3(64 * kWavesPerBlock), 0, st, a);
+            }
+            run_pass<G, GtFwdStored>(g, false, a, kStoredLabels, st);
+        } else {
+            run_pass<G, GtFwd>(g, false, a, kFwdLabels, st);
+        }
+        break;
     case DFGNN_GAT:
         run_pass<G, GatFwd>(g, false, a, kFwdLabels, st);
         break;
@@ -296,6 +316,7 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     fill_common(a, graph, layer, geo);
     a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
     a.o = out; a.o_max = row_max; a.o_sum = row_sum;
+    a.idx = graph->indices; a.edge_row = graph->edge_row; a.n_edges = (int)graph->E;
     bind_workspace(a, W, workspace, false);
     rc = dispatch_forward(geo.id, graph, layer->model, a, (hipStream_t)stream);
     if (rc != DFGNN_OK) return rc;

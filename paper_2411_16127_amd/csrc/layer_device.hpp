@@ -186,6 +186,10 @@ struct Args {
     float* part_s0;    // [chunks, H]
     float* part_s1;    // [chunks, H]
     float* part_s2;    // [chunks, H]
+    // scores-through-memory comparator
+    float* scores;        // [E, H] scaled scores in log2 units
+    const int* edge_row;  // [E] destination row of every CSR position
+    int n_edges;
 };
 
 // Lane geometry: LPE lanes per neighbour row, LPH lanes per head (0 = run-time), element type T.
@@ -388,7 +392,7 @@ template <class G, int U> struct GtFwd {
         for (int i = 0; i < VEC; ++i) q[i] *= a.c_score;
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         V[u] = gather_raw<G>(a.v, a, c, j);
     }
@@ -411,6 +415,29 @@ template <class G, int U> struct GtFwd {
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
 
+// Forward pass of the two-kernel comparator (Sec. 3, parallelism maximization fusion): the scores were
+// written by k_edge_scores; this pass reads them back and does the softmax and the aggregation.
+template <class G, int U> struct GtFwdStored {
+    static constexpr int VEC = G::VEC;
+    SoftmaxAcc<G, U> sm;
+    float S[U];
+    u32x4 V[U];
+    __device__ void init(const Args&, const Ctx&) { sm.reset(); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        S[u] = j >= 0 ? a.scores[(size_t)e * a.H + c.h] : -INFINITY;
+        V[u] = gather_raw<G>(a.v, a, c, j);
+    }
+    template <bool FULL> __device__ void consume(const Args&, const Ctx&, const int (&j)[U]) {
+        if (!FULL && j[0] < 0) return;
+        sm.update(S, V);
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
+    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
+    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
+};
+
 // dQ_i = scale sum_j dS_ij k_j with dS_ij = p_ij (dO_i.v_j - delta_i)   (Appendix B; fused chain of Sec. 4.3)
 template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
@@ -423,7 +450,7 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
         for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; pk[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         V[u] = gather_raw<G>(a.v, a, c, j);
     }
@@ -514,7 +541,7 @@ template <class G, int U> struct GtBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { k2[i] *= a.c_score; dk[i] = 0.f; dv[i] = 0.f; }
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
         Q[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats2(a, c, i);
@@ -596,7 +623,7 @@ template <class G, int U> struct GatFwd {
         el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
@@ -632,7 +659,7 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
         pl = 0.f;
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -712,7 +739,7 @@ template <class G, int U> struct GatBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dwh[i] = 0.f;
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats4(a, c, i);
     }
@@ -785,7 +812,7 @@ template <class G, int U> struct AgnnFwd {
         for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
@@ -822,7 +849,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; px[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -929,7 +956,7 @@ template <class G, int U> struct AgnnBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
         Xi[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats4(a, c, i);
@@ -1033,7 +1060,7 @@ __device__ inline void wave_item(const Args& a, int item, int lane) {
     load_indices<G, U>(a, c, eb, ee, j);
     for (int base = eb; base < ee; base += STEP) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u]);
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], base + u * G::EPW + c.g);
         load_indices<G, U>(a, c, base + STEP, ee, jn);
         if (base + STEP <= ee) p.template consume<true>(a, c, j);
         else p.template consume<false>(a, c, j);
@@ -1064,7 +1091,7 @@ __device__ inline void wave_small_rows(const Args& a, int item, int lane) {
     for (int u = 0; u < U; ++u) j[u] = eb + u < ee ? a.idx[eb + u] : -1;
     for (int pos = eb; __any(pos < ee); pos += U) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u]);
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], pos + u);
 #pragma unroll
         for (int u = 0; u < U; ++u) jn[u] = pos + U + u < ee ? a.idx[pos + U + u] : -1;
         if (__all(pos + U <= ee)) p.template consume<true>(a, c, j);
@@ -1130,6 +1157,45 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     }
     p.combine_slots(a, c);
     p.finalize(a, c);
+}
+
+// Edge-parallel SDDMM of the two-kernel comparator: the CSR positions are dealt out evenly, EPW * U per
+// round and kScoreRounds rounds per wavefront, whatever rows they belong to; each edge slot gathers
+// q of its edge's row (COO row array) and k of its neighbour and stores the scaled score of every head.
+constexpr int kScoreRounds = 4;
+template <class G, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_edge_scores(const Args a) {
+    const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const Ctx c = make_ctx<G>(a, lane, 0);
+    constexpr int STEP = G::EPW * U;
+    const int64_t first = (int64_t)wave * STEP * kScoreRounds;
+    for (int r = 0; r < kScoreRounds; ++r) {
+        const int64_t base = first + (int64_t)r * STEP;
+        if (base >= a.n_edges) return;
+        int i[U], j[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * G::EPW + c.g;
+            const bool live = e < a.n_edges;
+            i[u] = live ? a.edge_row[e] : -1;
+            j[u] = live ? a.idx[e] : -1;
+        }
+        u32x4 Q[U], K[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            Q[u] = gather_raw<G>(a.x, a, c, i[u]);
+            K[u] = gather_raw<G>(a.k, a, c, j[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float qf[G::VEC], kf[G::VEC];
+            Elem<typename G::T>::unpack(Q[u], qf);
+            Elem<typename G::T>::unpack(K[u], kf);
+            const float s = head_sum<G::LPH>(dotv<G::VEC>(qf, kf), a.lph) * a.c_score;
+            const int64_t e = base + u * G::EPW + c.g;
+            if (c.head0 && j[u] >= 0) a.scores[(size_t)e * a.H + c.h] = s;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
