@@ -1,7 +1,8 @@
 /*
  * CPU oracle for the attention-GNN graph convolution  O = SpMM(Softmax(SDDMM(Q, K, A)), V)
  * (Eq. 1 of Sec. 2.1) and its backward pass (Appendix B), for the three models of Sec. 5.1:
- * GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features).
+ * GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features), plus GATv2, the
+ * second member of the GAT family cited in Sec. 1, whose score is not a sum of two per-node scalars.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the plain definition written out as a single-threaded
  * loop over CSR rows in double precision.  It shares no code with the HIP library, is never called
@@ -17,14 +18,17 @@
  *   GT   : scale * sum_d Q[i,h,d] K[j,h,d]
  *   GAT  : LeakyReLU(el[i,h] + er[j,h]),  el[v,h] = a_l[h,:].X[v,h,:],  er[v,h] = a_r[h,:].X[v,h,:]
  *   AGNN : beta * xhat[i,h,:].xhat[j,h,:],  xhat[v,h,:] = X[v,h,:] / max(||X[v,h,:]||_2, eps)   (beta = scale)
- * Aggregated value rows: GT V, GAT X, AGNN X (the un-normalised features).
+ *   GATv2: sum_d a[h,d] LeakyReLU(X[i,h,d] + K[j,h,d])   (X = destination-side, K = source-side projection;
+ *          a = a_l; the non-linearity sits between the two linear maps, so the ranking of the neighbours
+ *          depends on the destination)
+ * Aggregated value rows: GT V, GAT X, AGNN X (the un-normalised features), GATv2 K.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-enum { ATGNN_GT = 0, ATGNN_GAT = 1, ATGNN_AGNN = 2 };
+enum { ATGNN_GT = 0, ATGNN_GAT = 1, ATGNN_AGNN = 2, ATGNN_GATV2 = 3 };
 
 typedef struct {
     int32_t model;
@@ -42,8 +46,9 @@ typedef struct {
     const int32_t* indptr;
     const int32_t* indices;
     const double* X;   /* GT: Q; GAT: Wh; AGNN: h */
-    const double* K;   /* GT only */
-    const double* Val; /* aggregated rows: GT V, else X */
+    const double* K;   /* GT keys; GATv2 source-side features */
+    const double* Val; /* aggregated rows: GT V, GATv2 K, else X */
+    const double* a;   /* GATv2 attention vector [H,D] */
     double* el;        /* GAT [N,H] */
     double* er;        /* GAT [N,H] */
     double* nrm;       /* AGNN [N,H]: max(||x||, eps) */
@@ -61,7 +66,8 @@ static int ctx_init(ctx_t* c, const atgnn_layer* L, int64_t N, const int32_t* in
     const int H = L->H, D = L->D;
     memset(c, 0, sizeof(*c));
     c->L = L; c->N = N; c->indptr = indptr; c->indices = indices; c->X = X; c->K = K;
-    c->Val = (L->model == ATGNN_GT) ? V : X;
+    c->Val = (L->model == ATGNN_GT) ? V : (L->model == ATGNN_GATV2 ? K : X);
+    c->a = a_l;
     if (L->model == ATGNN_GAT) {
         c->el = (double*)malloc(sizeof(double) * (size_t)(N * H + 1));
         c->er = (double*)malloc(sizeof(double) * (size_t)(N * H + 1));
@@ -105,6 +111,14 @@ static double score(const ctx_t* c, int64_t i, int64_t j, int h) {
     case ATGNN_GAT: {
         double z = gat_z(c, i, j, h);
         return z > 0.0 ? z : c->L->neg_slope * z;
+    }
+    case ATGNN_GATV2: {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) {
+            const double z = c->X[(i * H + h) * D + d] + c->K[(j * H + h) * D + d];
+            s += c->a[h * D + d] * (z > 0.0 ? z : c->L->neg_slope * z);
+        }
+        return s;
     }
     default:
         return c->L->scale * dot(c->xhat + (i * H + h) * D, c->xhat + (j * H + h) * D, D);
@@ -187,6 +201,8 @@ int atgnn_oracle_forward(const atgnn_layer* L, int64_t N, const int32_t* indptr,
  *          dX_v += d_el_v a_l + d_er_v a_r;  da_l[h] = sum_v d_el[v,h] X[v,h,:];  da_r likewise
  *   AGNN : c = xhat_i . xhat_j; dbeta += dS_ij c; g_i += beta dS_ij xhat_j; g_j += beta dS_ij xhat_i;
  *          dX_v += (g_v - (g_v . xhat_v) xhat_v) / ||x_v||   (||x_v|| > eps), else g_v / eps
+ *   GATv2: z_d = X_i,d + K_j,d; dz_d = dS_ij a_d (z_d > 0 ? 1 : neg_slope); dX_i += dz; dK_j += dz (on top of
+ *          the value term p_ij G_i);  da_l[h,d] += dS_ij LeakyReLU(z_d)
  * dS_out (optional) [nnz,H] receives dS of every processed edge.
  */
 int atgnn_oracle_backward(const atgnn_layer* L, int64_t N, const int32_t* indptr, const int32_t* indices,
@@ -202,7 +218,7 @@ int atgnn_oracle_backward(const atgnn_layer* L, int64_t N, const int32_t* indptr
     double* p = (double*)malloc(sizeof(double) * (size_t)(md + 1));
     double* dP = (double*)malloc(sizeof(double) * (size_t)(md + 1));
     double* d_el = NULL; double* d_er = NULL; double* g = NULL;
-    double* dVal = (L->model == ATGNN_GT) ? dV : dX;
+    double* dVal = (L->model == ATGNN_GT) ? dV : (L->model == ATGNN_GATV2 ? dK : dX);
 
     memset(dX, 0, sizeof(double) * NHD);
     if (L->model == ATGNN_GT) { memset(dK, 0, sizeof(double) * NHD); memset(dV, 0, sizeof(double) * NHD); }
@@ -213,6 +229,7 @@ int atgnn_oracle_backward(const atgnn_layer* L, int64_t N, const int32_t* indptr
         memset(da_r, 0, sizeof(double) * H * D);
     }
     if (L->model == ATGNN_AGNN) { g = (double*)calloc(NHD + 1, sizeof(double)); *dscale = 0.0; }
+    if (L->model == ATGNN_GATV2) { memset(dK, 0, sizeof(double) * NHD); memset(da_l, 0, sizeof(double) * H * D); }
 
     const int64_t count = rows ? n_rows : N;
     for (int64_t r = 0; r < count; ++r) {
@@ -242,6 +259,14 @@ int atgnn_oracle_backward(const atgnn_layer* L, int64_t N, const int32_t* indptr
                     const double dz = dS * (gat_z(&c, i, j, h) > 0.0 ? 1.0 : L->neg_slope);
                     d_el[i * H + h] += dz;
                     d_er[j * H + h] += dz;
+                } else if (L->model == ATGNN_GATV2) {
+                    for (int d = 0; d < D; ++d) {
+                        const double z = X[(i * H + h) * D + d] + K[(j * H + h) * D + d];
+                        const double dz = dS * a_l[h * D + d] * (z > 0.0 ? 1.0 : L->neg_slope);
+                        dX[(i * H + h) * D + d] += dz;
+                        dK[(j * H + h) * D + d] += dz;
+                        da_l[h * D + d] += dS * (z > 0.0 ? z : L->neg_slope * z);
+                    }
                 } else {
                     const double* xi = c.xhat + (i * H + h) * D;
                     const double* xj = c.xhat + (j * H + h) * D;

@@ -16,7 +16,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "atgnn_oracle.c")
 _LIB = os.path.join(_HERE, "libatgnn_oracle.so")
-_MODEL = {"gt": 0, "gat": 1, "agnn": 2}
+_MODEL = {"gt": 0, "gat": 1, "agnn": 2, "gatv2": 3}
 
 
 class _CLayer(ctypes.Structure):
@@ -30,7 +30,7 @@ class Layer:
     H: int
     D: int
     scale: float = 1.0       # GT: score scale, AGNN: beta
-    neg_slope: float = 0.2   # GAT
+    neg_slope: float = 0.2   # GAT, GATv2
     eps: float = 1e-12       # AGNN
 
     def _c(self) -> _CLayer:
@@ -83,7 +83,8 @@ def _graph(indptr, indices):
 
 def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, rows=None,
             want_p: bool = False) -> Dict[str, np.ndarray]:
-    """x: GT Q / GAT Wh / AGNN h, [N,H,D].  Returns out [N,H,D], row_max, row_sum [N,H] (float64)
+    """x: GT Q / GAT Wh / AGNN h / GATv2 destination-side features, [N,H,D]; k: GT K / GATv2 source-side
+    features; a_l: GAT left vector / GATv2 attention vector.  Returns out [N,H,D], row_max, row_sum [N,H] (float64)
     and optionally p [nnz,H].  With `rows`, only those rows are filled (others stay NaN)."""
     lib = _load()
     ip, ix, n = _graph(indptr, indices)
@@ -94,6 +95,8 @@ def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=N
         assert k_ is not None and v_ is not None and k_.size == x_.size and v_.size == x_.size
     if layer.model == "gat":
         assert al_ is not None and ar_ is not None and al_.size == H * D and ar_.size == H * D
+    if layer.model == "gatv2":
+        assert k_ is not None and k_.size == x_.size and al_ is not None and al_.size == H * D
     r_, nr, rp = _rows(rows)
     fill = np.nan if rows is not None else 0.0
     out = np.full((n, H, D), fill, dtype=np.float64)
@@ -117,7 +120,7 @@ def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=N
 def backward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, d_out, rows=None,
              want_ds: bool = False) -> Dict[str, np.ndarray]:
     """Gradients of sum(O * d_out): d_x [N,H,D]; GT also d_k, d_v; GAT also d_a_l, d_a_r [H,D];
-    AGNN also d_scale (d beta).  With `rows`, see the completeness note in atgnn_oracle.c."""
+    AGNN also d_scale (d beta); GATv2 also d_k, d_a_l.  With `rows`, see the completeness note in atgnn_oracle.c."""
     lib = _load()
     ip, ix, n = _graph(indptr, indices)
     H, D = layer.H, layer.D
@@ -139,6 +142,11 @@ def backward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=
         res["d_a_r"] = np.empty((H, D), dtype=np.float64)
         dalp = res["d_a_l"].ctypes.data_as(ctypes.c_void_p)
         darp = res["d_a_r"].ctypes.data_as(ctypes.c_void_p)
+    if layer.model == "gatv2":
+        res["d_k"] = np.empty((n, H, D), dtype=np.float64)
+        res["d_a_l"] = np.empty((H, D), dtype=np.float64)
+        dkp = res["d_k"].ctypes.data_as(ctypes.c_void_p)
+        dalp = res["d_a_l"].ctypes.data_as(ctypes.c_void_p)
     dscale = ctypes.c_double(0.0)
     ds = np.full((ix.size, H), np.nan, dtype=np.float64) if want_ds else None
     cl = layer._c()

@@ -1,4 +1,4 @@
-"""Dense masked-attention formulation of the three models in CPU torch float64 + autograd.
+"""Dense masked-attention formulation of the models in CPU torch float64 + autograd.
 
 Used only to pin the CPU oracle: it is a different route to the same numbers (dense N x N score
 matrix, library softmax, library autograd) and shares nothing with the oracle or the HIP path.
@@ -27,6 +27,10 @@ def dense_layer(model, indptr, indices, H, D, scale, neg_slope, eps, tensors, d_
         z = el.t()[:, :, None] + er.t()[:, None, :]  # [H, i, j]
         s = torch.nn.functional.leaky_relu(z, neg_slope)
         val = t["x"]
+    elif model == "gatv2":
+        z = t["x"].permute(1, 0, 2)[:, :, None, :] + t["k"].permute(1, 0, 2)[:, None, :, :]  # [H, i, j, D]
+        s = (torch.nn.functional.leaky_relu(z, neg_slope) * t["a_l"][:, None, None, :]).sum(-1)
+        val = t["k"]
     elif model == "agnn":
         nrm = torch.clamp(torch.linalg.vector_norm(t["x"], dim=-1, keepdim=True), min=eps)
         xh = t["x"] / nrm

@@ -1,7 +1,8 @@
 """Pins for the CPU oracle (no GPU): a dense library route, finite differences, invariants, closed forms.
 
 Each test names the passage whose reading it fixes: Eq. 1 (Sec. 2.1) for the layer, Appendix A for
-the edge softmax, Appendix B for the backward pass, Sec. 5.1 for the three models' scores.
+the edge softmax, Appendix B for the backward pass, Sec. 5.1 for the three models' scores; GATv2 is the
+second member of the GAT family cited in Sec. 1.
 """
 import numpy as np
 import pytest
@@ -10,7 +11,7 @@ import oracle
 from dfgnn_synth import complete_graph, tiny_graph, from_edge_list
 from dense_reference import dense_layer
 
-MODELS = ["gt", "gat", "agnn"]
+MODELS = ["gt", "gat", "agnn", "gatv2"]
 
 
 def make_inputs(model, n, H, D, seed):
@@ -22,12 +23,15 @@ def make_inputs(model, n, H, D, seed):
     if model == "gat":
         t["a_l"] = rng.standard_normal((H, D)) * 0.5
         t["a_r"] = rng.standard_normal((H, D)) * 0.5
+    if model == "gatv2":
+        t["k"] = rng.standard_normal((n, H, D))
+        t["a_l"] = rng.standard_normal((H, D)) * 0.5
     g = rng.standard_normal((n, H, D))
     return t, g
 
 
 def layer_for(model, H, D):
-    scale = {"gt": 1.0 / np.sqrt(D), "gat": 1.0, "agnn": 1.7}[model]
+    scale = {"gt": 1.0 / np.sqrt(D), "gat": 1.0, "agnn": 1.7, "gatv2": 1.0}[model]
     return oracle.Layer(model, H, D, scale=scale, neg_slope=0.2, eps=1e-12)
 
 
@@ -62,6 +66,9 @@ def test_matches_dense_masked_attention(model, graph):
         np.testing.assert_allclose(bw["d_a_r"], grads["a_r"], rtol=1e-9, atol=1e-11)
     if model == "agnn":
         np.testing.assert_allclose(bw["d_scale"], grads["beta"], rtol=1e-9, atol=1e-11)
+    if model == "gatv2":
+        np.testing.assert_allclose(bw["d_k"], grads["k"], rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(bw["d_a_l"], grads["a_l"], rtol=1e-9, atol=1e-11)
 
 
 def test_complete_graph_is_dense_softmax_attention():
@@ -175,6 +182,9 @@ def test_node_relabelling_equivariance(model):
     if model == "gt":
         np.testing.assert_allclose(bw2["d_k"][perm], bw["d_k"], rtol=1e-9, atol=1e-12)
         np.testing.assert_allclose(bw2["d_v"][perm], bw["d_v"], rtol=1e-9, atol=1e-12)
+    if model == "gatv2":
+        np.testing.assert_allclose(bw2["d_k"][perm], bw["d_k"], rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(bw2["d_a_l"], bw["d_a_l"], rtol=1e-9, atol=1e-12)
 
 
 def test_score_shift_invariance_gt():
@@ -211,13 +221,16 @@ def test_self_loop_only_rows_copy_the_value(model):
     g = tiny_graph("selfloop", n=10)
     t, d_out = make_inputs(model, g.n, H, D, seed=4)
     fw, bw = run_oracle(layer_for(model, H, D), g, t, d_out)
-    val = t["v"] if model == "gt" else t["x"]
+    val = {"gt": t.get("v"), "gatv2": t.get("k")}.get(model, t["x"])
     np.testing.assert_allclose(fw["out"], val, rtol=1e-14)
     np.testing.assert_allclose(fw["row_sum"], 1.0)
     np.testing.assert_allclose(bw["ds"], 0.0, atol=1e-15)
     if model == "gt":
         np.testing.assert_allclose(bw["d_v"], d_out, rtol=1e-14)
         assert np.all(bw["d_x"] == 0) and np.all(bw["d_k"] == 0)
+    elif model == "gatv2":
+        np.testing.assert_allclose(bw["d_k"], d_out, rtol=1e-14)
+        assert np.all(bw["d_x"] == 0) and np.all(bw["d_a_l"] == 0)
     else:
         np.testing.assert_allclose(bw["d_x"], d_out, rtol=1e-12, atol=1e-14)
 
@@ -300,6 +313,38 @@ def test_gat_leaky_relu_derivative_at_both_signs():
     dz = dS * np.array([1.0, 0.1])
     # dX_0 = d_el_0 * a_l ; dX_1 = p_1*dO_0 + d_er_1 * a_r ; dX_2 = p_2*dO_0 + d_er_2 * a_r
     np.testing.assert_allclose(bw["d_x"].ravel(), [dz.sum(), p[0] + dz[0], p[1] + dz[1]], rtol=1e-13)
+
+
+def test_gatv2_slope_one_is_gat_with_one_attention_vector():
+    """LeakyReLU with slope 1 is the identity, so a.(x_i + k_j) = a.x_i + a.k_j: with x = k = Wh the layer is
+    GAT with a_l = a_r = a (also slope 1), and the gradients add up accordingly."""
+    H, D = 2, 4
+    g = tiny_graph("hub", seed=5, n=15)
+    t, d_out = make_inputs("gat", g.n, H, D, seed=4)
+    gat = run_oracle(oracle.Layer("gat", H, D, neg_slope=1.0), g, dict(t, a_r=t["a_l"]), d_out)
+    v2 = run_oracle(oracle.Layer("gatv2", H, D, neg_slope=1.0), g, {"x": t["x"], "k": t["x"], "a_l": t["a_l"]}, d_out)
+    np.testing.assert_allclose(v2[0]["out"], gat[0]["out"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(v2[0]["p"], gat[0]["p"], rtol=1e-12)
+    np.testing.assert_allclose(v2[1]["d_x"] + v2[1]["d_k"], gat[1]["d_x"], rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(v2[1]["d_a_l"], gat[1]["d_a_l"] + gat[1]["d_a_r"], rtol=1e-10, atol=1e-13)
+
+
+def test_gatv2_ranking_depends_on_the_destination():
+    """The property the variant exists for: two destinations can rank the same two sources differently
+    (with GAT's separable score they cannot).  One head, D = 2, hand-computed scores."""
+    H, D = 1, 2
+    g = from_edge_list(4, [2, 3, 2, 3], [0, 0, 1, 1])  # destinations 0 and 1, sources 2 and 3
+    x = np.array([[[2.0, -2.0]], [[-2.0, 2.0]], [[0.0, 0.0]], [[0.0, 0.0]]])
+    k = np.array([[[0.0, 0.0]], [[0.0, 0.0]], [[1.0, 0.0]], [[0.0, 1.0]]])
+    a = np.array([[1.0, 1.0]])
+    layer = oracle.Layer("gatv2", H, D, neg_slope=0.5)
+    fw = oracle.forward(layer, g.indptr, g.indices, x=x, k=k, a_l=a, want_p=True)
+    lrelu = lambda z: np.where(z > 0, z, 0.5 * z)
+    s = np.array([[lrelu(x[i, 0] + k[j, 0]).sum() for j in (2, 3)] for i in (0, 1)])  # [[2.0, 1.5], [1.5, 2.0]]
+    np.testing.assert_allclose(s, [[2.0, 1.5], [1.5, 2.0]])
+    p = np.exp(s) / np.exp(s).sum(1, keepdims=True)
+    np.testing.assert_allclose(fw["p"][:, 0], p.ravel(), rtol=1e-14)
+    assert fw["p"][0, 0] > fw["p"][1, 0] and fw["p"][2, 0] < fw["p"][3, 0]
 
 
 # ---------------------------------------------------------------- row-subset mode used for sampled checks
