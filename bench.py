@@ -63,6 +63,10 @@ def algorithmic_bytes(w, graph):
                 "bwd_col": (R + 3 * s + 4, 2 * R + 3 * s + 4)},
         "agnn": {"fwd": (R + s + 4, 2 * R + 3 * s + 4), "bwd_row": (R + s + 4, 4 * R + 4 * s + 4),
                  "bwd_col": (2 * R + 3 * s + 4, 3 * R + s + 4)},
+        # GATv2: one neighbour row per edge forward and in the row pass (plus the fp32 per-row share of da),
+        # destination features, dO and the packed statistics per edge in the column pass
+        "gatv2": {"fwd": (R + 4, 2 * R + 2 * s + 4), "bwd_row": (R + 4, 4 * R + 4 * w.H * w.D + 4 * s + 4),
+                  "bwd_col": (2 * R + 2 * s + 4, 2 * R + 4)},
     }[w.model]
     res = {name: pe * graph.nnz + pn * graph.n for name, (pe, pn) in per.items()}
     # dense-tile kernels for batches of small graphs do the work of the same passes in one launch each
@@ -73,6 +77,8 @@ def algorithmic_bytes(w, graph):
         res["fwd_softmax_spmm"] = (R + s + 4) * graph.nnz + (R + 2 * s + 4) * graph.n
     if w.model == "gat":
         res["param_reduce"] = graph.n * (R + 2 * s)
+    if w.model == "gatv2":
+        res["param_reduce"] = graph.n * 4 * w.H * w.D
     if w.model == "agnn":
         res["param_reduce"] = graph.n * s
     return res
@@ -184,9 +190,9 @@ def main() -> int:
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])
-    k = dev(feats["k"]) if w.model == "gt" else None
+    k = dev(feats["k"]) if w.model in ("gt", "gatv2") else None
     v = dev(feats["v"]) if w.model == "gt" else None
-    a_l = torch.from_numpy(feats["a_l"]).cuda() if w.model == "gat" else None
+    a_l = torch.from_numpy(feats["a_l"]).cuda() if w.model in ("gat", "gatv2") else None
     a_r = torch.from_numpy(feats["a_r"]).cuda() if w.model == "gat" else None
     d_out = dev(feats["d_out"])
 
@@ -205,9 +211,9 @@ def main() -> int:
     row_max = torch.empty((N, H), dtype=torch.float32, device="cuda")
     row_sum = torch.empty((N, H), dtype=torch.float32, device="cuda")
     d_x = torch.empty_like(x)
-    d_k = torch.empty_like(x) if w.model == "gt" else None
+    d_k = torch.empty_like(x) if w.model in ("gt", "gatv2") else None
     d_v = torch.empty_like(x) if w.model == "gt" else None
-    d_a_l = torch.empty((H, w.D), dtype=torch.float32, device="cuda") if w.model == "gat" else None
+    d_a_l = torch.empty((H, w.D), dtype=torch.float32, device="cuda") if w.model in ("gat", "gatv2") else None
     d_a_r = torch.empty((H, w.D), dtype=torch.float32, device="cuda") if w.model == "gat" else None
     d_scale = torch.empty(1, dtype=torch.float32, device="cuda") if w.model == "agnn" else None
     fwd_b, bwd_b = dfgnn.workspace_bytes(g.handle, L)

@@ -20,7 +20,7 @@ from . import graphs as G
 class Workload:
     name: str
     number: int
-    model: str  # 'gt' | 'gat' | 'agnn'
+    model: str  # 'gt' | 'gat' | 'agnn' | 'gatv2'
     H: int
     D: int
     dtype: str  # 'f32' | 'bf16' (storage type of node tensors)
@@ -108,7 +108,8 @@ def _normal(seed: int, stream: int, shape, std: float = 1.0) -> np.ndarray:
 def make_features(w: Workload, n: int, seed: Optional[int] = None, threads: int = 4) -> Dict[str, np.ndarray]:
     """Node tensors [n, H, D] float32 (bf16 workloads: values already rounded to bf16).
 
-    GT: q, k, v;  GAT: feat (=Wh), a_l, a_r [H, D] fp32;  AGNN: feat (=h).
+    GT: q, k, v;  GAT: feat (=Wh), a_l, a_r [H, D] fp32;  AGNN: feat (=h);  GATv2: feat (destination-side
+    projection), k (source-side projection), a_l (= a) [H, D] fp32.
     'd_out' is the upstream gradient dL/dO.  Every tensor has its own random stream, so the values do
     not depend on `threads` (tensors are drawn concurrently).
     """
@@ -120,6 +121,8 @@ def make_features(w: Workload, n: int, seed: Optional[int] = None, threads: int 
         jobs = {"q": (s + 1, 0, shape, 1.0), "k": (s + 1, 1, shape, 1.0), "v": (s + 1, 2, shape, 1.0)}
     elif w.model == "gat":
         jobs = {"feat": (s + 1, 0, shape, 1.0), "a_l": (s + 1, 1, (w.H, w.D), 0.1), "a_r": (s + 1, 2, (w.H, w.D), 0.1)}
+    elif w.model == "gatv2":
+        jobs = {"feat": (s + 1, 0, shape, 1.0), "k": (s + 1, 1, shape, 1.0), "a_l": (s + 1, 2, (w.H, w.D), 0.1)}
     elif w.model == "agnn":
         jobs = {"feat": (s + 1, 0, shape, 1.0)}
     else:

@@ -41,7 +41,7 @@ typedef enum {
     DFGNN_EHIP = 4          /* a HIP runtime call failed (text in dfgnn_last_error)                  */
 } dfgnn_status;
 
-typedef enum { DFGNN_GT = 0, DFGNN_GAT = 1, DFGNN_AGNN = 2 } dfgnn_model;
+typedef enum { DFGNN_GT = 0, DFGNN_GAT = 1, DFGNN_AGNN = 2, DFGNN_GATV2 = 3 } dfgnn_model;
 typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
 
 /*
@@ -82,8 +82,8 @@ typedef struct {
     int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
                         of two (vec = 4 for fp32, 8 for bf16), H*D/vec <= 64, and one node tensor
                         (N*H*D elements) must stay below 4 GiB */
-    float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT: ignored */
-    float neg_slope; /* GAT: LeakyReLU slope (derivative at 0 is neg_slope) */
+    float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT, GATv2: ignored */
+    float neg_slope; /* GAT, GATv2: LeakyReLU slope (derivative at 0 is neg_slope) */
     float eps;       /* AGNN: lower clamp of the feature norm */
     int32_t reserved[1];
 } dfgnn_layer;
@@ -176,6 +176,9 @@ int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer* layer, si
  *   GT   s_ij = scale * q_i . k_j                         x = Q, k = K, v = V (Val = V)
  *   GAT  s_ij = LeakyReLU(a_l . Wh_i + a_r . Wh_j)        x = Wh, a_l, a_r [H, D] fp32 device (Val = Wh); k = v = NULL
  *   AGNN s_ij = beta * cos(h_i, h_j) per head             x = h (Val = h, un-normalised); k = v = a_l = a_r = NULL
+ *   GATv2 s_ij = sum_d a_d LeakyReLU(x_i,d + k_j,d)       x = destination-side, k = source-side projection of the
+ *        (the other member of the GAT family cited in       node features (Val = k), a_l = a [H, D] fp32 device;
+ *         Sec. 1; its score is not separable per node)       v = a_r = NULL
  * out [N,H,D] in the layer dtype; row_max, row_sum [N,H] fp32 are the softmax statistics
  * (max_j s_ij and sum_j exp(s_ij - max)) that dfgnn_backward consumes.
  * workspace: device, >= fwd_bytes of dfgnn_workspace_bytes, 256-byte aligned, contents undefined on
@@ -192,6 +195,7 @@ int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void
  *   GT   -> d_x = dL/dQ, d_k = dL/dK, d_v = dL/dV                        (d_a_l = d_a_r = d_scale = NULL)
  *   GAT  -> d_x = dL/dWh, d_a_l, d_a_r [H,D] fp32                        (d_k = d_v = d_scale = NULL)
  *   AGNN -> d_x = dL/dh, d_scale = dL/dbeta (1 float, device)            (d_k = d_v = d_a_l = d_a_r = NULL)
+ *   GATv2 -> d_x, d_k (destination- and source-side), d_a_l = dL/da      (d_v = d_a_r = d_scale = NULL)
  * Gradient node tensors are in the layer dtype.  workspace: >= bwd_bytes, 256-byte aligned.
  * Results are deterministic (no floating-point atomics).
  */

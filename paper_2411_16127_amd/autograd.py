@@ -42,6 +42,14 @@ def gat_conv(graph: Graph, wh, a_l, a_r, neg_slope: float = 0.2):
     return _FusedConv.apply(graph, layer, wh, None, None, a_l.contiguous(), a_r.contiguous())
 
 
+def gatv2_conv(graph: Graph, x_dst, x_src, a, neg_slope: float = 0.2):
+    """GATv2 convolution: scores sum_d a_d LeakyReLU(x_dst_i,d + x_src_j,d), applied to x_src.  x_dst, x_src:
+    the two projections of the node features [N,H,D]; a [H,D] (fp32)."""
+    H, D = x_dst.shape[1], x_dst.shape[2]
+    layer = Layer("gatv2", H, D, dtype="bf16" if x_dst.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    return _FusedConv.apply(graph, layer, x_dst, x_src, None, a.contiguous(), None)
+
+
 class _AgnnConv(torch.autograd.Function):
     """AGNN needs the gradient of the scalar beta, which is a layer field rather than a tensor argument."""
 

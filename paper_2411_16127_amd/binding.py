@@ -14,7 +14,7 @@ from typing import Dict, Optional, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdfgnn.so")
 
-MODEL = {"gt": 0, "gat": 1, "agnn": 2}
+MODEL = {"gt": 0, "gat": 1, "agnn": 2, "gatv2": 3}
 DTYPE = {"f32": 0, "bf16": 1}
 QUERY = {
     "row_order": 0, "row_chunk_ptr": 1, "row_chunks": 2, "t_indptr": 3, "t_indices": 4, "t_eid": 5,
@@ -52,7 +52,7 @@ class SchedParams:
 
 @dataclass
 class Layer:
-    model: str          # 'gt' | 'gat' | 'agnn'
+    model: str          # 'gt' | 'gat' | 'agnn' | 'gatv2'
     H: int
     D: int
     dtype: str = "f32"  # 'f32' | 'bf16'
@@ -325,6 +325,9 @@ class Graph:
         elif layer.model == "gat":
             d_a_l = res["d_a_l"] = torch.empty((layer.H, layer.D), dtype=torch.float32, device=self.device)
             d_a_r = res["d_a_r"] = torch.empty((layer.H, layer.D), dtype=torch.float32, device=self.device)
+        elif layer.model == "gatv2":
+            d_k = res["d_k"] = torch.empty_like(x)
+            d_a_l = res["d_a_l"] = torch.empty((layer.H, layer.D), dtype=torch.float32, device=self.device)
         else:
             d_scale = res["d_scale"] = torch.empty(1, dtype=torch.float32, device=self.device)
         ws, need = self.workspace(layer, True)

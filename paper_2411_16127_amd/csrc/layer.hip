@@ -57,7 +57,7 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
 // workspace layout (float offsets turned into pointers)
 // ---------------------------------------------------------------------------------------------
 struct Workspace {
-    size_t stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_s0, part_s1, part_s2, reduce, scores, total;
+    size_t stats, d_el, d_er, g_row, dbeta_row, part_v0, part_v1, part_v2, part_v3, part_s0, part_s1, part_s2, reduce, scores, total;
 };
 
 // the two-kernel forward comparator applies (GT on the general kernels)
@@ -72,19 +72,21 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
     const size_t N = (size_t)g->N, H = (size_t)L->H, HD = (size_t)L->H * L->D;
     const size_t chunks = backward ? (size_t)(g->n_row_chunks > g->n_col_chunks ? g->n_row_chunks : g->n_col_chunks)
                                    : (size_t)g->n_row_chunks;
-    const bool gat = L->model == DFGNN_GAT, agnn = L->model == DFGNN_AGNN;
+    const bool gat = L->model == DFGNN_GAT, agnn = L->model == DFGNN_AGNN, v2 = L->model == DFGNN_GATV2;
     W.part_v0 = take(chunks * HD);
     W.part_s0 = take(chunks * H);
     W.part_s1 = take(chunks * H);
     if (backward) {
-        W.stats = take(N * H * (L->model == DFGNN_GT ? 2 : 4));
+        W.stats = take(N * H * (L->model == DFGNN_GT || v2 ? 2 : 4));
         W.part_v1 = take(chunks * HD);
+        W.part_v2 = take(v2 ? chunks * HD : 0);
+        W.part_v3 = take(v2 ? chunks * HD : 0);
         W.part_s2 = take(chunks * H);
         W.d_el = take(gat ? N * H : 0);
         W.d_er = take(gat ? N * H : 0);
-        W.g_row = take(agnn ? N * HD : 0);
+        W.g_row = take(agnn || v2 ? N * HD : 0);
         W.dbeta_row = take(agnn ? N * H : 0);
-        W.reduce = take(gat ? (size_t)kReduceBlocks * 2 * HD : (agnn ? (size_t)kReduceBlocks : 0));
+        W.reduce = take(gat ? (size_t)kReduceBlocks * 2 * HD : (v2 ? (size_t)kRowsumBlocks * HD : (agnn ? (size_t)kReduceBlocks : 0)));
     }
     if (!backward && scores_in_memory(g, L)) W.scores = take((size_t)g->E * H);
     W.total = off;
@@ -100,6 +102,9 @@ static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward)
     if (backward) {
         a.stats = (float*)(b + W.stats);
         a.part_v1 = (float*)(b + W.part_v1);
+        a.part_v2 = (float*)(b + W.part_v2);
+        a.part_v3 = (float*)(b + W.part_v3);
+        a.da_row = (float*)(b + W.g_row);
         a.part_s2 = (float*)(b + W.part_s2);
         a.d_el = (float*)(b + W.d_el);
         a.d_er = (float*)(b + W.d_er);
@@ -179,6 +184,9 @@ template <class G> static void run_forward(const dfgnn_graph* g, int model, cons
     case DFGNN_GAT:
         run_pass<G, GatFwd>(g, false, a, kFwdLabels, st);
         break;
+    case DFGNN_GATV2:
+        run_pass<G, GatV2Fwd>(g, false, a, kFwdLabels, st);
+        break;
     default:
         run_pass<G, AgnnFwd>(g, false, a, kFwdLabels, st);
         break;
@@ -200,6 +208,23 @@ static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* 
             KernelTimer t("param_reduce", st);
             hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
             hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+        }
+        break;
+    case DFGNN_GATV2:
+        run_pass<G, GatV2BwdRow>(g, false, a, kRowLabels, st);
+        run_pass<G, GatV2BwdCol>(g, true, a, kColLabels, st);
+        {
+            KernelTimer t("param_reduce", st);
+            int w = 1;  // threads per row, 4 columns each (a power of two, so that it divides 256)
+            while (4 * w < a.HD && w < 256) w <<= 1;
+            // about 16 rows per thread of the first stage, at most kRowsumBlocks workgroups
+            int64_t blocks = ((int64_t)a.n_nodes + (256 / w) * 16 - 1) / ((256 / w) * 16);
+            if (blocks > kRowsumBlocks) blocks = kRowsumBlocks;
+            int wf = 4;
+            while (wf < a.HD && wf < 256) wf <<= 1;
+            hipLaunchKernelGGL(k_rowsum_partial, dim3((unsigned)blocks), dim3(256), 0, st, a.da_row, (int64_t)a.n_nodes,
+                               a.HD, w, reduce_tmp);
+            hipLaunchKernelGGL(k_rowsum_final, dim3(1), dim3(256), 0, st, reduce_tmp, (int)blocks, a.HD, wf, d_a_l);
         }
         break;
     default:
@@ -240,8 +265,8 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo) {
     DFGNN_REQUIRE(g != nullptr && L != nullptr, DFGNN_EINVAL, "graph / layer is NULL");
-    DFGNN_REQUIRE(L->model == DFGNN_GT || L->model == DFGNN_GAT || L->model == DFGNN_AGNN, DFGNN_EINVAL,
-                  "unknown model %d", L->model);
+    DFGNN_REQUIRE(L->model == DFGNN_GT || L->model == DFGNN_GAT || L->model == DFGNN_AGNN || L->model == DFGNN_GATV2,
+                  DFGNN_EINVAL, "unknown model %d", L->model);
     DFGNN_REQUIRE(L->reserved[0] == 0, DFGNN_EINVAL, "dfgnn_layer.reserved must be zero");
     int rc = pick_geometry(L, geo);
     if (rc != DFGNN_OK) return rc;
@@ -262,7 +287,7 @@ static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, con
     a.D = L->D;
     a.HD = L->H * L->D;
     a.lph = geo.lph;
-    a.scale = L->model == DFGNN_GAT ? 1.f : L->scale;
+    a.scale = (L->model == DFGNN_GAT || L->model == DFGNN_GATV2) ? 1.f : L->scale;
     a.c_score = a.scale * kLog2e;
     a.neg_slope = L->neg_slope;
     a.eps = L->eps;
@@ -291,13 +316,15 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
-    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2;
     if (graph->N == 0) return DFGNN_OK;  // nothing to compute; node tensors have no elements and may be NULL
     DFGNN_REQUIRE(x && out && row_max && row_sum, DFGNN_EINVAL, "x / out / row_max / row_sum is NULL");
     DFGNN_REQUIRE(!gt || (k && v), DFGNN_EINVAL, "GT needs k and v");
-    DFGNN_REQUIRE(gt || (!k && !v), DFGNN_EINVAL, "k and v must be NULL unless the model is GT");
+    DFGNN_REQUIRE(!v2 || (k && !v), DFGNN_EINVAL, "GATv2 needs k, and v must be NULL");
+    DFGNN_REQUIRE(gt || v2 || (!k && !v), DFGNN_EINVAL, "k and v must be NULL unless the model is GT or GATv2");
     DFGNN_REQUIRE(!gat || (a_l && a_r), DFGNN_EINVAL, "GAT needs a_l and a_r");
-    DFGNN_REQUIRE(gat || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT");
+    DFGNN_REQUIRE(!v2 || (a_l && !a_r), DFGNN_EINVAL, "GATv2 needs a_l, and a_r must be NULL");
+    DFGNN_REQUIRE(gat || v2 || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT or GATv2");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
     if (const int kind = dense_batch_kind(graph, layer)) {
@@ -332,22 +359,28 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
-    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN,
+               v2 = layer->model == DFGNN_GATV2;
     if (graph->N == 0) {  // no nodes: node tensors have no elements and may be NULL; parameter gradients are zero
         if (gat && d_a_l && d_a_r) {
             DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
             DFGNN_HIP(hipMemsetAsync(d_a_r, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
         }
+        if (v2 && d_a_l) DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
         if (agnn && d_scale) DFGNN_HIP(hipMemsetAsync(d_scale, 0, sizeof(float), (hipStream_t)stream));
         return DFGNN_OK;
     }
     DFGNN_REQUIRE(x && out && row_max && row_sum && d_out && d_x, DFGNN_EINVAL,
                   "x / out / row_max / row_sum / d_out / d_x is NULL");
     DFGNN_REQUIRE(!gt || (k && v && d_k && d_v), DFGNN_EINVAL, "GT needs k, v, d_k and d_v");
-    DFGNN_REQUIRE(gt || (!k && !v && !d_k && !d_v), DFGNN_EINVAL, "k, v, d_k, d_v must be NULL unless the model is GT");
+    DFGNN_REQUIRE(!v2 || (k && d_k && !v && !d_v), DFGNN_EINVAL, "GATv2 needs k and d_k; v and d_v must be NULL");
+    DFGNN_REQUIRE(gt || v2 || (!k && !v && !d_k && !d_v), DFGNN_EINVAL,
+                  "k, v, d_k, d_v must be NULL unless the model is GT or GATv2");
     DFGNN_REQUIRE(!gat || (a_l && a_r && d_a_l && d_a_r), DFGNN_EINVAL, "GAT needs a_l, a_r, d_a_l and d_a_r");
-    DFGNN_REQUIRE(gat || (!a_l && !a_r && !d_a_l && !d_a_r), DFGNN_EINVAL,
-                  "a_l, a_r, d_a_l, d_a_r must be NULL unless the model is GAT");
+    DFGNN_REQUIRE(!v2 || (a_l && d_a_l && !a_r && !d_a_r), DFGNN_EINVAL,
+                  "GATv2 needs a_l and d_a_l; a_r and d_a_r must be NULL");
+    DFGNN_REQUIRE(gat || v2 || (!a_l && !a_r && !d_a_l && !d_a_r), DFGNN_EINVAL,
+                  "a_l, a_r, d_a_l, d_a_r must be NULL unless the model is GAT or GATv2");
     DFGNN_REQUIRE(!agnn || d_scale, DFGNN_EINVAL, "AGNN needs d_scale");
     DFGNN_REQUIRE(agnn || !d_scale, DFGNN_EINVAL, "d_scale must be NULL unless the model is AGNN");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&

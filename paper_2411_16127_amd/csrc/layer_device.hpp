@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 namespace dfgnn {
 
@@ -183,6 +184,9 @@ struct Args {
     float* dbeta_row;  // AGNN [N,H]
     float* part_v0;    // [chunks, HD]
     float* part_v1;    // [chunks, HD]
+    float* part_v2;    // [chunks, HD] (GATv2 backward)
+    float* part_v3;    // [chunks, HD] (GATv2 backward)
+    float* da_row;     // GATv2 [N,HD] per-row contribution to the gradient of the attention vector
     float* part_s0;    // [chunks, H]
     float* part_s1;    // [chunks, H]
     float* part_s2;    // [chunks, H]
@@ -215,10 +219,10 @@ struct PartialIndex {
     __device__ explicit PartialIndex(const Ctx& c) : f0(c.active ? c.f0 : 0), h(c.h) {}
 };
 
-// One chunk's partial results as loaded by a merge wavefront: up to two feature vectors and three
+// One chunk's partial results as loaded by a merge wavefront: up to four feature vectors and three
 // per-head scalars (each pass uses the ones it stored; chunks of an absent index are masked when folded).
 template <int VEC> struct PartialRegs {
-    float v0[VEC], v1[VEC], s0, s1, s2;
+    float v0[VEC], v1[VEC], v2[VEC], v3[VEC], s0, s1, s2;
 };
 
 template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int node) {
@@ -793,6 +797,216 @@ template <class G, int U> struct GatBwdCol {
 };
 
 // =============================================================================================
+// GATv2 (the second member of the GAT family cited in Sec. 1): s_ij = sum_d a_d LeakyReLU(x_i,d + k_j,d),
+// x = destination-side and k = source-side projection; the aggregated value is k_j.  The score is not a
+// sum of two per-node scalars, so every edge costs a D-wide elementwise pass over the gathered row; the
+// memory traffic is that of GAT (one neighbour row per edge).
+// =============================================================================================
+template <class G, int U> struct GatV2Fwd {
+    static constexpr int VEC = G::VEC;
+    float x[VEC], al2[VEC];  // destination features; this lane's slice of a * log2e
+    SoftmaxAcc<G, U> sm;
+    u32x4 K[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, x);
+        load_attention<G>(a.a_l, c, kLog2e, al2);
+        sm.reset();
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { K[u] = gather_raw<G>(a.k, a, c, j); }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[VEC], t = 0.f;
+            Elem<typename G::T>::unpack(K[u], kf);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) t = fmaf(al2[i], leaky(x[i] + kf[i], a.neg_slope), t);
+            s[u] = head_sum<G::LPH>(t, a.lph);
+            if (!FULL && j[u] < 0) s[u] = -INFINITY;
+        }
+        if (!FULL && j[0] < 0) return;
+        sm.update(s, K);
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
+    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
+    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
+};
+
+// Row side: with z_d = x_i,d + k_j,d,  dX_i,d = a_d sum_j dS_ij LeakyReLU'(z_d)  and the row's share of
+// da_d = sum_ij dS_ij LeakyReLU(z_d)  (summed over rows afterwards).  The factor a_d is applied once at the end.
+template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
+    static constexpr int VEC = G::VEC;
+    static constexpr bool kExact = RowBackwardBase<G>::kExact;
+    static constexpr int kMergeBatch = kExact ? 2 : 4;  // four partial vectors per chunk: keep the merge in registers
+    float x[VEC], al2[VEC], dx[VEC], da[VEC];
+    float px[VEC], pa[VEC];  // sum_j p LeakyReLU'(z), sum_j p LeakyReLU(z)  (kExact only)
+    u32x4 K[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.x, c, x);
+        load_attention<G>(a.a_l, c, kLog2e, al2);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dx[i] = 0.f; da[i] = 0.f; px[i] = 0.f; pa[i] = 0.f; }
+        this->init_row(a, c);
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { K[u] = gather_raw<G>(a.k, a, c, j); }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[VEC], lr[VEC], sl[VEC], t = 0.f;
+            Elem<typename G::T>::unpack(K[u], kf);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float z = x[i] + kf[i];
+                sl[i] = z > 0.f ? 1.f : a.neg_slope;
+                lr[i] = z * sl[i];
+                t = fmaf(al2[i], lr[i], t);
+            }
+            const float s = head_sum<G::LPH>(t, a.lph);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, kf), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
+            if constexpr (kExact) {
+                const float w = p * dp;
+                this->dsum += w;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    dx[i] = fmaf(w, sl[i], dx[i]); da[i] = fmaf(w, lr[i], da[i]);
+                    px[i] = fmaf(p, sl[i], px[i]); pa[i] = fmaf(p, lr[i], pa[i]);
+                }
+            } else {
+                const float ds = p * (dp - this->delta);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) { dx[i] = fmaf(ds, sl[i], dx[i]); da[i] = fmaf(ds, lr[i], da[i]); }
+            }
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dx[i] = slot_sum<G::LPE>(dx[i]); da[i] = slot_sum<G::LPE>(da[i]); }
+        if constexpr (kExact) {
+            this->dsum = slot_sum<G::LPE>(this->dsum);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { px[i] = slot_sum<G::LPE>(px[i]); pa[i] = slot_sum<G::LPE>(pa[i]); }
+        }
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (!c.writer || !c.active) return;
+        const size_t o = (size_t)item * a.HD + c.f0;
+        store_f32<VEC>(a.part_v0 + o, dx);
+        store_f32<VEC>(a.part_v1 + o, da);
+        if constexpr (kExact) {
+            store_f32<VEC>(a.part_v2 + o, px);
+            store_f32<VEC>(a.part_v3 + o, pa);
+            if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
+        }
+    }
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
+        const PartialIndex c(c0);
+        const size_t o = (size_t)chunk * a.HD + c.f0;
+        load_f32<VEC>(a.part_v0 + o, P.v0);
+        load_f32<VEC>(a.part_v1 + o, P.v1);
+        if constexpr (kExact) {
+            load_f32<VEC>(a.part_v2 + o, P.v2);
+            load_f32<VEC>(a.part_v3 + o, P.v3);
+            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
+        }
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dx[i] = fmaf(w, P.v0[i], dx[i]); da[i] = fmaf(w, P.v1[i], da[i]); }
+        if constexpr (kExact) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { px[i] = fmaf(w, P.v2[i], px[i]); pa[i] = fmaf(w, P.v3[i], pa[i]); }
+            this->dsum = fmaf(w, P.s2, this->dsum);
+        }
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (!c.writer || !c.active) return;
+        if constexpr (kExact) {
+            this->delta = this->dsum;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { dx[i] -= this->delta * px[i]; da[i] -= this->delta * pa[i]; }
+        }
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = al2[i] * kLn2 * dx[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
+        store_f32<VEC>(a.da_row + c.off, da);
+        if (c.head0) {
+            f32x2 st = {this->lse2, this->delta};
+            *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)c.node * a.H + c.h)) = st;
+        }
+    }
+};
+
+// Column side: dK_j = sum_i p_ij dO_i + a (.) sum_i dS_ij LeakyReLU'(z_ij), p and dS recomputed per edge
+template <class G, int U> struct GatV2BwdCol {
+    static constexpr int VEC = G::VEC;
+    float kk[VEC], al2[VEC], dk[VEC], dz[VEC];
+    u32x4 X[U], Gd[U];
+    f32x2 St[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.k, c, kk);
+        load_attention<G>(a.a_l, c, kLog2e, al2);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] = 0.f; dz[i] = 0.f; }
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
+        X[u] = gather_raw<G>(a.x, a, c, i);
+        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
+        St[u] = gather_stats2(a, c, i);
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float xf[VEC], gf[VEC], sl[VEC], t = 0.f;
+            Elem<typename G::T>::unpack(X[u], xf);
+            Elem<typename G::T>::unpack(Gd[u], gf);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float z = xf[i] + kk[i];
+                sl[i] = z > 0.f ? 1.f : a.neg_slope;
+                t = fmaf(al2[i], z * sl[i], t);
+            }
+            const float s = head_sum<G::LPH>(t, a.lph);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, kk), a.lph);
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
+            const float ds = p * (dp - St[u][1]);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(p, gf[i], dk[i]); dz[i] = fmaf(ds, sl[i], dz[i]); }
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dz[i] = slot_sum<G::LPE>(dz[i]); }
+    }
+    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
+        if (!c.writer || !c.active) return;
+        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
+        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dz);
+    }
+    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
+        const PartialIndex c(c0);
+        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
+        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
+    }
+    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
+        const float w = valid ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(w, P.v0[i], dk[i]); dz[i] = fmaf(w, P.v1[i], dz[i]); }
+    }
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (!c.writer || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = fmaf(al2[i] * kLn2, dz[i], dk[i]);
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_k) + c.off, o);
+    }
+};
+
+// =============================================================================================
 // AGNN (Sec. 5.1): s_ij = beta * cos(h_i, h_j); aggregated value is the raw feature row
 // =============================================================================================
 // 1 / max(|h|, eps) from the squared norm.  The norm of a neighbour is taken from its gathered row
@@ -1128,6 +1342,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
     }
 }
 
+// chunks a merge wavefront loads per edge slot before folding them in (a pass may ask for fewer)
+template <class P, class = void> struct merge_batch { static constexpr int value = 8; };
+template <class P> struct merge_batch<P, std::void_t<decltype(P::kMergeBatch)>> { static constexpr int value = P::kMergeBatch; };
+
 // One wavefront per super row / column: the edge slots take the row's chunks round-robin and sum (or,
 // for the forward pass, softmax-merge) their partial results, the slots are combined as in the direct
 // pass, and the row is finished exactly as the direct pass would.  Summation order is fixed.
@@ -1144,7 +1362,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     p.init(a, c);
     // kMergeBatch chunks per edge slot are loaded before any is folded in (absent ones read the row's
     // first chunk and are masked), so the loop has no per-lane branch and its loads overlap
-    constexpr int kMergeBatch = 8;
+    constexpr int kMergeBatch = merge_batch<PassT<G, U>>::value;
     for (int base = c0; base < c1; base += G::EPW * kMergeBatch) {
         PartialRegs<G::VEC> P[kMergeBatch];
 #pragma unroll
@@ -1291,6 +1509,68 @@ __device__ inline float block_sum_256(float v) {
 [[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, float* __restrict__ out) {
     const float t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.f);
     if (threadIdx.x == 0) *out = t;
+}
+
+// Column sums of a row-major [n, hd] fp32 array (hd a multiple of 4) in two stages with a fixed summation
+// order: thread t of a workgroup owns the 4 columns 4 * (t % w) .. +3 and every (256 / w)-th row of the
+// workgroup's rows, four rows in flight at a time.
+constexpr int kRowsumBlocks = 1024;
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_rowsum_partial(const float* __restrict__ in, int64_t n, int hd, int w,
+                                                        float* __restrict__ partial) {
+    __shared__ f32x4 red[256];
+    const int rows_par = 256 / w, rs = threadIdx.x / w, fc = threadIdx.x % w;
+    const int64_t stride = (int64_t)gridDim.x * rows_par;
+    for (int f0 = 0; f0 < hd; f0 += 4 * w) {
+        const int f = f0 + 4 * fc;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (f < hd) {
+            int64_t r = (int64_t)blockIdx.x * rows_par + rs;
+            for (; r + 3 * stride < n; r += 4 * stride) {
+                f32x4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const f32x4*>(in + (r + k * stride) * hd + f);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc += v[k];
+            }
+            for (; r < n; r += stride) acc += *reinterpret_cast<const f32x4*>(in + r * hd + f);
+        }
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        if (rs == 0 && f < hd) {
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < rows_par; ++k) t += red[k * w + fc];
+            *reinterpret_cast<f32x4*>(partial + (size_t)blockIdx.x * hd + f) = t;
+        }
+        __syncthreads();
+    }
+}
+
+// second stage: thread t owns column t % wf and every (256 / wf)-th partial row; fixed order
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_rowsum_final(const float* __restrict__ partial, int nblocks, int hd,
+                                                      int wf, float* __restrict__ out) {
+    __shared__ float red[256];
+    const int groups = 256 / wf, bs = threadIdx.x / wf, fc = threadIdx.x % wf;
+    for (int f0 = 0; f0 < hd; f0 += wf) {
+        const int f = f0 + fc;
+        float sum = 0.f;
+        if (f < hd) {
+            for (int b = bs; b < nblocks; b += 16 * groups) {
+                float v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * hd + f] : 0.f;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) sum += v[k];
+            }
+        }
+        red[threadIdx.x] = sum;
+        __syncthreads();
+        if (bs == 0 && f < hd) {
+            float t = 0.f;
+            for (int k = 0; k < groups; ++k) t += red[k * wf + fc];
+            out[f] = t;
+        }
+        __syncthreads();
+    }
 }
 
 }  // namespace dfgnn

@@ -41,7 +41,7 @@ def run_gpu(graph, w, feats, sched=None, g=None, use_batch=True):
     L = gpu_layer(w)
     f32 = lambda name: None if name not in feats else torch.from_numpy(feats[name]).cuda()
     x = to_device(feats["q"] if w.model == "gt" else feats["feat"], w.dtype)
-    k = to_device(feats["k"], w.dtype) if w.model == "gt" else None
+    k = to_device(feats["k"], w.dtype) if w.model in ("gt", "gatv2") else None
     v = to_device(feats["v"], w.dtype) if w.model == "gt" else None
     a_l, a_r = f32("a_l"), f32("a_r")
     d_out = to_device(feats["d_out"], w.dtype)
