@@ -48,7 +48,7 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, graph):
+def algorithmic_bytes(w, graph, edge_bias=False):
     """Bytes each kernel must move if no neighbour row were ever reused from cache (gather model).
 
     R = bytes of one node row, s = 4*H bytes of one fp32 scalar per head; per-edge and per-row figures of
@@ -68,6 +68,11 @@ def algorithmic_bytes(w, graph):
         "gatv2": {"fwd": (R + 4, 2 * R + 2 * s + 4), "bwd_row": (R + 4, 4 * R + 4 * w.H * w.D + 4 * s + 4),
                   "bwd_col": (2 * R + 2 * s + 4, 2 * R + 4)},
     }[w.model]
+    if edge_bias:  # the edge term is read by every pass (the column pass also reads its position); dS is
+        # written by the row pass for fp32 layers and by the column pass for bf16 layers
+        f32 = w.dtype == "f32"
+        extra = {"fwd": s, "bwd_row": 2 * s if f32 else s, "bwd_col": s + 4 if f32 else 2 * s + 4}
+        per = {name: (pe + extra[name], pn) for name, (pe, pn) in per.items()}
     res = {name: pe * graph.nnz + pn * graph.n for name, (pe, pn) in per.items()}
     # dense-tile kernels for batches of small graphs do the work of the same passes in one launch each
     res["dense_fwd"] = res["fwd"]
@@ -142,6 +147,8 @@ def main() -> int:
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one step (forward + backward) into a HIP graph and replay it K times in the timed region")
     ap.add_argument("--force-dense-batch", action="store_true", help="dense-tile batch kernels whenever they apply")
+    ap.add_argument("--edge-bias", action="store_true",
+                    help="variant: add a seeded N(0,1) per-edge term [E,H] to the scores and compute its gradient")
     ap.add_argument("--scores-in-memory", action="store_true",
                     help="comparator: GT forward as an edge-parallel SDDMM kernel that writes the scores plus a softmax+SpMM kernel")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
@@ -220,12 +227,25 @@ def main() -> int:
     ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
 
+    bias = d_bias = None
+    if args.edge_bias:
+        gen = torch.Generator(device="cuda").manual_seed(w.seed + 3)
+        bias = torch.randn((graph.nnz, H), dtype=torch.float32, device="cuda", generator=gen)
+        d_bias = torch.empty_like(bias)
+
     def fwd():
-        dfgnn.forward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+        if bias is None:
+            dfgnn.forward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+        else:
+            dfgnn.forward_edge_bias(g.handle, L, x, k, v, a_l, a_r, bias, out, row_max, row_sum, ws, ws.numel(), stream)
 
     def bwd():
-        dfgnn.backward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l, d_a_r,
-                       d_scale, ws, ws.numel(), stream)
+        if bias is None:
+            dfgnn.backward(g.handle, L, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l, d_a_r,
+                           d_scale, ws, ws.numel(), stream)
+        else:
+            dfgnn.backward_edge_bias(g.handle, L, x, k, v, a_l, a_r, bias, out, row_max, row_sum, d_out, d_x, d_k, d_v,
+                                     d_a_l, d_a_r, d_scale, d_bias, ws, ws.numel(), stream)
 
     for _ in range(args.warmup):
         fwd(); bwd()
@@ -282,7 +302,7 @@ def main() -> int:
     gedges = graph.nnz / (ms_per_step * 1e-3) / 1e9
     log(f"{ms_per_step:.3f} ms/step (fwd {fwd_ms:.3f} + bwd {bwd_ms:.3f}), {gedges:.3f} GEdges/s")
 
-    model_bytes = algorithmic_bytes(w, graph)
+    model_bytes = algorithmic_bytes(w, graph, args.edge_bias)
     kern = {}
     for label, (ms, launches) in kernels.items():
         avg = ms / max(launches, 1)
@@ -305,7 +325,7 @@ def main() -> int:
         "value": round(gedges, 4), "unit": "GEdges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
-        "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
+        "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else "") + (" + edge term" if args.edge_bias else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
                    "super_threshold": T, "chunk_edges": C, "stands_in_for": w.stands_in_for},
         "roofline": roofline,
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "preprocess_ms": round(preprocess_ms, 2),
@@ -315,7 +335,7 @@ def main() -> int:
         "kernels": kern,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.edge_bias:
         target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 3000000, "cfg5": 2000000}[w.name]
         info, (rows, new_rows, fw, bw) = cpu_baseline(w, graph, feats, target)
         # the sampled rows double as a parity spot check of the buffers that were just timed

@@ -205,6 +205,24 @@ int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const voi
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same two calls with an additive per-edge term in the score (edge features entering the attention
+ * score, Sec. 1): s_ij = (model score) + edge_bias[t, h] for the edge stored at CSR position t, before the
+ * edge softmax of Appendix A.  edge_bias: [E, H] fp32 device, caller-owned, in the order of d_indices;
+ * NULL = no edge term (then the calls are dfgnn_forward / dfgnn_backward); E*H*4 bytes must stay below 4 GiB.  d_edge_bias: [E, H] fp32
+ * device, receives dL/d edge_bias = dS of every edge (Appendix B's dL/dS before it is multiplied into Q
+ * and K); may be NULL when the term is not trained.  Works for every model; batches of small graphs use the
+ * general kernels when an edge term is given (the dense-tile kernels have none).  Same errors as above.
+ */
+int dfgnn_forward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                            const void* v, const float* a_l, const float* a_r, const float* edge_bias, void* out,
+                            float* row_max, float* row_sum, void* workspace, size_t workspace_bytes, void* stream);
+int dfgnn_backward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                             const void* v, const float* a_l, const float* a_r, const float* edge_bias,
+                             const void* out, const float* row_max, const float* row_sum, const void* d_out, void* d_x,
+                             void* d_k, void* d_v, float* d_a_l, float* d_a_r, float* d_scale, float* d_edge_bias,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Optional per-kernel timing for benchmarks (the measurement protocol of Sec. 5.2 reports kernel time).
  * dfgnn_timing_enable(1) makes every later layer call record a pair of HIP events around each kernel
  * it launches, on the stream of that call; dfgnn_timing_enable(0) stops it.  Either call discards

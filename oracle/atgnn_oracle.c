@@ -22,6 +22,8 @@
  *          a = a_l; the non-linearity sits between the two linear maps, so the ranking of the neighbours
  *          depends on the destination)
  * Aggregated value rows: GT V, GAT X, AGNN X (the un-normalised features), GATv2 K.
+ * Optional edge term (edge features entering the score, Sec. 1): bias[t,h] for CSR position t is added
+ * to s_ij before the softmax; its gradient is dS of that edge.
  */
 #include <math.h>
 #include <stdint.h>
@@ -49,6 +51,7 @@ typedef struct {
     const double* K;   /* GT keys; GATv2 source-side features */
     const double* Val; /* aggregated rows: GT V, GATv2 K, else X */
     const double* a;   /* GATv2 attention vector [H,D] */
+    const double* bias; /* optional [nnz,H] additive edge term, NULL = none */
     double* el;        /* GAT [N,H] */
     double* er;        /* GAT [N,H] */
     double* nrm;       /* AGNN [N,H]: max(||x||, eps) */
@@ -103,7 +106,15 @@ static double gat_z(const ctx_t* c, int64_t i, int64_t j, int h) {
     return c->el[i * c->L->H + h] + c->er[j * c->L->H + h];
 }
 
-static double score(const ctx_t* c, int64_t i, int64_t j, int h) {
+static double model_score(const ctx_t* c, int64_t i, int64_t j, int h);
+
+/* score of the edge stored at CSR position t of row i */
+static double score(const ctx_t* c, int64_t i, int64_t t, int h) {
+    const double s = model_score(c, i, c->indices[t], h);
+    return c->bias ? s + c->bias[t * c->L->H + h] : s;
+}
+
+static double model_score(const ctx_t* c, int64_t i, int64_t j, int h) {
     const int H = c->L->H, D = c->L->D;
     switch (c->L->model) {
     case ATGNN_GT:
@@ -130,7 +141,7 @@ static void row_softmax(const ctx_t* c, int64_t i, int h, double* p, double* zma
     const int64_t b = c->indptr[i], e = c->indptr[i + 1];
     double m = -INFINITY, l = 0.0;
     for (int64_t t = b; t < e; ++t) { /* round 1: scores and their maximum */
-        p[t - b] = score(c, i, c->indices[t], h);
+        p[t - b] = score(c, i, t, h);
         if (p[t - b] > m) m = p[t - b];
     }
     for (int64_t t = b; t < e; ++t) { /* round 2: exponentials and their sum */
@@ -155,11 +166,12 @@ static int64_t max_degree(int64_t N, const int32_t* indptr) {
  */
 int atgnn_oracle_forward(const atgnn_layer* L, int64_t N, const int32_t* indptr, const int32_t* indices,
                          const double* X, const double* K, const double* V, const double* a_l, const double* a_r,
-                         int64_t n_rows, const int64_t* rows,
+                         const double* bias, int64_t n_rows, const int64_t* rows,
                          double* O, double* row_max, double* row_sum, double* P) {
     const int H = L->H, D = L->D;
     ctx_t c;
     if (ctx_init(&c, L, N, indptr, indices, X, K, V, a_l, a_r)) { ctx_free(&c); return -1; }
+    c.bias = bias;
     double* p = (double*)malloc(sizeof(double) * (size_t)(max_degree(N, indptr) + 1));
     const int64_t count = rows ? n_rows : N;
     for (int64_t r = 0; r < count; ++r) {
@@ -203,17 +215,18 @@ int atgnn_oracle_forward(const atgnn_layer* L, int64_t N, const int32_t* indptr,
  *          dX_v += (g_v - (g_v . xhat_v) xhat_v) / ||x_v||   (||x_v|| > eps), else g_v / eps
  *   GATv2: z_d = X_i,d + K_j,d; dz_d = dS_ij a_d (z_d > 0 ? 1 : neg_slope); dX_i += dz; dK_j += dz (on top of
  *          the value term p_ij G_i);  da_l[h,d] += dS_ij LeakyReLU(z_d)
- * dS_out (optional) [nnz,H] receives dS of every processed edge.
+ * dS_out (optional) [nnz,H] receives dS of every processed edge (= the gradient of the edge term).
  */
 int atgnn_oracle_backward(const atgnn_layer* L, int64_t N, const int32_t* indptr, const int32_t* indices,
                           const double* X, const double* K, const double* V, const double* a_l, const double* a_r,
-                          const double* G, int64_t n_rows, const int64_t* rows,
+                          const double* bias, const double* G, int64_t n_rows, const int64_t* rows,
                           double* dX, double* dK, double* dV, double* da_l, double* da_r, double* dscale,
                           double* dS_out) {
     const int H = L->H, D = L->D;
     const size_t NHD = (size_t)N * H * D;
     ctx_t c;
     if (ctx_init(&c, L, N, indptr, indices, X, K, V, a_l, a_r)) { ctx_free(&c); return -1; }
+    c.bias = bias;
     const int64_t md = max_degree(N, indptr);
     double* p = (double*)malloc(sizeof(double) * (size_t)(md + 1));
     double* dP = (double*)malloc(sizeof(double) * (size_t)(md + 1));

@@ -81,10 +81,11 @@ def _graph(indptr, indices):
     return ip, ix, n
 
 
-def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, rows=None,
+def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, edge_bias=None, rows=None,
             want_p: bool = False) -> Dict[str, np.ndarray]:
     """x: GT Q / GAT Wh / AGNN h / GATv2 destination-side features, [N,H,D]; k: GT K / GATv2 source-side
-    features; a_l: GAT left vector / GATv2 attention vector.  Returns out [N,H,D], row_max, row_sum [N,H] (float64)
+    features; a_l: GAT left vector / GATv2 attention vector; edge_bias: optional [nnz,H] term added to the
+    scores (CSR edge order).  Returns out [N,H,D], row_max, row_sum [N,H] (float64)
     and optionally p [nnz,H].  With `rows`, only those rows are filled (others stay NaN)."""
     lib = _load()
     ip, ix, n = _graph(indptr, indices)
@@ -97,6 +98,8 @@ def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=N
         assert al_ is not None and ar_ is not None and al_.size == H * D and ar_.size == H * D
     if layer.model == "gatv2":
         assert k_ is not None and k_.size == x_.size and al_ is not None and al_.size == H * D
+    b_, bp = _f64(edge_bias)
+    assert b_ is None or b_.size == ix.size * H
     r_, nr, rp = _rows(rows)
     fill = np.nan if rows is not None else 0.0
     out = np.full((n, H, D), fill, dtype=np.float64)
@@ -105,7 +108,7 @@ def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=N
     p = np.full((ix.size, H), np.nan, dtype=np.float64) if want_p else None
     cl = layer._c()
     rc = lib.atgnn_oracle_forward(ctypes.byref(cl), ctypes.c_int64(n), ip.ctypes.data_as(ctypes.c_void_p),
-                                  ix.ctypes.data_as(ctypes.c_void_p), xp, kp, vp, alp, arp, nr, rp,
+                                  ix.ctypes.data_as(ctypes.c_void_p), xp, kp, vp, alp, arp, bp, nr, rp,
                                   out.ctypes.data_as(ctypes.c_void_p), rmax.ctypes.data_as(ctypes.c_void_p),
                                   rsum.ctypes.data_as(ctypes.c_void_p),
                                   p.ctypes.data_as(ctypes.c_void_p) if want_p else ctypes.c_void_p(None))
@@ -117,16 +120,19 @@ def forward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=N
     return res
 
 
-def backward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, d_out, rows=None,
-             want_ds: bool = False) -> Dict[str, np.ndarray]:
+def backward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=None, edge_bias=None, d_out,
+             rows=None, want_ds: bool = False) -> Dict[str, np.ndarray]:
     """Gradients of sum(O * d_out): d_x [N,H,D]; GT also d_k, d_v; GAT also d_a_l, d_a_r [H,D];
-    AGNN also d_scale (d beta); GATv2 also d_k, d_a_l.  With `rows`, see the completeness note in atgnn_oracle.c."""
+    AGNN also d_scale (d beta); GATv2 also d_k, d_a_l; with want_ds, ds [nnz,H] (which is also the gradient
+    of edge_bias).  With `rows`, see the completeness note in atgnn_oracle.c."""
     lib = _load()
     ip, ix, n = _graph(indptr, indices)
     H, D = layer.H, layer.D
     x_, xp = _f64(x); k_, kp = _f64(k); v_, vp = _f64(v); al_, alp = _f64(a_l); ar_, arp = _f64(a_r)
     g_, gp = _f64(d_out)
+    b_, bp = _f64(edge_bias)
     assert x_.size == n * H * D and g_.size == x_.size
+    assert b_ is None or b_.size == ix.size * H
     r_, nr, rp = _rows(rows)
     null = ctypes.c_void_p(None)
     dx = np.empty((n, H, D), dtype=np.float64)
@@ -151,7 +157,7 @@ def backward(layer: Layer, indptr, indices, *, x, k=None, v=None, a_l=None, a_r=
     ds = np.full((ix.size, H), np.nan, dtype=np.float64) if want_ds else None
     cl = layer._c()
     rc = lib.atgnn_oracle_backward(ctypes.byref(cl), ctypes.c_int64(n), ip.ctypes.data_as(ctypes.c_void_p),
-                                   ix.ctypes.data_as(ctypes.c_void_p), xp, kp, vp, alp, arp, gp, nr, rp,
+                                   ix.ctypes.data_as(ctypes.c_void_p), xp, kp, vp, alp, arp, bp, gp, nr, rp,
                                    dx.ctypes.data_as(ctypes.c_void_p), dkp, dvp, dalp, darp, ctypes.byref(dscale),
                                    ds.ctypes.data_as(ctypes.c_void_p) if want_ds else null)
     if rc != 0:

@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     workspace_bytes,
     forward,
     backward,
+    forward_edge_bias,
+    backward_edge_bias,
     timing_enable,
     timing_collect,
     QUERY,

@@ -10,29 +10,32 @@ from .binding import Graph, Layer
 
 class _FusedConv(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, graph: Graph, layer: Layer, x, k, v, a_l, a_r):
-        x, k, v = (None if t is None else t.contiguous() for t in (x, k, v))
-        out, row_max, row_sum = graph.forward(layer, x, k, v, a_l, a_r)
+    def forward(ctx, graph: Graph, layer: Layer, x, k, v, a_l, a_r, edge_bias=None):
+        x, k, v, edge_bias = (None if t is None else t.contiguous() for t in (x, k, v, edge_bias))
+        out, row_max, row_sum = graph.forward(layer, x, k, v, a_l, a_r, edge_bias=edge_bias)
         ctx.graph, ctx.layer = graph, layer
-        ctx.save_for_backward(*(t for t in (x, k, v, a_l, a_r, out, row_max, row_sum) if t is not None))
-        ctx.has = tuple(t is not None for t in (x, k, v, a_l, a_r))
+        ctx.save_for_backward(*(t for t in (x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum) if t is not None))
+        ctx.has = tuple(t is not None for t in (x, k, v, a_l, a_r, edge_bias))
+        ctx.bias_grad = edge_bias is not None and edge_bias.requires_grad
         return out
 
     @staticmethod
     def backward(ctx, d_out):
         saved = list(ctx.saved_tensors)
-        x, k, v, a_l, a_r = (saved.pop(0) if h else None for h in ctx.has)
+        x, k, v, a_l, a_r, edge_bias = (saved.pop(0) if h else None for h in ctx.has)
         out, row_max, row_sum = saved
-        g = ctx.graph.backward(ctx.layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out.contiguous())
-        return (None, None, g["d_x"], g.get("d_k"), g.get("d_v"), g.get("d_a_l"), g.get("d_a_r"))
+        g = ctx.graph.backward(ctx.layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out.contiguous(),
+                               edge_bias=edge_bias, want_d_edge_bias=ctx.bias_grad)
+        return (None, None, g["d_x"], g.get("d_k"), g.get("d_v"), g.get("d_a_l"), g.get("d_a_r"), g.get("d_edge_bias"))
 
 
-def gt_conv(graph: Graph, q, k, v, scale=None):
-    """Graph-transformer convolution: softmax over in-neighbours of scale * q_i.k_j, applied to v.  [N,H,D]."""
+def gt_conv(graph: Graph, q, k, v, scale=None, edge_bias=None):
+    """Graph-transformer convolution: softmax over in-neighbours of scale * q_i.k_j (+ edge_bias [E,H], fp32, in
+    CSR edge order, if given), applied to v.  [N,H,D]."""
     H, D = q.shape[1], q.shape[2]
     layer = Layer("gt", H, D, dtype="bf16" if q.dtype == torch.bfloat16 else "f32",
                   scale=float(D) ** -0.5 if scale is None else float(scale))
-    return _FusedConv.apply(graph, layer, q, k, v, None, None)
+    return _FusedConv.apply(graph, layer, q, k, v, None, None, edge_bias)
 
 
 def gat_conv(graph: Graph, wh, a_l, a_r, neg_slope: float = 0.2):

@@ -95,11 +95,14 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
         L.dfgnn_backward.argtypes = [vp, vp] + [vp] * 15 + [vp, sz, vp]
+        L.dfgnn_forward_edge_bias.argtypes = [vp, vp] + [vp] * 9 + [vp, sz, vp]
+        L.dfgnn_backward_edge_bias.argtypes = [vp, vp] + [vp] * 17 + [vp, sz, vp]
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
         for name in ("dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
-                     "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward"):
+                     "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward",
+                     "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -212,6 +215,24 @@ def backward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_o
                                 _stream(stream)), "dfgnn_backward")
 
 
+def forward_edge_bias(handle, layer: Layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, workspace,
+                      workspace_bytes_: int, stream=None) -> None:
+    cl = layer._c()
+    _check(lib().dfgnn_forward_edge_bias(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r),
+                                         _ptr(edge_bias), _ptr(out), _ptr(row_max), _ptr(row_sum), _ptr(workspace),
+                                         workspace_bytes_, _stream(stream)), "dfgnn_forward_edge_bias")
+
+
+def backward_edge_bias(handle, layer: Layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, d_out, d_x, d_k, d_v,
+                       d_a_l, d_a_r, d_scale, d_edge_bias, workspace, workspace_bytes_: int, stream=None) -> None:
+    cl = layer._c()
+    _check(lib().dfgnn_backward_edge_bias(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r),
+                                          _ptr(edge_bias), _ptr(out), _ptr(row_max), _ptr(row_sum), _ptr(d_out),
+                                          _ptr(d_x), _ptr(d_k), _ptr(d_v), _ptr(d_a_l), _ptr(d_a_r), _ptr(d_scale),
+                                          _ptr(d_edge_bias), _ptr(workspace), workspace_bytes_, _stream(stream)),
+           "dfgnn_backward_edge_bias")
+
+
 def timing_enable(enable: bool) -> None:
     _check(lib().dfgnn_timing_enable(1 if enable else 0), "dfgnn_timing_enable")
 
@@ -302,21 +323,35 @@ class Graph:
             if t is not None and (t.dtype != torch.float32 or t.numel() != self.N * layer.H):
                 raise ValueError("softmax statistics must be float32 [N, H]")
 
-    def forward(self, layer: Layer, x, k=None, v=None, a_l=None, a_r=None, stream=None):
-        """Allocates out / row_max / row_sum and calls dfgnn_forward."""
+    def _check_edge_tensor(self, layer: Layer, t) -> None:
+        import torch
+        if t is not None and (t.dtype != torch.float32 or t.numel() != self.E * layer.H or t.device != self.device
+                              or not t.is_contiguous()):
+            raise ValueError(f"edge term must be contiguous float32 with {self.E}x{layer.H} elements on {self.device}")
+
+    def forward(self, layer: Layer, x, k=None, v=None, a_l=None, a_r=None, stream=None, edge_bias=None):
+        """Allocates out / row_max / row_sum and calls dfgnn_forward (dfgnn_forward_edge_bias with an edge term)."""
         import torch
         self._check_tensors(layer, (x, k, v), (a_l, a_r))
+        self._check_edge_tensor(layer, edge_bias)
         out = torch.empty_like(x)
         row_max = torch.empty((self.N, layer.H), dtype=torch.float32, device=self.device)
         row_sum = torch.empty((self.N, layer.H), dtype=torch.float32, device=self.device)
         ws, need = self.workspace(layer, False)
-        forward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+        if edge_bias is None:
+            forward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, ws, ws.numel(), stream)
+        else:
+            forward_edge_bias(self.handle, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, ws, ws.numel(),
+                              stream)
         return out, row_max, row_sum
 
-    def backward(self, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, stream=None):
-        """Allocates the gradient tensors and calls dfgnn_backward; returns a dict."""
+    def backward(self, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, stream=None, edge_bias=None,
+                 want_d_edge_bias: bool = True):
+        """Allocates the gradient tensors and calls dfgnn_backward (dfgnn_backward_edge_bias with an edge term,
+        which adds 'd_edge_bias' [E, H] to the result unless want_d_edge_bias is False); returns a dict."""
         import torch
         self._check_tensors(layer, (x, k, v, out, d_out), (a_l, a_r), (row_max, row_sum))
+        self._check_edge_tensor(layer, edge_bias)
         res = {"d_x": torch.empty_like(x)}
         d_k = d_v = d_a_l = d_a_r = d_scale = None
         if layer.model == "gt":
@@ -331,6 +366,13 @@ class Graph:
         else:
             d_scale = res["d_scale"] = torch.empty(1, dtype=torch.float32, device=self.device)
         ws, need = self.workspace(layer, True)
-        backward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, res["d_x"], d_k, d_v, d_a_l,
-                 d_a_r, d_scale, ws, ws.numel(), stream)
+        if edge_bias is None:
+            backward(self.handle, layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, res["d_x"], d_k, d_v, d_a_l,
+                     d_a_r, d_scale, ws, ws.numel(), stream)
+        else:
+            d_b = None
+            if want_d_edge_bias:
+                d_b = res["d_edge_bias"] = torch.empty((self.E, layer.H), dtype=torch.float32, device=self.device)
+            backward_edge_bias(self.handle, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, d_out,
+                               res["d_x"], d_k, d_v, d_a_l, d_a_r, d_scale, d_b, ws, ws.numel(), stream)
         return res

@@ -9,7 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfgnn.so")
-SOURCES = ["api.cpp", "graph.hip", "layer.hip", "dense_batch.hip", "dense_batch_f32.hip"]
+# the layer kernels are instantiated in one unit per model and direction so that they compile in parallel;
+# the slowest units come first
+SOURCES = ["layer_gt_bwd.hip", "layer_gatv2_bwd.hip", "layer_agnn_bwd.hip", "layer_gat_bwd.hip", "layer_gt_fwd.hip",
+           "layer_gatv2_fwd.hip", "layer_agnn_fwd.hip", "layer_gat_fwd.hip", "dense_batch_f32.hip", "dense_batch.hip",
+           "graph.hip", "layer.hip", "api.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",
     # packed fp32 arithmetic is kept off for all device code
@@ -42,7 +46,7 @@ def build(verbose: bool = False) -> str:
         subprocess.check_call(cmd)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(os.cpu_count() or 8, 16, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     tmp = LIB + f".tmp{os.getpid()}"
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])

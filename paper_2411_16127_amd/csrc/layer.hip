@@ -1,12 +1,9 @@
 // Host side of the layer calls: argument checks, workspace carving, lane-geometry selection and the
 // launch sequence of the fused kernels (Eq. 1 forward; Appendix B backward as a CSR row pass and a CSC
 // column pass).  Every launch goes to the caller's stream; nothing here synchronises or allocates.
-#include "common.hpp"
-#include "layer_device.hpp"
+#include "layer_launch.hpp"
 
 namespace dfgnn {
-
-constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the first is consumed
 
 // ---------------------------------------------------------------------------------------------
 // lane geometry
@@ -17,14 +14,6 @@ struct Geometry {
     int lpe;  // lanes per neighbour row (power of two, >= 4)
     int id;   // index into the instantiation table, -1 if none
 };
-
-// (type, LPE, LPH): LPH = 0 handles any head width at run time; the others are the shapes of the
-// benchmark workloads with compile-time DPP reductions.
-#define DFGNN_GEOMETRIES(X)                                                                        \
-    X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)   \
-    X(5, float, 16, 16) X(6, float, 32, 4) X(7, float, 16, 2)                                      \
-    X(8, bf16_t, 4, 0) X(9, bf16_t, 8, 0) X(10, bf16_t, 16, 0) X(11, bf16_t, 32, 0) X(12, bf16_t, 64, 0) \
-    X(13, bf16_t, 16, 2)
 
 static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
     DFGNN_REQUIRE(L->dtype == DFGNN_F32 || L->dtype == DFGNN_BF16, DFGNN_EINVAL, "unknown dtype %d", L->dtype);
@@ -114,151 +103,30 @@ static void bind_workspace(Args& a, const Workspace& W, void* ws, bool backward)
 }
 
 // ---------------------------------------------------------------------------------------------
-// launch sequences
+// launch sequences: one translation unit per model and direction holds the kernels
 // ---------------------------------------------------------------------------------------------
-static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock); }
-
-// chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
-template <class G, template <class, int> class PassT>
-static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st) {
-    a.ptr = columns ? g->t_indptr : g->indptr;
-    a.idx = columns ? g->t_indices : g->indices;
-    a.order = columns ? g->col_order : g->row_order;
-    a.chunks = columns ? g->col_chunks : g->row_chunks;
-    a.chunk_ptr = columns ? g->col_chunk_ptr : g->row_chunk_ptr;
-    const int n_super = columns ? g->n_super_cols : g->n_super_rows;
-    const int n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
-    // rows with fewer than EPW * U neighbours (less than one load round of a whole wavefront) go to the
-    // slot-per-row kernel; they are the tail of the degree-ordered list
-    const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
-    int64_t first_small = g->N;
-    if (G::EPW > 1 && !(g->flags & DFGNN_SCHED_NO_SHORT_ROWS)) {
-        int lg = 0;
-        while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
-        first_small = bucket[33 - lg];
-        if (first_small < n_super) first_small = n_super;
-    }
-    const int64_t n_direct = first_small - n_super;
-    const int64_t n_small = g->N - first_small;
-    a.n_chunks = n_chunks;
-    a.blocks_chunk = (int)blocks_for(n_chunks);
-    a.n_direct = (int)n_direct;
-    a.blocks_direct = (int)blocks_for(n_direct);
-    a.first_direct = n_super;
-    a.n_small = (int)n_small;
-    a.first_small = (int)first_small;
-    const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
-    const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
-    const dim3 block(64 * kWavesPerBlock);
-    if (total > 0) {
-        KernelTimer t(labels[0], st);
-        hipLaunchKernelGGL((k_pass<G, PassT, kUnroll>), dim3(total), block, 0, st, a);
-    }
-    if (n_super > 0) {
-        a.n_items = n_super;
-        KernelTimer t(labels[1], st);
-        hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
-    }
-}
-
-static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
-static const char* const kStoredLabels[2] = {"fwd_softmax_spmm", "fwd_softmax_spmm_merge"};
-static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
-static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
-
-template <class G> static void run_forward(const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
-    switch (model) {
-    case DFGNN_GT:
-        if (a.scores) {  // comparator: scores through memory (Sec. 3, parallelism maximization fusion)
-            const int64_t per_wave = (int64_t)G::EPW * kUnroll * kScoreRounds;
-            {
-                KernelTimer t("fwd_scores", st);
-                hipLaunchKernelGGL((k_edge_scores<G, kUnroll>), dim3(blocks_for((g->E + per_wave - 1) / per_wave)),
-                                   dim3(64 * kWavesPerBlock), 0, st, a);
-            }
-            run_pass<G, GtFwdStored>(g, false, a, kStoredLabels, st);
-        } else {
-            run_pass<G, GtFwd>(g, false, a, kFwdLabels, st);
-        }
-        break;
-    case DFGNN_GAT:
-        run_pass<G, GatFwd>(g, false, a, kFwdLabels, st);
-        break;
-    case DFGNN_GATV2:
-        run_pass<G, GatV2Fwd>(g, false, a, kFwdLabels, st);
-        break;
-    default:
-        run_pass<G, AgnnFwd>(g, false, a, kFwdLabels, st);
-        break;
-    }
-}
-
-template <class G>
-static void run_backward(const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
-                         float* d_scale, hipStream_t st) {
-    switch (model) {
-    case DFGNN_GT:
-        run_pass<G, GtBwdRow>(g, false, a, kRowLabels, st);
-        run_pass<G, GtBwdCol>(g, true, a, kColLabels, st);
-        break;
-    case DFGNN_GAT:
-        run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
-        run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
-        {
-            KernelTimer t("param_reduce", st);
-            hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
-            hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
-        }
-        break;
-    case DFGNN_GATV2:
-        run_pass<G, GatV2BwdRow>(g, false, a, kRowLabels, st);
-        run_pass<G, GatV2BwdCol>(g, true, a, kColLabels, st);
-        {
-            KernelTimer t("param_reduce", st);
-            int w = 1;  // threads per row, 4 columns each (a power of two, so that it divides 256)
-            while (4 * w < a.HD && w < 256) w <<= 1;
-            // about 16 rows per thread of the first stage, at most kRowsumBlocks workgroups
-            int64_t blocks = ((int64_t)a.n_nodes + (256 / w) * 16 - 1) / ((256 / w) * 16);
-            if (blocks > kRowsumBlocks) blocks = kRowsumBlocks;
-            int wf = 4;
-            while (wf < a.HD && wf < 256) wf <<= 1;
-            hipLaunchKernelGGL(k_rowsum_partial, dim3((unsigned)blocks), dim3(256), 0, st, a.da_row, (int64_t)a.n_nodes,
-                               a.HD, w, reduce_tmp);
-            hipLaunchKernelGGL(k_rowsum_final, dim3(1), dim3(256), 0, st, reduce_tmp, (int)blocks, a.HD, wf, d_a_l);
-        }
-        break;
-    default:
-        run_pass<G, AgnnBwdRow>(g, false, a, kRowLabels, st);
-        run_pass<G, AgnnBwdCol>(g, true, a, kColLabels, st);
-        {
-            KernelTimer t("param_reduce", st);
-            hipLaunchKernelGGL(k_sum_partial, dim3(kReduceBlocks), dim3(256), 0, st, a.dbeta_row,
-                               (int64_t)a.n_nodes * a.H, reduce_tmp);
-            hipLaunchKernelGGL(k_sum_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, d_scale);
-        }
-        break;
-    }
-}
-
 static int dispatch_forward(int geo, const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
-    switch (geo) {
-#define X(ID, T, LPE, LPH) case ID: run_forward<Geo<T, LPE, LPH>>(g, model, a, st); break;
-        DFGNN_GEOMETRIES(X)
-#undef X
-    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    switch (model) {
+    case DFGNN_GT: return launch_forward_gt(geo, g, a, st);
+    case DFGNN_GAT: return launch_forward_gat(geo, g, a, st);
+    case DFGNN_GATV2: return launch_forward_gatv2(geo, g, a, st);
+    default: return launch_forward_agnn(geo, g, a, st);
     }
-    return DFGNN_OK;
 }
 
 static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l,
                              float* d_a_r, float* d_scale, hipStream_t st) {
-    switch (geo) {
-#define X(ID, T, LPE, LPH) case ID: run_backward<Geo<T, LPE, LPH>>(g, model, a, reduce_tmp, d_a_l, d_a_r, d_scale, st); break;
-        DFGNN_GEOMETRIES(X)
-#undef X
-    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    switch (model) {
+    case DFGNN_GT: return launch_backward_gt(geo, g, a, st);
+    case DFGNN_GAT: return launch_backward_gat(geo, g, a, reduce_tmp, d_a_l, d_a_r, st);
+    case DFGNN_GATV2: return launch_backward_gatv2(geo, g, a, reduce_tmp, d_a_l, st);
+    default: return launch_backward_agnn(geo, g, a, reduce_tmp, d_scale, st);
     }
-    return DFGNN_OK;
+}
+
+// the edge term is read with 32-bit byte offsets
+static bool edge_term_fits(const dfgnn_graph* g, const dfgnn_layer* L) {
+    return (int64_t)g->E * L->H * 4 < ((int64_t)1 << 32) - 4096;
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -309,9 +177,9 @@ extern "C" int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer
     return DFGNN_OK;
 }
 
-extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
-                             const void* v, const float* a_l, const float* a_r, void* out, float* row_max,
-                             float* row_sum, void* workspace, size_t workspace_bytes, void* stream) {
+static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                        const void* v, const float* a_l, const float* a_r, const float* edge_bias, void* out,
+                        float* row_max, float* row_sum, void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
@@ -327,7 +195,10 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     DFGNN_REQUIRE(gat || v2 || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT or GATv2");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
-    if (const int kind = dense_batch_kind(graph, layer)) {
+    DFGNN_REQUIRE(((uintptr_t)edge_bias & 3u) == 0, DFGNN_EUNSUPPORTED, "edge_bias must be 4-byte aligned");
+    DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
+                  "edge term of E*H*4 bytes must stay below 4 GiB");
+    if (const int kind = edge_bias ? 0 : dense_batch_kind(graph, layer)) {  // the dense-tile kernels have no edge term
         rc = kind == 1 ? dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream)
                        : dense32_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream);
         if (rc != DFGNN_OK) return rc;
@@ -344,6 +215,8 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
     a.o = out; a.o_max = row_max; a.o_sum = row_sum;
     a.idx = graph->indices; a.edge_row = graph->edge_row; a.n_edges = (int)graph->E;
+    a.bias = edge_bias;
+    a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
     bind_workspace(a, W, workspace, false);
     rc = dispatch_forward(geo.id, graph, layer->model, a, (hipStream_t)stream);
     if (rc != DFGNN_OK) return rc;
@@ -351,10 +224,26 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
     return DFGNN_OK;
 }
 
-extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
-                              const void* v, const float* a_l, const float* a_r, const void* out, const float* row_max,
-                              const float* row_sum, const void* d_out, void* d_x, void* d_k, void* d_v, float* d_a_l,
-                              float* d_a_r, float* d_scale, void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                             const void* v, const float* a_l, const float* a_r, void* out, float* row_max,
+                             float* row_sum, void* workspace, size_t workspace_bytes, void* stream) {
+    return forward_impl(graph, layer, x, k, v, a_l, a_r, nullptr, out, row_max, row_sum, workspace, workspace_bytes,
+                        stream);
+}
+
+extern "C" int dfgnn_forward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                                       const void* v, const float* a_l, const float* a_r, const float* edge_bias,
+                                       void* out, float* row_max, float* row_sum, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+    return forward_impl(graph, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, workspace, workspace_bytes,
+                        stream);
+}
+
+static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                         const void* v, const float* a_l, const float* a_r, const float* edge_bias, const void* out,
+                         const float* row_max, const float* row_sum, const void* d_out, void* d_x, void* d_k, void* d_v,
+                         float* d_a_l, float* d_a_r, float* d_scale, float* d_edge_bias, void* workspace,
+                         size_t workspace_bytes, void* stream) {
     clear_error();
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
@@ -386,7 +275,12 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&
                       aligned16(d_k) && aligned16(d_v) && aligned16(a_l) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
-    const int dense_kind = dense_batch_kind(graph, layer);
+    DFGNN_REQUIRE((((uintptr_t)edge_bias | (uintptr_t)d_edge_bias) & 3u) == 0, DFGNN_EUNSUPPORTED,
+                  "edge_bias / d_edge_bias must be 4-byte aligned");
+    DFGNN_REQUIRE(edge_bias || !d_edge_bias, DFGNN_EINVAL, "d_edge_bias without edge_bias");
+    DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
+                  "edge term of E*H*4 bytes must stay below 4 GiB");
+    const int dense_kind = edge_bias ? 0 : dense_batch_kind(graph, layer);
     if (dense_kind == 1) {
         rc = dense_gt_backward(graph, layer, x, k, v, row_max, row_sum, d_out, d_x, d_k, d_v, (hipStream_t)stream);
         if (rc != DFGNN_OK) return rc;
@@ -412,10 +306,30 @@ extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer
     a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
     a.out = out; a.row_max = row_max; a.row_sum = row_sum; a.d_out = d_out;
     a.d_x = d_x; a.d_k = d_k; a.d_v = d_v;
+    a.bias = edge_bias; a.d_bias = d_edge_bias;
+    a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
     bind_workspace(a, W, workspace, true);
     float* reduce_tmp = (float*)((char*)workspace + W.reduce);
     rc = dispatch_backward(geo.id, graph, layer->model, a, reduce_tmp, d_a_l, d_a_r, d_scale, st);
     if (rc != DFGNN_OK) return rc;
     DFGNN_HIP(hipGetLastError());
     return DFGNN_OK;
+}
+
+extern "C" int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                              const void* v, const float* a_l, const float* a_r, const void* out, const float* row_max,
+                              const float* row_sum, const void* d_out, void* d_x, void* d_k, void* d_v, float* d_a_l,
+                              float* d_a_r, float* d_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(graph, layer, x, k, v, a_l, a_r, nullptr, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l,
+                         d_a_r, d_scale, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int dfgnn_backward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x,
+                                        const void* k, const void* v, const float* a_l, const float* a_r,
+                                        const float* edge_bias, const void* out, const float* row_max,
+                                        const float* row_sum, const void* d_out, void* d_x, void* d_k, void* d_v,
+                                        float* d_a_l, float* d_a_r, float* d_scale, float* d_edge_bias,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(graph, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, d_out, d_x, d_k, d_v,
+                         d_a_l, d_a_r, d_scale, d_edge_bias, workspace, workspace_bytes, stream);
 }

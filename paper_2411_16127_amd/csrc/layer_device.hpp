@@ -190,6 +190,11 @@ struct Args {
     float* part_s0;    // [chunks, H]
     float* part_s1;    // [chunks, H]
     float* part_s2;    // [chunks, H]
+    // optional additive edge term of the score (edge features, Sec. 1): [E, H] fp32 in CSR edge order
+    const float* bias;
+    uint32_t bias_bytes;  // E * H * 4 (< 4 GiB)
+    float* d_bias;   // its gradient dS (may be null)
+    const int* eid;  // column pass only, when there is an edge term: CSR position of every CSC entry
     // scores-through-memory comparator
     float* scores;        // [E, H] scaled scores in log2 units
     const int* edge_row;  // [E] destination row of every CSR position
@@ -197,9 +202,12 @@ struct Args {
 };
 
 // Lane geometry: LPE lanes per neighbour row, LPH lanes per head (0 = run-time), element type T.
-template <typename T_, int LPE_, int LPH_> struct Geo {
+// EDGE_TERM: the kernels also handle the optional additive edge term of the score (kept out of the
+// ordinary kernels at compile time, so that they pay nothing for it).
+template <typename T_, int LPE_, int LPH_, bool EDGE_TERM_ = false> struct Geo {
     using T = T_;
     static constexpr int LPE = LPE_, LPH = LPH_, VEC = Elem<T_>::VEC, EPW = 64 / LPE_;
+    static constexpr bool kEdgeTerm = EDGE_TERM_;
 };
 
 struct Ctx {
@@ -261,6 +269,27 @@ __device__ inline f32x2 gather_stats2(const Args& a, const Ctx& c, int i) {
 }
 __device__ inline f32x4 gather_stats4(const Args& a, const Ctx& c, int i) {
     return buf_load_f32x4(make_rsrc(a.stats, a.nh_bytes * 4u), (uint32_t)i * (uint32_t)(a.H * 16) + c.hbyte * 4u);
+}
+
+// additive edge term of edge e (CSR position); 0 for an empty slot (the offset is then out of range and
+// the buffer load returns zero; the [E, H] array is kept below 4 GiB)
+template <class G> __device__ inline float load_bias(const Args& a, const Ctx& c, int j, int e) {
+    if constexpr (G::kEdgeTerm)
+        return buf_load_f32(make_rsrc(a.bias, a.bias_bytes), j >= 0 ? (uint32_t)e * (uint32_t)(a.H * 4) + c.hbyte : 0xffffffffu);
+    else return 0.f;
+}
+// score in log2 units plus the edge term (given in natural units)
+template <class G> __device__ inline float with_bias(float s, float b) {
+    if constexpr (G::kEdgeTerm) return fmaf(b, kLog2e, s);
+    else return s;
+}
+// Gradient of the edge term = dS of the edge.  Both backward passes know dS of every edge; the row pass
+// writes it (in CSR order, i.e. sequentially) when it has the final delta during its sweep (fp32
+// tensors), otherwise the column pass does (bf16 tensors, where delta is only known at the end of a row).
+template <class G, bool ROW_PASS> __device__ inline void store_dbias(const Args& a, const Ctx& c, bool valid, int e, float ds) {
+    if constexpr (G::kEdgeTerm && ROW_PASS == (sizeof(typename G::T) == 4)) {
+        if (a.d_bias != nullptr && valid && c.head0) a.d_bias[(size_t)e * a.H + c.h] = ds;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -387,7 +416,7 @@ template <class G> struct RowBackwardBase {
 // =============================================================================================
 template <class G, int U> struct GtFwd {
     static constexpr int VEC = G::VEC;
-    float q[VEC];
+    float q[VEC], B[U];
     SoftmaxAcc<G, U> sm;
     u32x4 K[U], V[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -396,9 +425,10 @@ template <class G, int U> struct GtFwd {
         for (int i = 0; i < VEC; ++i) q[i] *= a.c_score;
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         V[u] = gather_raw<G>(a.v, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
     }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
@@ -406,7 +436,7 @@ template <class G, int U> struct GtFwd {
         for (int u = 0; u < U; ++u) {
             float kf[VEC];
             Elem<typename G::T>::unpack(K[u], kf);
-            s[u] = head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph);
+            s[u] = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph), B[u]);
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -447,6 +477,8 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
     static constexpr bool kExact = RowBackwardBase<G>::kExact;
     float q[VEC], dq[VEC], pk[VEC];  // pk = sum_j p k_j (kExact only)
+    float B[U];
+    int Ep[U];
     u32x4 K[U], V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, q);
@@ -454,17 +486,19 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
         for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; pk[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         V[u] = gather_raw<G>(a.v, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float kf[VEC], vf[VEC];
             Elem<typename G::T>::unpack(K[u], kf);
             Elem<typename G::T>::unpack(V[u], vf);
-            const float s = head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph);
+            const float s = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph), B[u]);
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
             if constexpr (kExact) {
@@ -474,6 +508,7 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
                 for (int i = 0; i < VEC; ++i) { dq[i] = fmaf(t, kf[i], dq[i]); pk[i] = fmaf(p, kf[i], pk[i]); }
             } else {
                 const float ds = p * (dp - this->delta);
+                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) dq[i] = fmaf(ds, kf[i], dq[i]);
             }
@@ -537,6 +572,8 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
 template <class G, int U> struct GtBwdCol {
     static constexpr int VEC = G::VEC;
     float k2[VEC], vv[VEC], dk[VEC], dv[VEC];
+    float B[U];
+    int Ep[U];
     u32x4 Q[U], Gd[U];
     f32x2 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -545,21 +582,24 @@ template <class G, int U> struct GtBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { k2[i] *= a.c_score; dk[i] = 0.f; dv[i] = 0.f; }
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
         Q[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats2(a, c, i);
+        B[u] = load_bias<G>(a, c, i, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float qf[VEC], gf[VEC];
             Elem<typename G::T>::unpack(Q[u], qf);
             Elem<typename G::T>::unpack(Gd[u], gf);
-            const float s = head_sum<G::LPH>(dotv<VEC>(qf, k2), a.lph);
+            const float s = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(qf, k2), a.lph), B[u]);
             const float dp = head_sum<G::LPH>(dotv<VEC>(gf, vv), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
             const float ds = p * (dp - St[u][1]);
+            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 dv[i] = fmaf(p, gf[i], dv[i]);
@@ -615,6 +655,7 @@ template <class G> __device__ inline void load_attention(const float* v, const C
 template <class G, int U> struct GatFwd {
     static constexpr int VEC = G::VEC;
     float el2, ar2[VEC];  // el_i * log2e; this lane's slice of a_r * log2e
+    float B[U];
     SoftmaxAcc<G, U> sm;
     u32x4 V[U];
     // el_i comes from the row's own features and er_j from the gathered neighbour row (one dot product
@@ -627,14 +668,17 @@ template <class G, int U> struct GatFwd {
         el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+    }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
-            s[u] = leaky(el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph), a.neg_slope);
+            s[u] = with_bias<G>(leaky(el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph), a.neg_slope), B[u]);
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -652,6 +696,8 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
     static constexpr int VEC = G::VEC;
     static constexpr bool kExact = RowBackwardBase<G>::kExact;
     float el2, ar2[VEC], d_el, pl;  // pl = sum_j p LeakyReLU'(z) (kExact only)
+    float B[U];
+    int Ep[U];
     u32x4 V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         float x[VEC], al[VEC];
@@ -663,15 +709,19 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
         pl = 0.f;
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
             const float z = el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - this->lse2) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(leaky(z, a.neg_slope), B[u]) - this->lse2) : 0.f;
             const float slope = z > 0.f ? 1.f : a.neg_slope;
             if constexpr (kExact) {
                 const float t = p * dp;
@@ -679,7 +729,9 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
                 d_el = fmaf(t, slope, d_el);
                 pl = fmaf(p, slope, pl);
             } else {
-                d_el = fmaf(p * (dp - this->delta), slope, d_el);
+                const float ds = p * (dp - this->delta);
+                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
+                d_el = fmaf(ds, slope, d_el);
             }
         }
     }
@@ -732,6 +784,8 @@ template <class G, int U> struct GatBwdCol {
     static constexpr int VEC = G::VEC;
     float wh[VEC], dwh[VEC];
     float er2, d_er;
+    float B[U];
+    int Ep[U];
     u32x4 Gd[U];
     f32x4 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -743,19 +797,22 @@ template <class G, int U> struct GatBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dwh[i] = 0.f;
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats4(a, c, i);
+        B[u] = load_bias<G>(a, c, i, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float gf[VEC];
             Elem<typename G::T>::unpack(Gd[u], gf);
             const float dp = head_sum<G::LPH>(dotv<VEC>(gf, wh), a.lph);
             const float z = St[u][0] + er2;
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(leaky(z, a.neg_slope) - St[u][1]) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(leaky(z, a.neg_slope), B[u]) - St[u][1]) : 0.f;
             const float ds = p * (dp - St[u][2]);
+            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
             d_er += ds * (z > 0.f ? 1.f : a.neg_slope);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) dwh[i] = fmaf(p, gf[i], dwh[i]);
@@ -805,6 +862,7 @@ template <class G, int U> struct GatBwdCol {
 template <class G, int U> struct GatV2Fwd {
     static constexpr int VEC = G::VEC;
     float x[VEC], al2[VEC];  // destination features; this lane's slice of a * log2e
+    float B[U];
     SoftmaxAcc<G, U> sm;
     u32x4 K[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -812,7 +870,10 @@ template <class G, int U> struct GatV2Fwd {
         load_attention<G>(a.a_l, c, kLog2e, al2);
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { K[u] = gather_raw<G>(a.k, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        K[u] = gather_raw<G>(a.k, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+    }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
@@ -821,7 +882,7 @@ template <class G, int U> struct GatV2Fwd {
             Elem<typename G::T>::unpack(K[u], kf);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) t = fmaf(al2[i], leaky(x[i] + kf[i], a.neg_slope), t);
-            s[u] = head_sum<G::LPH>(t, a.lph);
+            s[u] = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -842,6 +903,8 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
     static constexpr int kMergeBatch = kExact ? 2 : 4;  // four partial vectors per chunk: keep the merge in registers
     float x[VEC], al2[VEC], dx[VEC], da[VEC];
     float px[VEC], pa[VEC];  // sum_j p LeakyReLU'(z), sum_j p LeakyReLU(z)  (kExact only)
+    float B[U];
+    int Ep[U];
     u32x4 K[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, x);
@@ -850,8 +913,12 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
         for (int i = 0; i < VEC; ++i) { dx[i] = 0.f; da[i] = 0.f; px[i] = 0.f; pa[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { K[u] = gather_raw<G>(a.k, a, c, j); }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        K[u] = gather_raw<G>(a.k, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float kf[VEC], lr[VEC], sl[VEC], t = 0.f;
@@ -863,7 +930,7 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
                 lr[i] = z * sl[i];
                 t = fmaf(al2[i], lr[i], t);
             }
-            const float s = head_sum<G::LPH>(t, a.lph);
+            const float s = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, kf), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
             if constexpr (kExact) {
@@ -876,6 +943,7 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
                 }
             } else {
                 const float ds = p * (dp - this->delta);
+                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { dx[i] = fmaf(ds, sl[i], dx[i]); da[i] = fmaf(ds, lr[i], da[i]); }
             }
@@ -945,6 +1013,8 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
 template <class G, int U> struct GatV2BwdCol {
     static constexpr int VEC = G::VEC;
     float kk[VEC], al2[VEC], dk[VEC], dz[VEC];
+    float B[U];
+    int Ep[U];
     u32x4 X[U], Gd[U];
     f32x2 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -953,12 +1023,14 @@ template <class G, int U> struct GatV2BwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { dk[i] = 0.f; dz[i] = 0.f; }
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
         X[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats2(a, c, i);
+        B[u] = load_bias<G>(a, c, i, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float xf[VEC], gf[VEC], sl[VEC], t = 0.f;
@@ -970,10 +1042,11 @@ template <class G, int U> struct GatV2BwdCol {
                 sl[i] = z > 0.f ? 1.f : a.neg_slope;
                 t = fmaf(al2[i], z * sl[i], t);
             }
-            const float s = head_sum<G::LPH>(t, a.lph);
+            const float s = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
             const float dp = head_sum<G::LPH>(dotv<VEC>(gf, kk), a.lph);
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
             const float ds = p * (dp - St[u][1]);
+            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(p, gf[i], dk[i]); dz[i] = fmaf(ds, sl[i], dz[i]); }
         }
@@ -1016,7 +1089,7 @@ __device__ inline float inv_norm(float n2, float inv_eps) { return fminf(__built
 
 template <class G, int U> struct AgnnFwd {
     static constexpr int VEC = G::VEC;
-    float x2[VEC];
+    float x2[VEC], B[U];
     SoftmaxAcc<G, U> sm;
     u32x4 V[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -1026,7 +1099,10 @@ template <class G, int U> struct AgnnFwd {
         for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
         sm.reset();
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+    }
     template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
         float s[U];
 #pragma unroll
@@ -1034,7 +1110,7 @@ template <class G, int U> struct AgnnFwd {
             float vf[VEC];
             Elem<typename G::T>::unpack(V[u], vf);
             const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
-            s[u] = head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * rnj;
+            s[u] = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * rnj, B[u]);
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
@@ -1053,6 +1129,8 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     static constexpr bool kExact = RowBackwardBase<G>::kExact;
     float xh[VEC], ga[VEC], px[VEC];  // px = sum_j p xhat_j (kExact only)
     float rn, dbeta, pc;              // pc = sum_j p cos_ij (kExact only)
+    float B[U];
+    int Ep[U];
     u32x4 V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, xh);
@@ -1063,8 +1141,12 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; px[i] = 0.f; }
         this->init_row(a, c);
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int /*e*/) { V[u] = gather_raw<G>(a.x, a, c, j); }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
+        V[u] = gather_raw<G>(a.x, a, c, j);
+        B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float vf[VEC];
@@ -1072,7 +1154,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
             const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * rnj;
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - this->lse2) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
                 this->dsum += t;
@@ -1083,6 +1165,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
                 for (int i = 0; i < VEC; ++i) { ga[i] = fmaf(w1, vf[i], ga[i]); px[i] = fmaf(w2, vf[i], px[i]); }
             } else {
                 const float ds = p * (dp - this->delta);
+                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
                 dbeta = fmaf(ds, cs, dbeta);
                 const float w = ds * rnj;
 #pragma unroll
@@ -1162,6 +1245,8 @@ template <class G, int U> struct AgnnBwdCol {
     static constexpr int VEC = G::VEC;
     float hj[VEC], xh[VEC], val[VEC], ga[VEC];
     float rn;
+    float B[U];
+    int Ep[U];
     u32x4 Xi[U], Gd[U];
     f32x4 St[U];
     __device__ void init(const Args& a, const Ctx& c) {
@@ -1170,12 +1255,14 @@ template <class G, int U> struct AgnnBwdCol {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
     }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int /*e*/) {
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
         Xi[u] = gather_raw<G>(a.x, a, c, i);
         Gd[u] = gather_raw<G>(a.d_out, a, c, i);
         St[u] = gather_stats4(a, c, i);
+        B[u] = load_bias<G>(a, c, i, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float xf[VEC], gf[VEC];
@@ -1183,8 +1270,9 @@ template <class G, int U> struct AgnnBwdCol {
             Elem<typename G::T>::unpack(Gd[u], gf);
             const float cs = head_sum<G::LPH>(dotv<VEC>(xf, xh), a.lph) * St[u][0];
             const float dp = head_sum<G::LPH>(dotv<VEC>(gf, hj), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(cs * a.c_score - St[u][1]) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - St[u][1]) : 0.f;
             const float ds = p * (dp - St[u][2]);
+            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
             const float w = ds * St[u][0];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
@@ -1239,12 +1327,16 @@ template <class G, int U> struct AgnnBwdCol {
 // =============================================================================================
 constexpr int kWavesPerBlock = 4;
 
+// neighbour ids of one load round and the CSR position of their edges: the list position itself for a
+// row pass, the stored CSR position of the CSC entry for a column pass that needs it (a.eid set)
 template <class G, int U>
-__device__ inline void load_indices(const Args& a, const Ctx& c, int base, int ee, int (&j)[U]) {
+__device__ inline void load_indices(const Args& a, const Ctx& c, int base, int ee, int (&j)[U], int (&ep)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int e = base + u * G::EPW + c.g;
         j[u] = e < ee ? a.idx[e] : -1;
+        if constexpr (G::kEdgeTerm) ep[u] = (a.eid != nullptr && e < ee) ? a.eid[e] : e;
+        else ep[u] = e;
     }
 }
 
@@ -1270,16 +1362,16 @@ __device__ inline void wave_item(const Args& a, int item, int lane) {
     PassT<G, U> p;
     p.init(a, c);
     constexpr int STEP = G::EPW * U;
-    int j[U], jn[U];
-    load_indices<G, U>(a, c, eb, ee, j);
+    int j[U], jn[U], ep[U], epn[U];
+    load_indices<G, U>(a, c, eb, ee, j, ep);
     for (int base = eb; base < ee; base += STEP) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], base + u * G::EPW + c.g);
-        load_indices<G, U>(a, c, base + STEP, ee, jn);
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], ep[u]);
+        load_indices<G, U>(a, c, base + STEP, ee, jn, epn);
         if (base + STEP <= ee) p.template consume<true>(a, c, j);
         else p.template consume<false>(a, c, j);
 #pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = jn[u];
+        for (int u = 0; u < U; ++u) { j[u] = jn[u]; ep[u] = epn[u]; }
     }
     p.combine_slots(a, c);
     if (PARTIAL) p.store_partial(a, c, item);
@@ -1300,18 +1392,27 @@ __device__ inline void wave_small_rows(const Args& a, int item, int lane) {
     c.writer = live;
     PassT<G, U> p;
     p.init(a, c);
-    int j[U], jn[U];
+    int j[U], jn[U], ep[U], epn[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) j[u] = eb + u < ee ? a.idx[eb + u] : -1;
+    for (int u = 0; u < U; ++u) {
+        j[u] = eb + u < ee ? a.idx[eb + u] : -1;
+        if constexpr (G::kEdgeTerm) ep[u] = (a.eid != nullptr && eb + u < ee) ? a.eid[eb + u] : eb + u;
+        else ep[u] = eb + u;
+    }
     for (int pos = eb; __any(pos < ee); pos += U) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], pos + u);
+        for (int u = 0; u < U; ++u) p.issue(a, c, u, j[u], ep[u]);
 #pragma unroll
-        for (int u = 0; u < U; ++u) jn[u] = pos + U + u < ee ? a.idx[pos + U + u] : -1;
+        for (int u = 0; u < U; ++u) {
+            const int e = pos + U + u;
+            jn[u] = e < ee ? a.idx[e] : -1;
+            if constexpr (G::kEdgeTerm) epn[u] = (a.eid != nullptr && e < ee) ? a.eid[e] : e;
+            else epn[u] = e;
+        }
         if (__all(pos + U <= ee)) p.template consume<true>(a, c, j);
         else p.template consume<false>(a, c, j);
 #pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = jn[u];
+        for (int u = 0; u < U; ++u) { j[u] = jn[u]; ep[u] = epn[u]; }
     }
     p.finalize(a, c);
 }
@@ -1409,8 +1510,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_edge_scores(const Args 
             float qf[G::VEC], kf[G::VEC];
             Elem<typename G::T>::unpack(Q[u], qf);
             Elem<typename G::T>::unpack(K[u], kf);
-            const float s = head_sum<G::LPH>(dotv<G::VEC>(qf, kf), a.lph) * a.c_score;
             const int64_t e = base + u * G::EPW + c.g;
+            const float s = with_bias<G>(head_sum<G::LPH>(dotv<G::VEC>(qf, kf), a.lph) * a.c_score, load_bias<G>(a, c, j[u], (int)e));
             if (c.head0 && j[u] >= 0) a.scores[(size_t)e * a.H + c.h] = s;
         }
     }

@@ -1,0 +1,26 @@
+// GAT backward kernels (Appendix B with the chain rule through LeakyReLU) and the reduction of da_l, da_r.
+#include "layer_launch.hpp"
+
+namespace dfgnn {
+
+template <class G>
+static void run(const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r, hipStream_t st) {
+    run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
+    run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
+    KernelTimer t("param_reduce", st);
+    hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
+    hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+}
+
+int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
+                        hipStream_t st) {
+    switch (geo) {
+#define X(ID, T, LPE, LPH) case ID: run<Geo<T, LPE, LPH>>(g, a, reduce_tmp, d_a_l, d_a_r, st); break;
+        DFGNN_GEOMETRIES(X)
+#undef X
+    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    }
+    return DFGNN_OK;
+}
+
+}  // namespace dfgnn

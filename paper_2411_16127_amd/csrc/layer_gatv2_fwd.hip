@@ -1,0 +1,16 @@
+// GATv2 forward kernels (the second member of the GAT family cited in Sec. 1).
+#include "layer_launch.hpp"
+
+namespace dfgnn {
+
+int launch_forward_gatv2(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st) {
+    switch (geo) {
+#define X(ID, T, LPE, LPH) case ID: run_pass<Geo<T, LPE, LPH>, GatV2Fwd>(g, false, a, kFwdLabels, st); break;
+        DFGNN_GEOMETRIES(X)
+#undef X
+    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    }
+    return DFGNN_OK;
+}
+
+}  // namespace dfgnn

@@ -1,0 +1,92 @@
+// Launch side shared by the per-model translation units: the table of lane geometries, the launch of one
+// pass (chunks of super rows, whole rows and short rows in one kernel, then the merge of chunk partials)
+// and the entry points each unit defines.  The kernels of one model and direction are instantiated in
+// one unit each, so that the library builds in parallel.
+#pragma once
+#include "common.hpp"
+#include "layer_device.hpp"
+
+namespace dfgnn {
+
+constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the first is consumed
+
+// (type, LPE, LPH): LPH = 0 handles any head width at run time; the others are the shapes of the
+// benchmark workloads with compile-time DPP reductions.
+#define DFGNN_GEOMETRIES(X)                                                                        \
+    X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)   \
+    X(5, float, 16, 16) X(6, float, 32, 4) X(7, float, 16, 2)                                      \
+    X(8, bf16_t, 4, 0) X(9, bf16_t, 8, 0) X(10, bf16_t, 16, 0) X(11, bf16_t, 32, 0) X(12, bf16_t, 64, 0) \
+    X(13, bf16_t, 16, 2)
+
+
+// the same geometry with the code for the optional additive edge term compiled in
+template <class G> using with_edge_term = Geo<typename G::T, G::LPE, G::LPH, true>;
+
+// ---------------------------------------------------------------------------------------------
+// launch sequences
+// ---------------------------------------------------------------------------------------------
+static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock); }
+
+// chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
+template <class G, template <class, int> class PassT>
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st) {
+    a.ptr = columns ? g->t_indptr : g->indptr;
+    a.idx = columns ? g->t_indices : g->indices;
+    a.order = columns ? g->col_order : g->row_order;
+    a.chunks = columns ? g->col_chunks : g->row_chunks;
+    a.chunk_ptr = columns ? g->col_chunk_ptr : g->row_chunk_ptr;
+    a.eid = (columns && a.bias) ? g->t_eid : nullptr;  // the edge term is stored in CSR edge order
+    const int n_super = columns ? g->n_super_cols : g->n_super_rows;
+    const int n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
+    // rows with fewer than EPW * U neighbours (less than one load round of a whole wavefront) go to the
+    // slot-per-row kernel; they are the tail of the degree-ordered list
+    const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
+    int64_t first_small = g->N;
+    if (G::EPW > 1 && !(g->flags & DFGNN_SCHED_NO_SHORT_ROWS)) {
+        int lg = 0;
+        while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
+        first_small = bucket[33 - lg];
+        if (first_small < n_super) first_small = n_super;
+    }
+    const int64_t n_direct = first_small - n_super;
+    const int64_t n_small = g->N - first_small;
+    a.n_chunks = n_chunks;
+    a.blocks_chunk = (int)blocks_for(n_chunks);
+    a.n_direct = (int)n_direct;
+    a.blocks_direct = (int)blocks_for(n_direct);
+    a.first_direct = n_super;
+    a.n_small = (int)n_small;
+    a.first_small = (int)first_small;
+    const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
+    const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
+    const dim3 block(64 * kWavesPerBlock);
+    if (total > 0) {
+        KernelTimer t(labels[0], st);
+        if (a.bias) hipLaunchKernelGGL((k_pass<with_edge_term<G>, PassT, kUnroll>), dim3(total), block, 0, st, a);
+        else hipLaunchKernelGGL((k_pass<G, PassT, kUnroll>), dim3(total), block, 0, st, a);
+    }
+    if (n_super > 0) {
+        a.n_items = n_super;
+        KernelTimer t(labels[1], st);
+        hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
+    }
+}
+
+[[maybe_unused]] static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
+[[maybe_unused]] static const char* const kStoredLabels[2] = {"fwd_softmax_spmm", "fwd_softmax_spmm_merge"};
+[[maybe_unused]] static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
+[[maybe_unused]] static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
+
+
+// One entry point per model and direction; `geo` is an id of the table above.  Each returns a status.
+int launch_forward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_forward_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_forward_gatv2(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_forward_agnn(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_backward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
+                        hipStream_t st);
+int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, hipStream_t st);
+int launch_backward_agnn(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_scale, hipStream_t st);
+
+}  // namespace dfgnn

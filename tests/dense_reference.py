@@ -9,7 +9,8 @@ import torch
 
 
 def dense_layer(model, indptr, indices, H, D, scale, neg_slope, eps, tensors, d_out):
-    """tensors: dict of numpy arrays (x, k, v, a_l, a_r as applicable).  Returns (outputs, grads)."""
+    """tensors: dict of numpy arrays (x, k, v, a_l, a_r as applicable; optional edge_bias [nnz, H] in CSR
+    edge order, added to the scores).  Returns (outputs, grads)."""
     n = len(indptr) - 1
     mask = torch.zeros(n, n, dtype=torch.bool)  # mask[i, j] = edge i <- j
     for i in range(n):
@@ -38,6 +39,12 @@ def dense_layer(model, indptr, indices, H, D, scale, neg_slope, eps, tensors, d_
         val = t["x"]
     else:
         raise ValueError(model)
+    if "edge_bias" in t:  # scatter the per-edge term into the dense [H, i, j] score matrix
+        rows_of = torch.tensor(np.repeat(np.arange(n), np.diff(indptr)), dtype=torch.long)
+        cols_of = torch.tensor(np.asarray(indices), dtype=torch.long)
+        dense_b = torch.zeros(H, n, n, dtype=torch.float64)
+        dense_b = dense_b.index_put((torch.arange(H)[:, None], rows_of[None, :], cols_of[None, :]), t["edge_bias"].t())
+        s = s + dense_b
     has = mask.any(dim=1)
     s = s.masked_fill(~mask[None], float("-inf"))
     s_safe = torch.where(has[None, :, None], s, torch.zeros_like(s))

@@ -45,8 +45,9 @@ def run_gpu(graph, w, feats, sched=None, g=None, use_batch=True):
     v = to_device(feats["v"], w.dtype) if w.model == "gt" else None
     a_l, a_r = f32("a_l"), f32("a_r")
     d_out = to_device(feats["d_out"], w.dtype)
-    out, rmax, rsum = g.forward(L, x, k, v, a_l, a_r)
-    grads = g.backward(L, x, k, v, a_l, a_r, out, rmax, rsum, d_out)
+    bias = f32("edge_bias")  # optional additive edge term [E, H]
+    out, rmax, rsum = g.forward(L, x, k, v, a_l, a_r, edge_bias=bias)
+    grads = g.backward(L, x, k, v, a_l, a_r, out, rmax, rsum, d_out, edge_bias=bias)
     torch.cuda.synchronize()
     res = {"out": to_host(out), "row_max": to_host(rmax), "row_sum": to_host(rsum)}
     for key, val in grads.items():
@@ -57,13 +58,15 @@ def run_gpu(graph, w, feats, sched=None, g=None, use_batch=True):
 def run_oracle(graph, w, feats, rows=None, backward_rows=None):
     L = oracle_layer(w)
     kw = dict(x=feats["q"] if w.model == "gt" else feats["feat"], k=feats.get("k"), v=feats.get("v"),
-              a_l=feats.get("a_l"), a_r=feats.get("a_r"))
+              a_l=feats.get("a_l"), a_r=feats.get("a_r"), edge_bias=feats.get("edge_bias"))
     kw = {k_: (None if v_ is None else np.asarray(v_, dtype=np.float64)) for k_, v_ in kw.items()}
     fw = oracle.forward(L, graph.indptr, graph.indices, rows=rows, **kw)
     bw = oracle.backward(L, graph.indptr, graph.indices, d_out=np.asarray(feats["d_out"], dtype=np.float64),
-                         rows=backward_rows, **kw)
+                         rows=backward_rows, want_ds="edge_bias" in feats, **kw)
     ref = dict(fw)
     ref.update(bw)
+    if "ds" in ref:
+        ref["d_edge_bias"] = ref.pop("ds")
     if "d_scale" in ref:
         ref["d_scale"] = np.array([ref["d_scale"]])
     return ref
@@ -109,7 +112,8 @@ def assert_close(name, got, ref, dtype, rows=None, tol=None):
 
 
 def compare_all(res, ref, w, rows=None, keys=None, tol=None):
-    names = keys or [k for k in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v", "d_a_l", "d_a_r", "d_scale") if k in ref]
+    names = keys or [k for k in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v", "d_a_l", "d_a_r", "d_scale",
+                                 "d_edge_bias") if k in ref]
     for name in names:
         per_node = name in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v")
         assert_close(name, res[name], ref[name], w.dtype, rows if per_node else None, tol)

@@ -37,9 +37,10 @@ def layer_for(model, H, D):
 
 def run_oracle(layer, g, t, d_out, **kw):
     fw = oracle.forward(layer, g.indptr, g.indices, x=t["x"], k=t.get("k"), v=t.get("v"),
-                        a_l=t.get("a_l"), a_r=t.get("a_r"), want_p=True)
+                        a_l=t.get("a_l"), a_r=t.get("a_r"), edge_bias=t.get("edge_bias"), want_p=True)
     bw = oracle.backward(layer, g.indptr, g.indices, x=t["x"], k=t.get("k"), v=t.get("v"),
-                         a_l=t.get("a_l"), a_r=t.get("a_r"), d_out=d_out, want_ds=True, **kw)
+                         a_l=t.get("a_l"), a_r=t.get("a_r"), edge_bias=t.get("edge_bias"), d_out=d_out,
+                         want_ds=True, **kw)
     return fw, bw
 
 
@@ -90,7 +91,7 @@ def test_complete_graph_is_dense_softmax_attention():
 # ---------------------------------------------------------------- finite differences (Appendix B)
 def _loss(layer, g, t, d_out):
     fw = oracle.forward(layer, g.indptr, g.indices, x=t["x"], k=t.get("k"), v=t.get("v"),
-                        a_l=t.get("a_l"), a_r=t.get("a_r"))
+                        a_l=t.get("a_l"), a_r=t.get("a_r"), edge_bias=t.get("edge_bias"))
     return float((fw["out"] * d_out).sum())
 
 
@@ -102,7 +103,7 @@ def test_backward_by_central_differences(model, graph):
     t, d_out = make_inputs(model, g.n, H, D, seed=23)
     layer = layer_for(model, H, D)
     _, bw = run_oracle(layer, g, t, d_out)
-    names = {"x": "d_x", "k": "d_k", "v": "d_v", "a_l": "d_a_l", "a_r": "d_a_r"}
+    names = {"x": "d_x", "k": "d_k", "v": "d_v", "a_l": "d_a_l", "a_r": "d_a_r", "edge_bias": "ds"}
     step = 1e-6
     rng = np.random.default_rng(0)
     for key in t:
@@ -345,6 +346,67 @@ def test_gatv2_ranking_depends_on_the_destination():
     p = np.exp(s) / np.exp(s).sum(1, keepdims=True)
     np.testing.assert_allclose(fw["p"][:, 0], p.ravel(), rtol=1e-14)
     assert fw["p"][0, 0] > fw["p"][1, 0] and fw["p"][2, 0] < fw["p"][3, 0]
+
+
+# ---------------------------------------------------------------- additive edge term in the score
+@pytest.mark.parametrize("model", MODELS)
+@pytest.mark.parametrize("graph", ["random", "hub", "selfloop"])
+def test_edge_bias_matches_dense_masked_attention(model, graph):
+    H, D = 2, 4
+    g = tiny_graph(graph, seed=3, n=17)
+    t, d_out = make_inputs(model, g.n, H, D, seed=11)
+    t["edge_bias"] = np.random.default_rng(7).standard_normal((g.nnz, H))
+    layer = layer_for(model, H, D)
+    fw, bw = run_oracle(layer, g, t, d_out)
+    ref, grads = dense_layer(model, g.indptr, g.indices, H, D, layer.scale, layer.neg_slope, layer.eps, t, d_out)
+    np.testing.assert_allclose(fw["out"], ref["out"], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw["d_x"], grads["x"], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(bw["ds"], grads["edge_bias"], rtol=1e-9, atol=1e-12)
+    if model in ("gt", "gatv2"):
+        np.testing.assert_allclose(bw["d_k"], grads["k"], rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("graph", ["dups", "unsorted"])
+def test_edge_bias_gradient_by_central_differences(graph):
+    """Graphs the dense route cannot hold (repeated edges carry separate bias entries)."""
+    H, D = 2, 3
+    g = tiny_graph(graph, seed=2, n=14)
+    t, d_out = make_inputs("gt", g.n, H, D, seed=23)
+    t["edge_bias"] = np.random.default_rng(8).standard_normal((g.nnz, H))
+    layer = layer_for("gt", H, D)
+    _, bw = run_oracle(layer, g, t, d_out)
+    step = 1e-6
+    flat = t["edge_bias"].reshape(-1)
+    for idx in np.random.default_rng(0).choice(flat.size, size=min(flat.size, 40), replace=False):
+        keep = flat[idx]
+        flat[idx] = keep + step
+        up = _loss(layer, g, t, d_out)
+        flat[idx] = keep - step
+        dn = _loss(layer, g, t, d_out)
+        flat[idx] = keep
+        an = bw["ds"].reshape(-1)[idx]
+        assert abs((up - dn) / (2 * step) - an) <= 2e-7 + 2e-6 * abs(an)
+
+
+def test_edge_bias_closed_forms():
+    """A bias that is constant along a row shifts the row's scores and changes nothing; with q = 0 the
+    attention is softmax of the bias alone, i.e. p_ij = w_ij / sum_j w_ij for bias = log w."""
+    H, D = 2, 4
+    g = tiny_graph("dups", seed=2, n=15)
+    t, d_out = make_inputs("gt", g.n, H, D, seed=4)
+    layer = layer_for("gt", H, D)
+    rows = g.rows_of_edges()
+    base, _ = run_oracle(layer, g, t, d_out)
+    per_row = np.random.default_rng(1).standard_normal((g.n, H))
+    shifted, _ = run_oracle(layer, g, dict(t, edge_bias=per_row[rows]), d_out)
+    np.testing.assert_allclose(shifted["out"], base["out"], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(shifted["p"], base["p"], rtol=1e-11)
+    wgt = np.random.default_rng(2).uniform(0.1, 3.0, size=(g.nnz, H))
+    t0 = dict(t, x=np.zeros_like(t["x"]), edge_bias=np.log(wgt))
+    fw, _ = run_oracle(layer, g, t0, d_out)
+    for h in range(H):
+        tot = np.bincount(rows, weights=wgt[:, h], minlength=g.n)
+        np.testing.assert_allclose(fw["p"][:, h], wgt[:, h] / tot[rows], rtol=1e-12)
 
 
 # ---------------------------------------------------------------- row-subset mode used for sampled checks
