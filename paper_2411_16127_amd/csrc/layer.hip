@@ -28,16 +28,18 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
     g.lpe = 4;
     while (g.lpe < lanes) g.lpe <<= 1;
     const bool f32 = L->dtype == DFGNN_F32;
-    g.id = -1;
-    if (f32 && g.lpe == 16 && lanes == 16 && g.lph == 16) g.id = 5;
-    else if (f32 && g.lpe == 32 && lanes == 32 && g.lph == 4) g.id = 6;
-    else if (f32 && g.lpe == 16 && lanes == 16 && g.lph == 2) g.id = 7;
-    else if (!f32 && g.lpe == 16 && lanes == 16 && g.lph == 2) g.id = 13;
-    else {
-        int k = 0;
-        for (int l = 4; l < g.lpe; l <<= 1) ++k;
-        g.id = (f32 ? 0 : 8) + k;
-    }
+    // a compile-time geometry needs the row to fill its lanes exactly; otherwise the run-time one of that width
+    int k = 0;
+    for (int l = 4; l < g.lpe; l <<= 1) ++k;
+    g.id = (f32 ? 0 : 5) + k;
+    struct Entry { int id; bool f32; int lpe, lph; };
+    static const Entry table[] = {
+#define X(ID, T, LPE, LPH) {ID, sizeof(T) == 4, LPE, LPH},
+        DFGNN_GEOMETRIES(X)
+#undef X
+    };
+    for (const Entry& e : table)
+        if (e.lph != 0 && e.f32 == f32 && e.lpe == g.lpe && lanes == g.lpe && e.lph == g.lph) g.id = e.id;
     *out = g;
     return DFGNN_OK;
 }

@@ -10,14 +10,16 @@ namespace dfgnn {
 
 constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the first is consumed
 
-// (type, LPE, LPH): LPH = 0 handles any head width at run time; the others are the shapes of the
-// benchmark workloads with compile-time DPP reductions.
-#define DFGNN_GEOMETRIES(X)                                                                        \
-    X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)   \
-    X(5, float, 16, 16) X(6, float, 32, 4) X(7, float, 16, 2)                                      \
-    X(8, bf16_t, 4, 0) X(9, bf16_t, 8, 0) X(10, bf16_t, 16, 0) X(11, bf16_t, 32, 0) X(12, bf16_t, 64, 0) \
-    X(13, bf16_t, 16, 2)
-
+// (id, type, LPE, LPH): LPH = 0 handles any head width at run time (ids 0-4 fp32, 5-9 bf16, by LPE);
+// the others are full rows of 64 or 128 features split into 1 to 16 heads, with compile-time DPP
+// reductions over the lanes of a head.
+#define DFGNN_GEOMETRIES(X)                                                                          \
+    X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)     \
+    X(5, bf16_t, 4, 0) X(6, bf16_t, 8, 0) X(7, bf16_t, 16, 0) X(8, bf16_t, 32, 0) X(9, bf16_t, 64, 0) \
+    X(10, float, 16, 16) X(11, float, 16, 8) X(12, float, 16, 4) X(13, float, 16, 2)                 \
+    X(14, float, 32, 32) X(15, float, 32, 16) X(16, float, 32, 8) X(17, float, 32, 4) X(18, float, 32, 2) \
+    X(19, bf16_t, 16, 16) X(20, bf16_t, 16, 8) X(21, bf16_t, 16, 4) X(22, bf16_t, 16, 2) X(23, bf16_t, 16, 1) \
+    X(24, bf16_t, 8, 8) X(25, bf16_t, 8, 4) X(26, bf16_t, 8, 2) X(27, bf16_t, 8, 1)
 
 // the same geometry with the code for the optional additive edge term compiled in
 template <class G> using with_edge_term = Geo<typename G::T, G::LPE, G::LPH, true>;

@@ -45,6 +45,22 @@ def test_tiny_graphs_bf16(model, H, D):
     g.close()
 
 
+# rows of 64 or 128 features split into 1 to 16 heads: every lane geometry with compile-time head reductions
+FULL_ROW_SHAPES = [("f32", H, 64 // H) for H in (1, 2, 4, 8)] + [("f32", H, 128 // H) for H in (1, 2, 4, 8, 16)] + \
+                  [("bf16", H, 128 // H) for H in (1, 2, 4, 8, 16)] + [("bf16", H, 64 // H) for H in (1, 2, 4, 8)]
+
+
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
+@pytest.mark.parametrize("dtype,H,D", FULL_ROW_SHAPES)
+def test_full_row_geometries(model, dtype, H, D):
+    graph = tiny_graph("hub", seed=11, n=90)
+    w = Workload("tiny", 99, model, H, D, dtype, {"gt": float(1.0 / np.sqrt(D)), "agnn": 1.3}.get(model, 1.0))
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
 @pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
 def test_complete_graph(model):
     graph = complete_graph(67)  # every row has 67 neighbours: several unrolled rounds plus a ragged tail
