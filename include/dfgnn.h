@@ -148,12 +148,12 @@ int dfgnn_graph_destroy(dfgnn_graph* graph);
  * does not decrease and that no edge connects two graphs (EINVAL otherwise), and records for each row
  * and each column its adjacency bits inside its graph.
  * If no edge is repeated, GT layers are then computed by dense-tile kernels when that pays, i.e. when the
- * 16 x 16 score tiles of the graphs are full enough (edges / (256 x number of tiles) at least about 0.22
- * for bf16 and 0.33 for fp32; below that the general kernels are faster):
+ * 16 x 16 score tiles of the graphs are full enough (edges / (256 x number of tiles) at least about 0.17
+ * to 0.25 depending on the kernel; below that the general kernels are faster):
  *   bf16, D = 16 or 32, graphs of at most 64 nodes: one wavefront per (graph, head) stages the head's
  *     Q, K, V once into LDS and forms the masked score block with MFMA;
- *   fp32, D = 16, 32 or 64, graphs of at most 512 nodes: one wavefront per (graph, head, 16 rows)
- *     streams over the graph's column tiles with fp32 MFMA.
+ *   fp32 or bf16, D = 16, 32 or 64, graphs of at most 512 nodes: one wavefront per (graph, head, 16
+ *     rows) streams over the graph's column tiles with MFMA.
  * Every node row is then read once per graph (or once per row tile) instead of once per edge; results
  * agree with the general path to rounding.  Other layers, and batches that do not qualify, use the
  * general kernels unchanged.  Passing (NULL, 0, NULL, 0) forgets the batch structure.  Synchronises

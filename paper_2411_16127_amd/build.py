@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libdfgnn.so")
 # the layer kernels are instantiated in one unit per model and direction so that they compile in parallel;
 # the slowest units come first
 SOURCES = ["layer_gt_bwd.hip", "layer_gatv2_bwd.hip", "layer_agnn_bwd.hip", "layer_gat_bwd.hip", "layer_gt_fwd.hip",
-           "layer_gatv2_fwd.hip", "layer_agnn_fwd.hip", "layer_gat_fwd.hip", "dense_batch_f32.hip", "dense_batch.hip",
+           "layer_gatv2_fwd.hip", "layer_agnn_fwd.hip", "layer_gat_fwd.hip", "dense_batch_f32.hip", "dense_batch_bf16.hip", "dense_batch.hip",
            "graph.hip", "layer.hip", "api.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",

@@ -75,6 +75,7 @@ struct dfgnn_graph {
     const int32_t* batch_ptr;
     int64_t n_graphs;
     int32_t* tile_ptr;               // [n_graphs + 1] first 16-node tile of every graph
+    int32_t* tile_graph;             // [n_tiles] graph of every 16-node tile
     int64_t n_tiles;
     int64_t tile_pairs;              // sum over graphs of (tiles of the graph)^2: 16 x 16 score tiles a dense pass forms
     int32_t max_graph_nodes;
@@ -93,6 +94,11 @@ int dense_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, 
 int dense_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,
                       const float* row_max, const float* row_sum, const void* d_out, void* d_q, void* d_k, void* d_v,
                       hipStream_t st);
+int dense16_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v, void* out,
+                       float* row_max, float* row_sum, hipStream_t st);
+int dense16_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,
+                        const float* row_max, const float* row_sum, const void* d_out, void* d_q, void* d_k, void* d_v,
+                        float* stats, hipStream_t st);
 int dense32_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v, void* out,
                        float* row_max, float* row_sum, hipStream_t st);
 int dense32_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,

@@ -15,10 +15,9 @@
 // is already the A-operand layout of P for the second product, and no transpose through LDS is needed.
 #include "common.hpp"
 #include "layer_device.hpp"
+#include "dense_bf16.hpp"
 
 namespace dfgnn {
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kDenseMaxNodes = kDenseSmallNodes;  // nodes per graph these kernels cover (4 tiles of 16)
 constexpr int kDenseTiles = kDenseMaxNodes / 16;
@@ -34,37 +33,6 @@ struct DenseArgs {
     int n_graphs, H, D, HD, W;  // W: 64-bit words per mask row (only word 0 is used: graphs have <= 64 nodes)
     float c_score, scale;
 };
-
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
-__device__ inline uint32_t cvt_pk_bf16(float lo, float hi) {
-    const f32x2_t v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-__device__ inline uint16_t to_bf16(float f) { return (uint16_t)(cvt_pk_bf16(f, 0.f) & 0xffffu); }
-// A tile of fp32 weights (attention weights or their gradients) as MFMA A operand.  The weights are
-// split into a bf16 head and a bf16 remainder and multiplied in two MFMAs, so the second products keep
-// ~16 bits of the weights instead of 8 (MFMA time is negligible here; the inputs K, V, Q, dO are exact).
-struct SplitFrag {
-    s16x4 hi, lo;
-};
-__device__ inline SplitFrag split_bf16x4(float a, float b, float c, float d) {
-    const uint32_t h01 = cvt_pk_bf16(a, b), h23 = cvt_pk_bf16(c, d);
-    const float ha = __builtin_bit_cast(float, h01 << 16), hb = __builtin_bit_cast(float, h01 & 0xffff0000u);
-    const float hc = __builtin_bit_cast(float, h23 << 16), hd = __builtin_bit_cast(float, h23 & 0xffff0000u);
-    const uint32_t l01 = cvt_pk_bf16(a - ha, b - hb), l23 = cvt_pk_bf16(c - hc, d - hd);
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    SplitFrag f;
-    f.hi = __builtin_bit_cast(s16x4, u32x2{h01, h23});
-    f.lo = __builtin_bit_cast(s16x4, u32x2{l01, l23});
-    return f;
-}
-__device__ inline f32x4 mfma_split(const SplitFrag& a, s16x4 b, f32x4 acc) {
-    acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.hi, b, acc, 0, 0, 0);
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.lo, b, acc, 0, 0, 0);
-}
 
 __device__ inline float sum_over_q(float x) { x += __shfl_xor(x, 16); x += __shfl_xor(x, 32); return x; }
 __device__ inline float max_over_q(float x) { x = fmaxf(x, __shfl_xor(x, 16)); x = fmaxf(x, __shfl_xor(x, 32)); return x; }
@@ -340,19 +308,30 @@ __global__ __launch_bounds__(64 * WAVES) void k_dense_gt_backward(const DenseArg
 
 // The dense kernels form every 16 x 16 score tile of a graph whatever its density, the gather kernels pay
 // per edge, so what decides is how full the tiles are: fill = E / (256 * tile pairs).  Measured on MI355X
-// (profiles/dense_batch_study.md): the bf16 kernels win from a fill of about 0.22 (0.83x at 0.19, 1.6x at
-// 0.30, 3.6x at 0.94), the fp32 kernels, whose MFMA rate is 16 times lower, from about 0.33 (1.05x at
-// 0.31, 1.28x at 0.43).
-constexpr int64_t kDenseMinEdgesPerTileBf16 = 56;  // 0.22 * 256
-constexpr int64_t kDenseMinEdgesPerTileF32 = 85;   // 0.33 * 256
+// against the gather kernels:
+//   bf16 kernels of this file:   0.83x at fill 0.19, 1.6x at 0.30, 3.6x at 0.94   -> used from 0.22
+//   fp32 streaming kernels:      0.88x at 0.10, 1.16x at 0.19, 1.3x at 0.28, 1.6x at 0.39   -> used from 0.17
+//   bf16 streaming kernels:      0.54x at 0.10, 1.3x at 0.28, 1.5x at 0.39 (2.5x for one head of 64
+//                                features)   -> used from 0.25
+// The streaming kernels gain less because they fetch their operands again for every row tile and spend
+// most of their time on the softmax arithmetic of masked-out tile entries.
+constexpr int64_t kDenseMinEdgesPerTileBf16 = 56;        // 0.22 * 256
+constexpr int64_t kDenseMinEdgesPerTileBf16Stream = 64;  // 0.25 * 256
+constexpr int64_t kDenseMinEdgesPerTileF32 = 44;         // 0.17 * 256
 
-// 1: bf16 kernels of this file; 2: fp32 kernels (dense_batch_f32.hip); 0: general kernels
+// 1: bf16 kernels of this file (graphs of at most 64 nodes, staged in LDS); 2: fp32 streaming kernels
+// (dense_batch_f32.hip); 3: bf16 streaming kernels (dense_batch_bf16.hip); 0: general kernels
 int dense_batch_kind(const dfgnn_graph* g, const dfgnn_layer* L) {
     if (!g->batch_dense || (g->flags & DFGNN_SCHED_NO_DENSE_BATCH) || L->model != DFGNN_GT) return 0;
     const bool force = g->flags & DFGNN_SCHED_FORCE_DENSE_BATCH;
-    if (L->dtype == DFGNN_BF16 && (L->D == 16 || L->D == 32) && g->max_graph_nodes <= kDenseSmallNodes)
-        return (force || g->E >= kDenseMinEdgesPerTileBf16 * g->tile_pairs) ? 1 : 0;
-    if (L->dtype == DFGNN_F32 && (L->D == 16 || L->D == 32 || L->D == 64))
+    const bool width_ok = L->D == 16 || L->D == 32 || L->D == 64;
+    if (L->dtype == DFGNN_BF16 && width_ok) {
+        const bool small = L->D <= 32 && g->max_graph_nodes <= kDenseSmallNodes;
+        const int64_t need = small ? kDenseMinEdgesPerTileBf16 : kDenseMinEdgesPerTileBf16Stream;
+        if (!force && g->E < need * g->tile_pairs) return 0;
+        return small ? 1 : 3;
+    }
+    if (L->dtype == DFGNN_F32 && width_ok)
         return (force || g->E >= kDenseMinEdgesPerTileF32 * g->tile_pairs) ? 2 : 0;
     return 0;
 }

@@ -12,16 +12,20 @@
 // Score tiles are computed transposed (S^T = K Q^T): a lane owns query row i = l % 16 and keys
 // j = 4q + r, which is the A-operand layout of the second product (k index q <-> key 4q + r in MFMA
 // number r, whose B operand is the single element V[4q + r][l % 16]).
-// The forward kernel makes two sweeps over the column tiles (row maximum and sum, then weights and
+// The forward kernel makes two sweeps over the column tiles (row maximum, then weights, their sum and the
 // aggregation); recomputing the score tile costs four MFMAs and avoids rescaling the accumulator.
+// All loads of the tile loops are buffer loads against a view of the wavefront's own graph and head
+// (rows past the graph's end read as zero), so the loops have no bounds checks and no branches.
 #include "common.hpp"
 #include "layer_device.hpp"
+#include "dense_stream.hpp"
 
 namespace dfgnn {
 
 struct DenseF32Args {
     const int* batch_ptr;
     const int* tile_ptr;                   // first 16-row tile of every graph
+    const int* tile_graph;                 // graph of every 16-row tile
     const unsigned long long* adj_mask;    // [N][W]: bit j of row i's words = edge i <- (first node of the graph + j)
     const unsigned long long* adj_mask_t;  // [N][W]: bit i of column j's words = edge (first + i) <- j
     const float *q, *k, *v, *out, *d_out, *row_max, *row_sum;
@@ -30,38 +34,19 @@ struct DenseF32Args {
     float c_score, scale;
 };
 
-struct Unit {
-    int base, n, tiles, t, h;  // graph's first node, node count, tile count; this wave's tile and head
+// Per-lane byte offsets into a unit's tensor view for column (or row) tile 0; a tile step adds 16 rows.
+struct LaneOffsets32 {
+    uint32_t frag;  // features 4q .. 4q+3 of row l16 (operands of a score product)
+    uint32_t col;   // feature l16 of row 4q (B operand of a second product: rows 4q .. 4q+3)
+    uint32_t row_bytes, tile_bytes;
 };
-
-__device__ inline Unit find_unit(const DenseF32Args& a, int u) {
-    const int tile = u / a.H;
-    Unit r;
-    r.h = u - tile * a.H;
-    int lo = 0, hi = a.n_graphs;  // last graph whose first tile is <= tile
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.tile_ptr[mid] <= tile) lo = mid; else hi = mid;
-    }
-    r.base = a.batch_ptr[lo];
-    r.n = a.batch_ptr[lo + 1] - r.base;
-    r.tiles = (r.n + 15) >> 4;
-    r.t = tile - a.tile_ptr[lo];
-    return r;
-}
-
-// features kb*16 + 4q .. +3 of node `row` of the unit's graph and head (zeros past the graph's end)
-__device__ inline f32x4 row_frag(const float* x, const DenseF32Args& a, const Unit& u, int row, int kb, int q, int D) {
-    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    if (row < u.n) z = *reinterpret_cast<const f32x4*>(x + (size_t)(u.base + row) * a.HD + u.h * D + kb * 16 + 4 * q);
-    return z;
-}
-__device__ inline float elem(const float* x, const DenseF32Args& a, const Unit& u, int row, int d, int D) {
-    return row < u.n ? x[(size_t)(u.base + row) * a.HD + u.h * D + d] : 0.f;
-}
-// bits for entries 4q .. 4q+3 of 16-wide tile `t` in a row of mask words (nullptr: no bits)
-__device__ inline uint32_t tile_bits(const unsigned long long* words, int t, int q) {
-    return words ? (uint32_t)(words[t >> 2] >> ((t & 3) * 16 + 4 * q)) & 0xfu : 0u;
+__device__ inline LaneOffsets32 lane_offsets32(int HD, int l16, int q) {
+    LaneOffsets32 o;
+    o.row_bytes = (uint32_t)HD * 4u;
+    o.tile_bytes = 16u * o.row_bytes;
+    o.frag = (uint32_t)l16 * o.row_bytes + (uint32_t)q * 16u;
+    o.col = (uint32_t)(4 * q) * o.row_bytes + (uint32_t)l16 * 4u;
+    return o;
 }
 
 template <int KB> __device__ inline f32x4 tile_product(const f32x4 (&a)[KB], const f32x4 (&b)[KB]) {
@@ -73,77 +58,65 @@ template <int KB> __device__ inline f32x4 tile_product(const f32x4 (&a)[KB], con
     return acc;
 }
 
-__device__ inline float sum_q(float x) { x += __shfl_xor(x, 16); x += __shfl_xor(x, 32); return x; }
-
-constexpr int kDenseWaves = 4;
-
 // ---------------------------------------------------------------------------------------------
-// forward
+// forward: a sweep for the row maximum, then a sweep for weights, their sum and the aggregation
 // ---------------------------------------------------------------------------------------------
 template <int KB>
 __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_forward(const DenseF32Args a) {
     constexpr int D = KB * 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int uidx = blockIdx.x * kDenseWaves + wave;
+    const int uidx = xcd_block(blockIdx.x, gridDim.x) * kDenseWaves + wave;
     if (uidx >= a.n_tiles * a.H) return;
     const Unit u = find_unit(a, uidx);
     const int l16 = lane & 15, q = lane >> 4;
+    const LaneOffsets32 lo = lane_offsets32(a.HD, l16, q);
+    const rsrc_t rq = unit_tensor(a.q, u, a.HD, D, 4), rk = unit_tensor(a.k, u, a.HD, D, 4), rv = unit_tensor(a.v, u, a.HD, D, 4);
+    const rsrc_t rm = unit_rows(a.adj_mask, u, a.W * 8, 0, a.W * 8);
     const int i = u.t * 16 + l16;
+    const uint32_t moff = (uint32_t)i * (uint32_t)(a.W * 8);
     f32x4 qf[KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) qf[kb] = row_frag(a.q, a, u, i, kb, q, D) * a.c_score;
-    const unsigned long long* mrow = i < u.n ? a.adj_mask + (size_t)(u.base + i) * a.W : nullptr;
+    for (int kb = 0; kb < KB; ++kb) qf[kb] = buf_load_f32x4(rq, lo.frag + (uint32_t)u.t * lo.tile_bytes + kb * 64u) * a.c_score;
 
-    // sweep 1: maximum and sum of the row's exponentials, each lane over its own keys
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY;
     for (int jt = 0; jt < u.tiles; ++jt) {
         f32x4 kf[KB];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) kf[kb] = row_frag(a.k, a, u, jt * 16 + l16, kb, q, D);
+        for (int kb = 0; kb < KB; ++kb) kf[kb] = buf_load_f32x4(rk, lo.frag + (uint32_t)jt * lo.tile_bytes + kb * 64u);
+        const uint32_t bits = tile_bits(rm, moff, jt, q);
         const f32x4 s = tile_product<KB>(kf, qf);
-        const uint32_t bits = tile_bits(mrow, jt, q);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if ((bits >> r) & 1u) {
-                const float mn = fmaxf(m, s[r]);
-                l = l * fast_exp2(m - mn) + fast_exp2(s[r] - mn);
-                m = mn;
-            }
-        }
+        for (int r = 0; r < 4; ++r) m = fmaxf(m, ((bits >> r) & 1u) ? s[r] : -INFINITY);
     }
-#pragma unroll
-    for (int o = 16; o < 64; o <<= 1) {
-        const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
-        const float mn = fmaxf(m, mo);
-        l = (m == mn ? l : l * fast_exp2(m - mn)) + (mo == mn ? lo : lo * fast_exp2(mo - mn));
-        m = mn;
-    }
-    if (q == 0 && i < u.n) {
-        a.o_max[(size_t)(u.base + i) * a.H + u.h] = m * kLn2;
-        a.o_sum[(size_t)(u.base + i) * a.H + u.h] = l;
-    }
+    m = max_q(m);
 
-    // sweep 2: weights and aggregation
+    float l = 0.f;
     f32x4 acc[KB];
 #pragma unroll
     for (int nt = 0; nt < KB; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int jt = 0; jt < u.tiles; ++jt) {
         f32x4 kf[KB];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) kf[kb] = row_frag(a.k, a, u, jt * 16 + l16, kb, q, D);
+        for (int kb = 0; kb < KB; ++kb) kf[kb] = buf_load_f32x4(rk, lo.frag + (uint32_t)jt * lo.tile_bytes + kb * 64u);
         float vv[KB][4];
 #pragma unroll
         for (int nt = 0; nt < KB; ++nt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) vv[nt][r] = elem(a.v, a, u, jt * 16 + 4 * q + r, nt * 16 + l16, D);
+            for (int r = 0; r < 4; ++r) vv[nt][r] = buf_load_f32(rv, lo.col + (uint32_t)jt * lo.tile_bytes + r * lo.row_bytes + nt * 64u);
+        const uint32_t bits = tile_bits(rm, moff, jt, q);
         const f32x4 s = tile_product<KB>(kf, qf);
-        const uint32_t bits = tile_bits(mrow, jt, q);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float p = ((bits >> r) & 1u) ? fast_exp2(s[r] - m) : 0.f;
+            l += p;
 #pragma unroll
             for (int nt = 0; nt < KB; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(p, vv[nt][r], acc[nt], 0, 0, 0);
         }
+    }
+    l = sum_q(l);
+    if (q == 0 && i < u.n) {
+        a.o_max[(size_t)(u.base + i) * a.H + u.h] = m * kLn2;
+        a.o_sum[(size_t)(u.base + i) * a.H + u.h] = l;
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -164,18 +137,24 @@ template <int KB>
 __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_backward_rows(const DenseF32Args a) {
     constexpr int D = KB * 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int uidx = blockIdx.x * kDenseWaves + wave;
+    const int uidx = xcd_block(blockIdx.x, gridDim.x) * kDenseWaves + wave;
     if (uidx >= a.n_tiles * a.H) return;
     const Unit u = find_unit(a, uidx);
     const int l16 = lane & 15, q = lane >> 4;
+    const LaneOffsets32 lo = lane_offsets32(a.HD, l16, q);
+    const rsrc_t rq = unit_tensor(a.q, u, a.HD, D, 4), rk = unit_tensor(a.k, u, a.HD, D, 4), rv = unit_tensor(a.v, u, a.HD, D, 4);
+    const rsrc_t rg = unit_tensor(a.d_out, u, a.HD, D, 4), ro = unit_tensor(a.out, u, a.HD, D, 4);
+    const rsrc_t rm = unit_rows(a.adj_mask, u, a.W * 8, 0, a.W * 8);
     const int i = u.t * 16 + l16;
+    const uint32_t moff = (uint32_t)i * (uint32_t)(a.W * 8);
     f32x4 qf[KB], gf[KB];
     float dsum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
-        qf[kb] = row_frag(a.q, a, u, i, kb, q, D) * a.c_score;
-        gf[kb] = row_frag(a.d_out, a, u, i, kb, q, D);
-        const f32x4 of = row_frag(a.out, a, u, i, kb, q, D);
+        const uint32_t off = lo.frag + (uint32_t)u.t * lo.tile_bytes + kb * 64u;
+        qf[kb] = buf_load_f32x4(rq, off) * a.c_score;
+        gf[kb] = buf_load_f32x4(rg, off);
+        const f32x4 of = buf_load_f32x4(ro, off);
 #pragma unroll
         for (int e = 0; e < 4; ++e) dsum = fmaf(gf[kb][e], of[e], dsum);
     }
@@ -183,7 +162,6 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_backward_rows(cons
     float lse = 0.f;
     if (i < u.n)
         lse = a.row_max[(size_t)(u.base + i) * a.H + u.h] * kLog2e + fast_log2(a.row_sum[(size_t)(u.base + i) * a.H + u.h]);
-    const unsigned long long* mrow = i < u.n ? a.adj_mask + (size_t)(u.base + i) * a.W : nullptr;
     if (q == 0 && i < u.n) {
         f32x2 st = {lse, delta};
         *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)(u.base + i) * a.H + u.h)) = st;
@@ -195,17 +173,17 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_backward_rows(cons
         f32x4 kf[KB], vf[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            kf[kb] = row_frag(a.k, a, u, jt * 16 + l16, kb, q, D);
-            vf[kb] = row_frag(a.v, a, u, jt * 16 + l16, kb, q, D);
+            kf[kb] = buf_load_f32x4(rk, lo.frag + (uint32_t)jt * lo.tile_bytes + kb * 64u);
+            vf[kb] = buf_load_f32x4(rv, lo.frag + (uint32_t)jt * lo.tile_bytes + kb * 64u);
         }
         float kk[KB][4];
 #pragma unroll
         for (int nt = 0; nt < KB; ++nt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) kk[nt][r] = elem(a.k, a, u, jt * 16 + 4 * q + r, nt * 16 + l16, D);
+            for (int r = 0; r < 4; ++r) kk[nt][r] = buf_load_f32(rk, lo.col + (uint32_t)jt * lo.tile_bytes + r * lo.row_bytes + nt * 64u);
+        const uint32_t bits = tile_bits(rm, moff, jt, q);
         const f32x4 s = tile_product<KB>(kf, qf);
         const f32x4 dp = tile_product<KB>(vf, gf);
-        const uint32_t bits = tile_bits(mrow, jt, q);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float p = ((bits >> r) & 1u) ? fast_exp2(s[r] - lse) : 0.f;
@@ -232,18 +210,24 @@ template <int KB>
 __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_backward_cols(const DenseF32Args a) {
     constexpr int D = KB * 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int uidx = blockIdx.x * kDenseWaves + wave;
+    const int uidx = xcd_block(blockIdx.x, gridDim.x) * kDenseWaves + wave;
     if (uidx >= a.n_tiles * a.H) return;
     const Unit u = find_unit(a, uidx);
     const int l16 = lane & 15, q = lane >> 4;
+    const LaneOffsets32 lo = lane_offsets32(a.HD, l16, q);
+    const rsrc_t rq = unit_tensor(a.q, u, a.HD, D, 4), rk = unit_tensor(a.k, u, a.HD, D, 4), rv = unit_tensor(a.v, u, a.HD, D, 4);
+    const rsrc_t rg = unit_tensor(a.d_out, u, a.HD, D, 4);
+    const rsrc_t rm = unit_rows(a.adj_mask_t, u, a.W * 8, 0, a.W * 8);
+    const rsrc_t rs = unit_rows(a.stats, u, a.H * 8, u.h * 8, 8);  // {lse2, delta} of (row, this head)
     const int j = u.t * 16 + l16;
+    const uint32_t moff = (uint32_t)j * (uint32_t)(a.W * 8);
+    const uint32_t soff = (uint32_t)(4 * q) * (uint32_t)(a.H * 8);
     f32x4 kf[KB], vf[KB];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
-        kf[kb] = row_frag(a.k, a, u, j, kb, q, D) * a.c_score;
-        vf[kb] = row_frag(a.v, a, u, j, kb, q, D);
+        kf[kb] = buf_load_f32x4(rk, lo.frag + (uint32_t)u.t * lo.tile_bytes + kb * 64u) * a.c_score;
+        vf[kb] = buf_load_f32x4(rv, lo.frag + (uint32_t)u.t * lo.tile_bytes + kb * 64u);
     }
-    const unsigned long long* mcol = j < u.n ? a.adj_mask_t + (size_t)(u.base + j) * a.W : nullptr;
     f32x4 acc_v[KB], acc_k[KB];
 #pragma unroll
     for (int nt = 0; nt < KB; ++nt) { acc_v[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; acc_k[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
@@ -251,30 +235,28 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense32_backward_cols(cons
         f32x4 qf[KB], gf[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            qf[kb] = row_frag(a.q, a, u, it * 16 + l16, kb, q, D);
-            gf[kb] = row_frag(a.d_out, a, u, it * 16 + l16, kb, q, D);
+            qf[kb] = buf_load_f32x4(rq, lo.frag + (uint32_t)it * lo.tile_bytes + kb * 64u);
+            gf[kb] = buf_load_f32x4(rg, lo.frag + (uint32_t)it * lo.tile_bytes + kb * 64u);
         }
-        float qq[KB][4], gg[KB][4], lse[4], delta[4];
+        float qq[KB][4], gg[KB][4];
+        f32x2 st[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = it * 16 + 4 * q + r;
-            f32x2 st = {0.f, 0.f};
-            if (row < u.n) st = *reinterpret_cast<const f32x2*>(a.stats + 2 * ((size_t)(u.base + row) * a.H + u.h));
-            lse[r] = st[0];
-            delta[r] = st[1];
+            st[r] = buf_load_f32x2(rs, soff + (uint32_t)(it * 16 + r) * (uint32_t)(a.H * 8));
 #pragma unroll
             for (int nt = 0; nt < KB; ++nt) {
-                qq[nt][r] = elem(a.q, a, u, row, nt * 16 + l16, D);
-                gg[nt][r] = elem(a.d_out, a, u, row, nt * 16 + l16, D);
+                const uint32_t off = lo.col + (uint32_t)it * lo.tile_bytes + r * lo.row_bytes + nt * 64u;
+                qq[nt][r] = buf_load_f32(rq, off);
+                gg[nt][r] = buf_load_f32(rg, off);
             }
         }
+        const uint32_t bits = tile_bits(rm, moff, it, q);
         const f32x4 s = tile_product<KB>(qf, kf);    // s[r] = score of (row 4q + r of the tile, column j)
         const f32x4 dp = tile_product<KB>(gf, vf);
-        const uint32_t bits = tile_bits(mcol, it, q);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float p = ((bits >> r) & 1u) ? fast_exp2(s[r] - lse[r]) : 0.f;
-            const float ds = p * (dp[r] - delta[r]);
+            const float p = ((bits >> r) & 1u) ? fast_exp2(s[r] - st[r][0]) : 0.f;
+            const float ds = p * (dp[r] - st[r][1]);
 #pragma unroll
             for (int nt = 0; nt < KB; ++nt) {
                 acc_v[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(p, gg[nt][r], acc_v[nt], 0, 0, 0);
@@ -303,6 +285,7 @@ static DenseF32Args dense32_args(const dfgnn_graph* g, const dfgnn_layer* L) {
     DenseF32Args a{};
     a.batch_ptr = g->batch_ptr;
     a.tile_ptr = g->tile_ptr;
+    a.tile_graph = g->tile_graph;
     a.adj_mask = g->adj_mask;
     a.adj_mask_t = g->adj_mask_t;
     a.n_graphs = (int)g->n_graphs;

@@ -557,6 +557,13 @@ __global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int 
     if (bad) atomicOr(flags, bad);
 }
 
+// graph of every 16-row tile
+__global__ void k_batch_tile_graph(const int* __restrict__ tile_ptr, int n_graphs, int* __restrict__ tile_graph) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_graphs) return;
+    for (int t = tile_ptr[g]; t < tile_ptr[g + 1]; ++t) tile_graph[t] = g;
+}
+
 // One thread per node: adjacency bits of its row (from the CSR) and of its column (from the CSC), both
 // relative to the first node of its graph, `words` 64-bit words each.
 __global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const int* __restrict__ ptr,
@@ -594,7 +601,7 @@ __global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const in
 }
 
 struct BatchLayout {
-    size_t adj_mask, adj_mask_t, tile_ptr, scan_tmp, total;
+    size_t adj_mask, adj_mask_t, tile_ptr, tile_graph, scan_tmp, total;
 };
 static BatchLayout batch_layout(int64_t N, int64_t n_graphs) {
     BatchLayout L{};
@@ -603,6 +610,7 @@ static BatchLayout batch_layout(int64_t N, int64_t n_graphs) {
     L.adj_mask = take((size_t)N * kDenseMaxWords * 8);
     L.adj_mask_t = take((size_t)N * kDenseMaxWords * 8);
     L.tile_ptr = take((size_t)(n_graphs + 2) * 4);
+    L.tile_graph = take((size_t)(N / 16 + n_graphs + 2) * 4);  // every graph has at most nodes/16 + 1 tiles
     L.scan_tmp = take((size_t)(scan_blocks(n_graphs + 2) + 1) * 4);
     L.total = off;
     return L;
@@ -651,6 +659,10 @@ extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr,
     DFGNN_HIP(hipMemcpyAsync(&pairs, d_pairs, sizeof(pairs), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
     DFGNN_REQUIRE(!(host[0] & BATCH_BAD_PTR), DFGNN_EINVAL, "batch_ptr must start at 0, end at N and be non-decreasing");
+    int* tile_graph = (int*)(buf + B.tile_graph);  // a valid pointer array has at most N / 16 + n_graphs tiles
+    if (n_graphs > 0)
+        hipLaunchKernelGGL(k_batch_tile_graph, dim3((unsigned)((n_graphs + tpb - 1) / tpb)), dim3(tpb), 0, st, tile_ptr,
+                           (int)n_graphs, tile_graph);
     const int max_nodes = host[1];
     int words = (max_nodes + 63) / 64;
     if (words < 1) words = 1;
@@ -671,6 +683,7 @@ extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr,
     g->batch_ptr = d_batch_ptr;
     g->n_graphs = n_graphs;
     g->tile_ptr = tile_ptr;
+    g->tile_graph = tile_graph;
     g->n_tiles = n_tiles;
     g->tile_pairs = (int64_t)pairs;
     g->max_graph_nodes = max_nodes;

@@ -201,8 +201,10 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
     DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
                   "edge term of E*H*4 bytes must stay below 4 GiB");
     if (const int kind = edge_bias ? 0 : dense_batch_kind(graph, layer)) {  // the dense-tile kernels have no edge term
-        rc = kind == 1 ? dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream)
-                       : dense32_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, (hipStream_t)stream);
+        hipStream_t st = (hipStream_t)stream;
+        rc = kind == 1   ? dense_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, st)
+             : kind == 2 ? dense32_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, st)
+                         : dense16_gt_forward(graph, layer, x, k, v, out, row_max, row_sum, st);
         if (rc != DFGNN_OK) return rc;
         DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;
@@ -295,9 +297,11 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, backward needs %zu",
                   workspace_bytes, W.total);
     hipStream_t st = (hipStream_t)stream;
-    if (dense_kind == 2) {  // the row kernel hands {lse2, delta} to the column kernel through the workspace
-        rc = dense32_gt_backward(graph, layer, x, k, v, out, row_max, row_sum, d_out, d_x, d_k, d_v,
-                                 (float*)((char*)workspace + W.stats), st);
+    if (dense_kind != 0) {  // the row kernel hands {lse2, delta} to the column kernel through the workspace
+        float* stats = (float*)((char*)workspace + W.stats);
+        rc = dense_kind == 2 ? dense32_gt_backward(graph, layer, x, k, v, out, row_max, row_sum, d_out, d_x, d_k, d_v,
+                                                   stats, st)
+                             : dense16_gt_backward(graph, layer, x, k, v, row_max, row_sum, d_out, d_x, d_k, d_v, stats, st);
         if (rc != DFGNN_OK) return rc;
         DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;

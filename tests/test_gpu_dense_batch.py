@@ -84,7 +84,7 @@ def test_dense_path_is_chosen_for_dense_enough_batches():
 def test_layers_outside_the_dense_path_still_use_the_general_kernels():
     graph = batched_small_graphs(30, 10, 40, 0.3, seed=9)
     for w in (Workload("b", 92, "gt", 2, 16, "f32", 0.25), Workload("b", 92, "gat", 2, 16, "bf16", 1.0),
-              Workload("b", 92, "gt", 2, 64, "bf16", 0.125)):
+              Workload("b", 92, "gt", 1, 128, "bf16", 0.09)):
         feats = make_features(w, graph.n)
         res, g = run_gpu(graph, w, feats)
         compare_all(res, run_oracle(graph, w, feats), w)
@@ -92,7 +92,7 @@ def test_layers_outside_the_dense_path_still_use_the_general_kernels():
 
 
 def test_large_graphs_and_repeated_edges_switch_the_dense_path_off():
-    big = batched_small_graphs(6, 60, 90, 0.2, seed=2)  # some graphs exceed 64 nodes: too large for the bf16 kernels
+    big = batched_small_graphs(3, 520, 530, 0.01, seed=2)  # graphs above 512 nodes: too large for dense tiles
     w = gt_bf16(2, 16)
     feats = make_features(w, big.n)
     res, g = run_gpu(big, w, feats, sched=FORCE)
@@ -140,6 +140,52 @@ def test_set_batch_rejects_bad_input():
 
 
 # ------------------------------------------------------------------ fp32 dense-tile path (graphs up to 512 nodes)
+@pytest.mark.parametrize("H,D", [(8, 16), (1, 16), (3, 32), (2, 64)])
+@pytest.mark.parametrize("sizes,density", [((60, 70), 0.3), ((100, 130), 0.4), ((250, 260), 0.05), ((500, 512), 0.02),
+                                           ((65, 65), 1.0)])
+def test_dense_bf16_streaming_matches_oracle(H, D, sizes, density):
+    """Graphs above 64 nodes (and heads of 64 features at any size): one wavefront per 16-row tile streams
+    over the graph's column tiles."""
+    graph = batched_small_graphs(9, sizes[0], sizes[1], density, seed=12)
+    w = gt_bf16(H, D)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, sched=FORCE)
+    assert g.query("n_batch_dense") == 1
+    general, g2 = run_gpu(graph, w, feats, use_batch=False)
+    assert any(not np.array_equal(res[key], general[key]) for key in res)  # really a different path
+    ref = run_oracle(graph, w, feats)
+    compare_all(res, ref, w)
+    compare_all(general, ref, w)
+    g.close(); g2.close()
+
+
+def test_dense_bf16_streaming_small_graphs_wide_heads_and_empty_rows():
+    rng = np.random.default_rng(15)
+    sizes = rng.integers(5, 150, size=14)
+    bp = np.concatenate([[0], np.cumsum(sizes)])
+    src, dst = [], []
+    for b in range(14):
+        adj = rng.random((sizes[b], sizes[b])) < 0.03
+        d, s_ = np.nonzero(adj)
+        src.append(s_ + bp[b]); dst.append(d + bp[b])
+    graph = from_edge_list(int(bp[-1]), np.concatenate(src), np.concatenate(dst), batch_ptr=bp)
+    assert (graph.degrees() == 0).sum() > 50
+    for H, D in ((2, 16), (1, 64)):
+        w = gt_bf16(H, D)
+        feats = make_features(w, graph.n)
+        res, g = run_gpu(graph, w, feats, sched=FORCE)
+        compare_all(res, run_oracle(graph, w, feats), w)
+        g.close()
+    small = batched_small_graphs(20, 10, 40, 0.3, seed=4)  # at most 64 nodes but 64 features per head
+    w = gt_bf16(2, 64)
+    feats = make_features(w, small.n)
+    res, g = run_gpu(small, w, feats, sched=FORCE)
+    general, g2 = run_gpu(small, w, feats, use_batch=False)
+    assert any(not np.array_equal(res[key], general[key]) for key in res)
+    compare_all(res, run_oracle(small, w, feats), w)
+    g.close(); g2.close()
+
+
 def gt_f32(H, D):
     return Workload("batch32", 93, "gt", H, D, "f32", float(D) ** -0.5)
 
