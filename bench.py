@@ -337,7 +337,7 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline and not args.edge_bias:
-        target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 3000000, "cfg5": 2000000}[w.name]
+        target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 8000000, "cfg5": 10000000}[w.name]
         info, (rows, new_rows, fw, bw) = cpu_baseline(w, graph, feats, target)
         # the sampled rows double as a parity spot check of the buffers that were just timed
         got = out[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
