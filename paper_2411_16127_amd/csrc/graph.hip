@@ -298,18 +298,31 @@ __global__ void k_pointer_from_sorted(const uint32_t* __restrict__ sorted, int e
     t_indptr[j] = lo;
 }
 
-// destination row of CSR position p: the last row whose pointer is <= p
-__global__ void k_rows_of_positions(const int* __restrict__ t_eid, const int* __restrict__ indptr, int n, int e,
-                                    int* __restrict__ t_indices) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= e) return;
-    const int p = t_eid ? t_eid[t] : (int)t;  // no position list: the positions are 0..e-1 themselves
-    int lo = 0, hi = n;  // invariant: indptr[lo] <= p < indptr[hi]
+// Destination row of every CSR position (the COO row array of the CSR).  A thread finds the row of the
+// first of its kRowsPerThread consecutive positions by binary search (the last row whose pointer is <= p)
+// and walks the pointer array from there, so the search is paid once per 16 edges.
+constexpr int kRowsPerThread = 16;
+__global__ void k_edge_rows(const int* __restrict__ indptr, int n, int e, int* __restrict__ edge_row) {
+    const int64_t p0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * kRowsPerThread;
+    if (p0 >= e) return;
+    int lo = 0, hi = n;  // invariant: indptr[lo] <= p0 < indptr[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (indptr[mid] <= p) lo = mid; else hi = mid;
+        if (indptr[mid] <= p0) lo = mid; else hi = mid;
     }
-    t_indices[t] = lo;
+    int row = lo, next = indptr[lo + 1];
+    for (int k = 0; k < kRowsPerThread && p0 + k < e; ++k) {
+        const int p = (int)(p0 + k);
+        while (p >= next) next = indptr[++row + 1];  // p < e = indptr[n], so row stays below n
+        edge_row[p] = row;
+    }
+}
+
+// destination of every CSC entry: the row of its CSR position
+__global__ void k_gather_rows(const int* __restrict__ t_eid, const int* __restrict__ edge_row, int e,
+                              int* __restrict__ t_indices) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < e) t_indices[t] = edge_row[t_eid[t]];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -509,11 +522,13 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
         if (rc != DFGNN_OK) return rc;
         hipLaunchKernelGGL(k_pointer_from_sorted, dim3((unsigned)((N + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, sorted,
                            (int)E, (int)N, g.t_indptr);
-        hipLaunchKernelGGL(k_rows_of_positions, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid,
-                           d_indptr, (int)N, (int)E, g.t_indices);
-        if (g.edge_row)  // COO row array of the CSR itself (edge-parallel comparator)
-            hipLaunchKernelGGL(k_rows_of_positions, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st,
-                               (const int*)nullptr, d_indptr, (int)N, (int)E, g.edge_row);
+        // COO row array of the CSR: kept when the edge-parallel comparator asked for it, else in sort scratch
+        int* edge_row = g.edge_row ? g.edge_row : (int*)(scratch + S.vals);
+        const int64_t row_threads = (E + kRowsPerThread - 1) / kRowsPerThread;
+        hipLaunchKernelGGL(k_edge_rows, dim3((unsigned)((row_threads + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr, (int)N,
+                           (int)E, edge_row);
+        hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid, edge_row, (int)E,
+                           g.t_indices);
         DFGNN_HIP(hipGetLastError());
     } else {
         DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));
