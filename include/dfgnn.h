@@ -80,8 +80,10 @@ typedef struct {
     int32_t dtype;   /* dfgnn_dtype of node tensors (inputs, outputs and their gradients) */
     int32_t H;       /* heads */
     int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
-                        of two (vec = 4 for fp32, 8 for bf16), H*D/vec <= 64, and one node tensor
-                        (N*H*D elements) must stay below 4 GiB */
+                        of two (vec = 4 for fp32, 8 for bf16) and at most 64 (one head fits one wavefront of
+                        16-byte lanes: D <= 256 in fp32, 512 in bf16), and one node tensor (N*H*D elements)
+                        must stay below 4 GiB.  Rows of more than 64 such lanes (H*D/vec > 64) are processed
+                        in groups of heads, one launch sequence per group. */
     float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT, GATv2: ignored */
     float neg_slope; /* GAT, GATv2: LeakyReLU slope (derivative at 0 is neg_slope) */
     float eps;       /* AGNN: lower clamp of the feature norm */

@@ -8,11 +8,16 @@ namespace dfgnn {
 // ---------------------------------------------------------------------------------------------
 // lane geometry
 // ---------------------------------------------------------------------------------------------
+// A wavefront covers at most 64 lanes x 16 bytes of a node row.  A layer whose rows are wider is run as
+// `groups` launches sequences over `heads` heads each (heads are independent): the kernels see a layer
+// of `heads` heads whose tensors have the strides of the whole layer.
 struct Geometry {
-    int vec;  // elements per lane
-    int lph;  // lanes per head
-    int lpe;  // lanes per neighbour row (power of two, >= 4)
-    int id;   // index into the instantiation table, -1 if none
+    int vec;     // elements per lane
+    int lph;     // lanes per head
+    int lpe;     // lanes per neighbour row (power of two, >= 4)
+    int id;      // index into the instantiation table
+    int heads;   // heads per group (a divisor of H)
+    int groups;  // H / heads
 };
 
 static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
@@ -23,8 +28,12 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
     DFGNN_REQUIRE(L->D % g.vec == 0, DFGNN_EUNSUPPORTED, "D=%d: a head must be a multiple of 16 bytes", L->D);
     g.lph = L->D / g.vec;
     DFGNN_REQUIRE((g.lph & (g.lph - 1)) == 0, DFGNN_EUNSUPPORTED, "D=%d: D/%d must be a power of two", L->D, g.vec);
-    const int lanes = L->H * g.lph;
-    DFGNN_REQUIRE(lanes <= 64, DFGNN_EUNSUPPORTED, "H*D=%d exceeds one wavefront of 16-byte lanes", L->H * L->D);
+    DFGNN_REQUIRE(g.lph <= 64, DFGNN_EUNSUPPORTED, "D=%d: one head exceeds one wavefront of 16-byte lanes", L->D);
+    g.heads = 1;
+    for (int h = 1; h <= L->H && h * g.lph <= 64; ++h)
+        if (L->H % h == 0) g.heads = h;
+    g.groups = L->H / g.heads;
+    const int lanes = g.heads * g.lph;
     g.lpe = 4;
     while (g.lpe < lanes) g.lpe <<= 1;
     const bool f32 = L->dtype == DFGNN_F32;
@@ -56,11 +65,12 @@ static bool scores_in_memory(const dfgnn_graph* g, const dfgnn_layer* L) {
     return (g->flags & DFGNN_SCHED_SCORES_IN_MEMORY) && L->model == DFGNN_GT && g->E > 0;
 }
 
-static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward) {
+// sized for one group of `heads` heads: the groups of a wide layer run one after the other and reuse it
+static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bool backward, int heads) {
     Workspace W{};
     size_t off = 0;
     auto take = [&](size_t floats) { size_t o = off; off += align_up((floats ? floats : 1) * sizeof(float)); return o; };
-    const size_t N = (size_t)g->N, H = (size_t)L->H, HD = (size_t)L->H * L->D;
+    const size_t N = (size_t)g->N, H = (size_t)heads, HD = (size_t)heads * L->D;
     const size_t chunks = backward ? (size_t)(g->n_row_chunks > g->n_col_chunks ? g->n_row_chunks : g->n_col_chunks)
                                    : (size_t)g->n_row_chunks;
     const bool gat = L->model == DFGNN_GAT, agnn = L->model == DFGNN_AGNN, v2 = L->model == DFGNN_GATV2;
@@ -117,12 +127,12 @@ static int dispatch_forward(int geo, const dfgnn_graph* g, int model, const Args
 }
 
 static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l,
-                             float* d_a_r, float* d_scale, hipStream_t st) {
+                             float* d_a_r, float* d_scale, bool add_to_scale, hipStream_t st) {
     switch (model) {
     case DFGNN_GT: return launch_backward_gt(geo, g, a, st);
     case DFGNN_GAT: return launch_backward_gat(geo, g, a, reduce_tmp, d_a_l, d_a_r, st);
     case DFGNN_GATV2: return launch_backward_gatv2(geo, g, a, reduce_tmp, d_a_l, st);
-    default: return launch_backward_agnn(geo, g, a, reduce_tmp, d_scale, st);
+    default: return launch_backward_agnn(geo, g, a, reduce_tmp, d_scale, add_to_scale, st);
     }
 }
 
@@ -152,16 +162,42 @@ static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, con
     a.n_nodes = (int)g->N;
     a.row_bytes = (uint32_t)(L->H * L->D * (L->dtype == DFGNN_F32 ? 4 : 2));
     a.tensor_bytes = (uint32_t)((uint64_t)g->N * a.row_bytes);
-    a.nh_bytes = (uint32_t)((uint64_t)g->N * L->H * 4u);
-    a.H = L->H;
+    a.nh_bytes = (uint32_t)((uint64_t)g->N * geo.heads * 4u);
+    a.H = geo.heads;
     a.D = L->D;
-    a.HD = L->H * L->D;
+    a.HD = geo.heads * L->D;
+    a.row_stride = L->H * L->D;
+    a.stat_stride = L->H;
+    a.bias_stride = L->H;
     a.lph = geo.lph;
     a.scale = (L->model == DFGNN_GAT || L->model == DFGNN_GATV2) ? 1.f : L->scale;
     a.c_score = a.scale * kLog2e;
     a.neg_slope = L->neg_slope;
     a.eps = L->eps;
     a.inv_eps = L->eps > 0.f ? 1.f / L->eps : 0.f;
+}
+
+// Pointers of head group `gi`: the caller's tensors start at the group's first head; buffer ranges shrink by
+// the same amount so that the hardware range check still ends at the end of the allocation.
+template <typename T> static T* shift(T* p, size_t bytes) { return p ? (T*)((char*)p + bytes) : nullptr; }
+template <typename T> static const T* shift(const T* p, size_t bytes) { return p ? (const T*)((const char*)p + bytes) : nullptr; }
+
+static void select_group(Args& a, const Args& whole, const dfgnn_layer* L, const Geometry& geo, int gi) {
+    a = whole;
+    const size_t elem = L->dtype == DFGNN_F32 ? 4 : 2;
+    const size_t first = (size_t)gi * geo.heads;      // first head of the group
+    const size_t tb = first * L->D * elem;            // byte offset inside a node row
+    const size_t pb = first * L->D * sizeof(float);   // inside an [H, D] fp32 parameter
+    const size_t sb = first * sizeof(float);          // inside an [.., H] fp32 record
+    a.x = shift(whole.x, tb); a.k = shift(whole.k, tb); a.v = shift(whole.v, tb);
+    a.out = shift(whole.out, tb); a.d_out = shift(whole.d_out, tb);
+    a.o = shift(whole.o, tb); a.d_x = shift(whole.d_x, tb); a.d_k = shift(whole.d_k, tb); a.d_v = shift(whole.d_v, tb);
+    a.a_l = shift(whole.a_l, pb); a.a_r = shift(whole.a_r, pb);
+    a.row_max = shift(whole.row_max, sb); a.row_sum = shift(whole.row_sum, sb);
+    a.o_max = shift(whole.o_max, sb); a.o_sum = shift(whole.o_sum, sb);
+    a.bias = shift(whole.bias, sb); a.d_bias = shift(whole.d_bias, sb);
+    a.tensor_bytes = whole.tensor_bytes - (uint32_t)tb;
+    a.bias_bytes = whole.bias_bytes - (uint32_t)sb;
 }
 
 }  // namespace dfgnn
@@ -174,8 +210,8 @@ extern "C" int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
-    if (fwd_bytes) *fwd_bytes = workspace_layout(graph, layer, false).total;
-    if (bwd_bytes) *bwd_bytes = workspace_layout(graph, layer, true).total;
+    if (fwd_bytes) *fwd_bytes = workspace_layout(graph, layer, false, geo.heads).total;
+    if (bwd_bytes) *bwd_bytes = workspace_layout(graph, layer, true, geo.heads).total;
     return DFGNN_OK;
 }
 
@@ -209,7 +245,7 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
         DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;
     }
-    const Workspace W = workspace_layout(graph, layer, false);
+    const Workspace W = workspace_layout(graph, layer, false, geo.heads);
     DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
     DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, forward needs %zu",
@@ -222,8 +258,12 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
     a.bias = edge_bias;
     a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
     bind_workspace(a, W, workspace, false);
-    rc = dispatch_forward(geo.id, graph, layer->model, a, (hipStream_t)stream);
-    if (rc != DFGNN_OK) return rc;
+    for (int gi = 0; gi < geo.groups; ++gi) {
+        Args ag;
+        select_group(ag, a, layer, geo, gi);
+        rc = dispatch_forward(geo.id, graph, layer->model, ag, (hipStream_t)stream);
+        if (rc != DFGNN_OK) return rc;
+    }
     DFGNN_HIP(hipGetLastError());
     return DFGNN_OK;
 }
@@ -291,7 +331,7 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
         DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;
     }
-    const Workspace W = workspace_layout(graph, layer, true);
+    const Workspace W = workspace_layout(graph, layer, true, geo.heads);
     DFGNN_REQUIRE(workspace != nullptr, DFGNN_EINVAL, "workspace is NULL");
     DFGNN_REQUIRE(((uintptr_t)workspace % kAlign) == 0, DFGNN_EUNSUPPORTED, "workspace must be 256-byte aligned");
     DFGNN_REQUIRE(workspace_bytes >= W.total, DFGNN_EWORKSPACE, "workspace has %zu bytes, backward needs %zu",
@@ -316,8 +356,15 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
     bind_workspace(a, W, workspace, true);
     float* reduce_tmp = (float*)((char*)workspace + W.reduce);
-    rc = dispatch_backward(geo.id, graph, layer->model, a, reduce_tmp, d_a_l, d_a_r, d_scale, st);
-    if (rc != DFGNN_OK) return rc;
+    for (int gi = 0; gi < geo.groups; ++gi) {
+        Args ag;
+        select_group(ag, a, layer, geo, gi);
+        const size_t pb = (size_t)gi * geo.heads * layer->D * sizeof(float);
+        // d_scale (AGNN) is one number for all heads: the first group writes it, the others add to it
+        rc = dispatch_backward(geo.id, graph, layer->model, ag, reduce_tmp, shift(d_a_l, pb), shift(d_a_r, pb), d_scale,
+                               gi > 0, st);
+        if (rc != DFGNN_OK) return rc;
+    }
     DFGNN_HIP(hipGetLastError());
     return DFGNN_OK;
 }

@@ -165,8 +165,12 @@ struct Args {
     uint32_t row_bytes;     // bytes of one node row
     uint32_t tensor_bytes;  // bytes of one node tensor (< 4 GiB)
     uint32_t nh_bytes;      // bytes of one [N, H] fp32 array
-    // shape and constants
+    // shape and constants.  H, HD describe the heads this launch works on; when a layer has more features
+    // than one wavefront covers, the host runs it in groups of heads, and the caller's tensors keep the
+    // strides of the whole layer (row_stride, stat_stride, bias_stride: elements between consecutive nodes
+    // or edges), while workspace arrays are compact ([.., HD] or [.., H] of the group).
     int H, D, HD, lph;
+    int row_stride, stat_stride, bias_stride;
     float c_score;  // GT scale*log2(e); AGNN beta*log2(e); GAT log2(e)
     float scale;    // GT scale; AGNN beta
     float neg_slope, eps, inv_eps;
@@ -217,7 +221,8 @@ struct Ctx {
     bool writer;  // this lane stores results: edge slot 0 when the wave shares one row, every live slot otherwise
     uint32_t fbyte;  // byte offset of this lane's features inside a node row
     uint32_t hbyte;  // byte offset of this lane's head inside a [.., H] fp32 record
-    size_t off;   // node*HD + f0
+    size_t off;   // node*row_stride + f0: this lane's features in a caller's node tensor
+    size_t woff;  // node*HD + f0: the same in a compact workspace array
 };
 
 // Where a lane reads chunk partials: lanes without features of their own read feature 0 / head 0, so
@@ -243,7 +248,8 @@ template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int n
     c.h = c.active ? c.f0 / a.D : 0;
     c.head0 = c.active && (c.f0 % a.D) == 0;
     c.node = node;
-    c.off = (size_t)node * a.HD + c.f0;
+    c.off = (size_t)node * a.row_stride + c.f0;
+    c.woff = (size_t)node * a.HD + c.f0;
     c.writer = c.g == 0;
     c.fbyte = (uint32_t)c.f0 * (uint32_t)sizeof(typename G::T);
     c.hbyte = (uint32_t)c.h * 4u;
@@ -275,7 +281,7 @@ __device__ inline f32x4 gather_stats4(const Args& a, const Ctx& c, int i) {
 // the buffer load returns zero; the [E, H] array is kept below 4 GiB)
 template <class G> __device__ inline float load_bias(const Args& a, const Ctx& c, int j, int e) {
     if constexpr (G::kEdgeTerm)
-        return buf_load_f32(make_rsrc(a.bias, a.bias_bytes), j >= 0 ? (uint32_t)e * (uint32_t)(a.H * 4) + c.hbyte : 0xffffffffu);
+        return buf_load_f32(make_rsrc(a.bias, a.bias_bytes), j >= 0 ? (uint32_t)e * (uint32_t)(a.bias_stride * 4) + c.hbyte : 0xffffffffu);
     else return 0.f;
 }
 // score in log2 units plus the edge term (given in natural units)
@@ -288,7 +294,7 @@ template <class G> __device__ inline float with_bias(float s, float b) {
 // tensors), otherwise the column pass does (bf16 tensors, where delta is only known at the end of a row).
 template <class G, bool ROW_PASS> __device__ inline void store_dbias(const Args& a, const Ctx& c, bool valid, int e, float ds) {
     if constexpr (G::kEdgeTerm && ROW_PASS == (sizeof(typename G::T) == 4)) {
-        if (a.d_bias != nullptr && valid && c.head0) a.d_bias[(size_t)e * a.H + c.h] = ds;
+        if (a.d_bias != nullptr && valid && c.head0) a.d_bias[(size_t)e * a.bias_stride + c.h] = ds;
     }
 }
 
@@ -376,8 +382,8 @@ template <class G, int U> struct SoftmaxAcc {
         for (int i = 0; i < VEC; ++i) o[i] = acc[i] * inv;
         Elem<typename G::T>::store(static_cast<typename G::T*>(a.o) + c.off, o);
         if (c.head0) {
-            a.o_max[(size_t)c.node * a.H + c.h] = m * kLn2;
-            a.o_sum[(size_t)c.node * a.H + c.h] = l;
+            a.o_max[(size_t)c.node * a.stat_stride + c.h] = m * kLn2;
+            a.o_sum[(size_t)c.node * a.stat_stride + c.h] = l;
         }
     }
 };
@@ -404,8 +410,8 @@ template <class G> struct RowBackwardBase {
         }
         float mx = 0.f, sm = 1.f;
         if (c.active) {
-            mx = a.row_max[(size_t)c.node * a.H + c.h];
-            sm = a.row_sum[(size_t)c.node * a.H + c.h];
+            mx = a.row_max[(size_t)c.node * a.stat_stride + c.h];
+            sm = a.row_sum[(size_t)c.node * a.stat_stride + c.h];
         }
         lse2 = mx * kLog2e + fast_log2(sm);
     }
@@ -1001,7 +1007,7 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = al2[i] * kLn2 * dx[i];
         Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
-        store_f32<VEC>(a.da_row + c.off, da);
+        store_f32<VEC>(a.da_row + c.woff, da);
         if (c.head0) {
             f32x2 st = {this->lse2, this->delta};
             *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)c.node * a.H + c.h)) = st;
@@ -1229,7 +1235,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = a.scale * ga[i];
-        store_f32<VEC>(a.g_row + c.off, o);
+        store_f32<VEC>(a.g_row + c.woff, o);
         if (c.head0) {
             const size_t nh = (size_t)c.node * a.H + c.h;
             a.dbeta_row[nh] = dbeta;
@@ -1304,7 +1310,7 @@ template <class G, int U> struct AgnnBwdCol {
     __device__ void finalize(const Args& a, const Ctx& c) {
         float gt[VEC];
         if (c.active) {
-            load_f32<VEC>(a.g_row + c.off, gt);
+            load_f32<VEC>(a.g_row + c.woff, gt);
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gt[i] = 0.f;
@@ -1607,9 +1613,10 @@ __device__ inline float block_sum_256(float v) {
     if (threadIdx.x == 0) partial[blockIdx.x] = t;
 }
 
-[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, float* __restrict__ out) {
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, bool add,
+                                                   float* __restrict__ out) {
     const float t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.f);
-    if (threadIdx.x == 0) *out = t;
+    if (threadIdx.x == 0) *out = add ? *out + t : t;
 }
 
 // Column sums of a row-major [n, hd] fp32 array (hd a multiple of 4) in two stages with a fixed summation

@@ -89,6 +89,7 @@ int launch_backward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t
 int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
                         hipStream_t st);
 int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, hipStream_t st);
-int launch_backward_agnn(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_scale, hipStream_t st);
+int launch_backward_agnn(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_scale, bool add_to_scale,
+                         hipStream_t st);
 
 }  // namespace dfgnn

@@ -71,7 +71,7 @@ def test_layer_argument_checks():
     gt = dfgnn.Layer("gt", 1, 64)
     assert status(layer=dfgnn.Layer("gt", 1, 6), x=x, k=x, v=x) == EUNSUPPORTED      # head not a multiple of 16 bytes
     assert status(layer=dfgnn.Layer("gt", 1, 12), x=x, k=x, v=x) == EUNSUPPORTED     # D/4 not a power of two
-    assert status(layer=dfgnn.Layer("gt", 5, 64), x=x, k=x, v=x) == EUNSUPPORTED     # more than 64 lanes per row
+    assert status(layer=dfgnn.Layer("gt", 1, 512), x=x, k=x, v=x) == EUNSUPPORTED    # one head wider than a wavefront
     assert status(layer=dfgnn.Layer("gt", 0, 64), x=x, k=x, v=x) == EINVAL
     assert status(layer=gt, x=x, k=None, v=x) == EINVAL                                # GT needs k
     assert status(layer=gt, x=x, k=x, v=x, a_l=x) == EINVAL                            # a_l only for GAT

@@ -61,6 +61,25 @@ def test_full_row_geometries(model, dtype, H, D):
     g.close()
 
 
+# rows wider than one wavefront of 16-byte lanes: the layer runs in groups of heads
+WIDE_SHAPES = [("f32", 8, 64), ("f32", 3, 128), ("f32", 2, 256), ("f32", 16, 32), ("bf16", 16, 64), ("bf16", 3, 256),
+               ("f32", 5, 64)]
+
+
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
+@pytest.mark.parametrize("dtype,H,D", WIDE_SHAPES)
+def test_rows_wider_than_a_wavefront(model, dtype, H, D):
+    graph = tiny_graph("hub", seed=13, n=60)
+    w = Workload("tiny", 100, model, H, D, dtype, {"gt": float(1.0 / np.sqrt(D)), "agnn": 1.3}.get(model, 1.0))
+    feats = make_features(w, graph.n)
+    if model == "gt":  # with an edge term too: its head offset moves with the group
+        rng = np.random.default_rng(5)
+        feats["edge_bias"] = rng.standard_normal((graph.nnz, H)).astype(np.float32)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
 @pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
 def test_complete_graph(model):
     graph = complete_graph(67)  # every row has 67 neighbours: several unrolled rounds plus a ragged tail
