@@ -166,6 +166,9 @@ def main() -> int:
 
     import torch
     import paper_2411_16127_amd as dfgnn
+    from paper_2411_16127_amd import build as lib_build
+    if not os.path.exists(lib_build.lib_path()):  # load what is built; build only if nothing is
+        lib_build.build()
     from dfgnn_synth import make_workload, make_features
     from dfgnn_synth.workloads import make_graph
 
