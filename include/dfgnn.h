@@ -83,7 +83,9 @@ typedef struct {
                         of two (vec = 4 for fp32, 8 for bf16) and at most 64 (one head fits one wavefront of
                         16-byte lanes: D <= 256 in fp32, 512 in bf16), and one node tensor (N*H*D elements)
                         must stay below 4 GiB.  Rows of more than 64 such lanes (H*D/vec > 64) are processed
-                        in groups of heads, one launch sequence per group. */
+                        in groups of heads, one launch sequence per group.  Other head widths (a classifier
+                        layer with 7 outputs, say) are used zero-padded to the next accepted width: zero
+                        features change no score of any model and aggregate to zero. */
     float scale;     /* GT: factor on q.k (callers pass 1/sqrt(D)); AGNN: beta; GAT, GATv2: ignored */
     float neg_slope; /* GAT, GATv2: LeakyReLU slope (derivative at 0 is neg_slope) */
     float eps;       /* AGNN: lower clamp of the feature norm */

@@ -29,28 +29,48 @@ class _FusedConv(torch.autograd.Function):
         return (None, None, g["d_x"], g.get("d_k"), g.get("d_v"), g.get("d_a_l"), g.get("d_a_r"), g.get("d_edge_bias"))
 
 
+def _kernel_width(D: int, dtype) -> int:
+    """Head width the kernels accept: a power-of-two number of 16-byte lanes."""
+    per_lane = 4 if dtype == torch.float32 else 8
+    lanes = 1
+    while lanes * per_lane < D:
+        lanes *= 2
+    return lanes * per_lane
+
+
+def _pad(t, width: int):
+    """Zero-pads the features of every head to `width`.  Zero features change no score of any of the models
+    (dot products, norms and a.LeakyReLU(0) terms are unaffected) and aggregate to zero, so the wrappers
+    pad odd head widths, call the kernels, and cut the padding off the result; torch differentiates both."""
+    return t if t.shape[-1] == width else torch.nn.functional.pad(t, (0, width - t.shape[-1]))
+
+
 def gt_conv(graph: Graph, q, k, v, scale=None, edge_bias=None):
     """Graph-transformer convolution: softmax over in-neighbours of scale * q_i.k_j (+ edge_bias [E,H], fp32, in
     CSR edge order, if given), applied to v.  [N,H,D]."""
     H, D = q.shape[1], q.shape[2]
-    layer = Layer("gt", H, D, dtype="bf16" if q.dtype == torch.bfloat16 else "f32",
+    W = _kernel_width(D, q.dtype)
+    layer = Layer("gt", H, W, dtype="bf16" if q.dtype == torch.bfloat16 else "f32",
                   scale=float(D) ** -0.5 if scale is None else float(scale))
-    return _FusedConv.apply(graph, layer, q, k, v, None, None, edge_bias)
+    return _FusedConv.apply(graph, layer, _pad(q, W), _pad(k, W), _pad(v, W), None, None, edge_bias)[..., :D]
 
 
 def gat_conv(graph: Graph, wh, a_l, a_r, neg_slope: float = 0.2):
     """GAT convolution on projected features Wh [N,H,D] with attention vectors a_l, a_r [H,D] (fp32)."""
     H, D = wh.shape[1], wh.shape[2]
-    layer = Layer("gat", H, D, dtype="bf16" if wh.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
-    return _FusedConv.apply(graph, layer, wh, None, None, a_l.contiguous(), a_r.contiguous())
+    W = _kernel_width(D, wh.dtype)
+    layer = Layer("gat", H, W, dtype="bf16" if wh.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    return _FusedConv.apply(graph, layer, _pad(wh, W), None, None, _pad(a_l, W).contiguous(),
+                            _pad(a_r, W).contiguous())[..., :D]
 
 
 def gatv2_conv(graph: Graph, x_dst, x_src, a, neg_slope: float = 0.2):
     """GATv2 convolution: scores sum_d a_d LeakyReLU(x_dst_i,d + x_src_j,d), applied to x_src.  x_dst, x_src:
     the two projections of the node features [N,H,D]; a [H,D] (fp32)."""
     H, D = x_dst.shape[1], x_dst.shape[2]
-    layer = Layer("gatv2", H, D, dtype="bf16" if x_dst.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
-    return _FusedConv.apply(graph, layer, x_dst, x_src, None, a.contiguous(), None)
+    W = _kernel_width(D, x_dst.dtype)
+    layer = Layer("gatv2", H, W, dtype="bf16" if x_dst.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    return _FusedConv.apply(graph, layer, _pad(x_dst, W), _pad(x_src, W), None, _pad(a, W).contiguous(), None)[..., :D]
 
 
 class _AgnnConv(torch.autograd.Function):
@@ -75,4 +95,5 @@ class _AgnnConv(torch.autograd.Function):
 
 def agnn_conv(graph: Graph, h, beta, eps: float = 1e-12):
     """AGNN convolution: softmax of beta * cos(h_i, h_j), applied to h.  beta: 0-d or 1-element tensor."""
-    return _AgnnConv.apply(graph, h, beta, eps)
+    D = h.shape[2]
+    return _AgnnConv.apply(graph, _pad(h, _kernel_width(D, h.dtype)), beta, eps)[..., :D]
