@@ -4,9 +4,10 @@
  * The library computes, for a graph stored as CSR by destination, the three fused steps of an
  * attention-GNN layer (Eq. 1, Sec. 2.1):  S = SDDMM(Q, K, A)  ->  P = Softmax(S) over each node's
  * neighbourhood (Appendix A)  ->  O = SpMM(P, V),  and the backward pass of Appendix B, for the three
- * models of Sec. 5.1: GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features).
+ * models of Sec. 5.1: GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features),
+ * and for GATv2 (the other member of the GAT family cited in Sec. 1).
  * Per-edge scores and attention weights live only in registers; nothing of size O(edges) is written
- * to memory by the layer calls.
+ * to memory by the layer calls (except the gradient of an edge term, when the caller asks for one).
  *
  * General rules
  *  - Every pointer named d_* or documented as "device" is GPU global memory owned by the caller; the
@@ -170,8 +171,8 @@ int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, in
 
 /*
  * Bytes of device workspace one forward / one backward call needs for this graph and layer (partial
- * results of super-row chunks, per-node score terms, statistics handed from the row pass to the
- * column pass, reduction staging).  Either output pointer may be NULL.  Errors: EINVAL, EUNSUPPORTED.
+ * results of super-row chunks, statistics and per-node terms handed from the row pass to the column
+ * pass, reduction staging).  Either output pointer may be NULL.  Errors: EINVAL, EUNSUPPORTED.
  */
 int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer* layer, size_t* fwd_bytes, size_t* bwd_bytes);
 
@@ -212,10 +213,11 @@ int dfgnn_backward(const dfgnn_graph* graph, const dfgnn_layer* layer, const voi
  * The same two calls with an additive per-edge term in the score (edge features entering the attention
  * score, Sec. 1): s_ij = (model score) + edge_bias[t, h] for the edge stored at CSR position t, before the
  * edge softmax of Appendix A.  edge_bias: [E, H] fp32 device, caller-owned, in the order of d_indices;
- * NULL = no edge term (then the calls are dfgnn_forward / dfgnn_backward); E*H*4 bytes must stay below 4 GiB.  d_edge_bias: [E, H] fp32
- * device, receives dL/d edge_bias = dS of every edge (Appendix B's dL/dS before it is multiplied into Q
- * and K); may be NULL when the term is not trained.  Works for every model; batches of small graphs use the
- * general kernels when an edge term is given (the dense-tile kernels have none).  Same errors as above.
+ * NULL = no edge term (then the calls are dfgnn_forward / dfgnn_backward); E*H*4 bytes must stay below
+ * 4 GiB.  d_edge_bias: [E, H] fp32 device, receives dL/d edge_bias = dS of every edge (Appendix B's dL/dS
+ * before it is multiplied into Q and K); may be NULL when the term is not trained.  Works for every
+ * model; batches of small graphs use the general kernels when an edge term is given (the dense-tile
+ * kernels have none).  Same errors as above.
  */
 int dfgnn_forward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
                             const void* v, const float* a_l, const float* a_r, const float* edge_bias, void* out,
