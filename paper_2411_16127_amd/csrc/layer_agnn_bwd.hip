@@ -1,5 +1,6 @@
 // AGNN backward kernels (Appendix B with the derivative of the L2 normalisation) and the reduction of dbeta.
 #include "layer_launch.hpp"
+#include "pass_agnn.hpp"
 
 namespace dfgnn {
 

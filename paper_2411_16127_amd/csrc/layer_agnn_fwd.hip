@@ -1,5 +1,6 @@
 // AGNN forward kernels (cosine score of Sec. 5.1).
 #include "layer_launch.hpp"
+#include "pass_agnn.hpp"
 
 namespace dfgnn {
 

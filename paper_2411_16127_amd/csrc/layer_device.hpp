@@ -9,6 +9,10 @@
 //   * a head's dot product is reduced over its LPH lanes with DPP cross-lane moves; the softmax is kept
 //     online per edge slot (max / sum / accumulator in registers), so no score or attention weight is
 //     ever stored (Sec. 4.2 "Softmax": no duplicated work, no recomputation inside a pass).
+// This file holds what all models share (element types, buffer loads, reductions, the online softmax,
+// the kernels that drive a pass); the passes of a model are in pass_gt.hpp, pass_gat.hpp,
+// pass_gatv2.hpp and pass_agnn.hpp.  A pass is a struct with init / issue / consume / combine_slots /
+// store_partial / load_partial / fold_partial / finalize; k_pass and k_merge are templates over it.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -417,234 +421,9 @@ template <class G> struct RowBackwardBase {
     }
 };
 
-// =============================================================================================
-// GT (dot-SDDMM, Sec. 5.1): s_ij = scale q_i.k_j
-// =============================================================================================
-template <class G, int U> struct GtFwd {
-    static constexpr int VEC = G::VEC;
-    float q[VEC], B[U];
-    SoftmaxAcc<G, U> sm;
-    u32x4 K[U], V[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, q);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) q[i] *= a.c_score;
-        sm.reset();
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        K[u] = gather_raw<G>(a.k, a, c, j);
-        V[u] = gather_raw<G>(a.v, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[VEC];
-            Elem<typename G::T>::unpack(K[u], kf);
-            s[u] = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph), B[u]);
-            if (!FULL && j[u] < 0) s[u] = -INFINITY;
-        }
-        if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
-    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
-};
-
-// Forward pass of the two-kernel comparator (Sec. 3, parallelism maximization fusion): the scores were
-// written by k_edge_scores; this pass reads them back and does the softmax and the aggregation.
-template <class G, int U> struct GtFwdStored {
-    static constexpr int VEC = G::VEC;
-    SoftmaxAcc<G, U> sm;
-    float S[U];
-    u32x4 V[U];
-    __device__ void init(const Args&, const Ctx&) { sm.reset(); }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        S[u] = j >= 0 ? a.scores[(size_t)e * a.H + c.h] : -INFINITY;
-        V[u] = gather_raw<G>(a.v, a, c, j);
-    }
-    template <bool FULL> __device__ void consume(const Args&, const Ctx&, const int (&j)[U]) {
-        if (!FULL && j[0] < 0) return;
-        sm.update(S, V);
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
-    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
-};
-
-// dQ_i = scale sum_j dS_ij k_j with dS_ij = p_ij (dO_i.v_j - delta_i)   (Appendix B; fused chain of Sec. 4.3)
-template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
-    static constexpr int VEC = G::VEC;
-    static constexpr bool kExact = RowBackwardBase<G>::kExact;
-    float q[VEC], dq[VEC], pk[VEC];  // pk = sum_j p k_j (kExact only)
-    float B[U];
-    int Ep[U];
-    u32x4 K[U], V[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, q);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { q[i] *= a.c_score; dq[i] = 0.f; pk[i] = 0.f; }
-        this->init_row(a, c);
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        K[u] = gather_raw<G>(a.k, a, c, j);
-        V[u] = gather_raw<G>(a.v, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[VEC], vf[VEC];
-            Elem<typename G::T>::unpack(K[u], kf);
-            Elem<typename G::T>::unpack(V[u], vf);
-            const float s = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(q, kf), a.lph), B[u]);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
-            if constexpr (kExact) {
-                const float t = p * dp;
-                this->dsum += t;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) { dq[i] = fmaf(t, kf[i], dq[i]); pk[i] = fmaf(p, kf[i], pk[i]); }
-            } else {
-                const float ds = p * (dp - this->delta);
-                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) dq[i] = fmaf(ds, kf[i], dq[i]);
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dq[i] = slot_sum<G::LPE>(dq[i]);
-        if constexpr (kExact) {
-            this->dsum = slot_sum<G::LPE>(this->dsum);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) pk[i] = slot_sum<G::LPE>(pk[i]);
-        }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dq);
-        if constexpr (kExact) {
-            store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, pk);
-            if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
-        }
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        if constexpr (kExact) {
-            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
-            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
-        }
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dq[i] = fmaf(w, P.v0[i], dq[i]);
-        if constexpr (kExact) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) pk[i] = fmaf(w, P.v1[i], pk[i]);
-            this->dsum = fmaf(w, P.s2, this->dsum);
-        }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        if constexpr (kExact) {
-            this->delta = this->dsum;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) dq[i] -= this->delta * pk[i];
-        }
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = a.scale * dq[i];
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
-        if (c.head0) {
-            f32x2 st = {this->lse2, this->delta};
-            *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)c.node * a.H + c.h)) = st;
-        }
-    }
-};
-
-// Column pass over the CSC (transposed products of Appendix B): for source j and every edge i <- j,
-// dV_j += p_ij dO_i,  dK_j += scale dS_ij q_i, with p and dS recomputed from the row statistics.
-template <class G, int U> struct GtBwdCol {
-    static constexpr int VEC = G::VEC;
-    float k2[VEC], vv[VEC], dk[VEC], dv[VEC];
-    float B[U];
-    int Ep[U];
-    u32x4 Q[U], Gd[U];
-    f32x2 St[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.k, c, k2);
-        load_row<G>(a.v, c, vv);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { k2[i] *= a.c_score; dk[i] = 0.f; dv[i] = 0.f; }
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
-        Q[u] = gather_raw<G>(a.x, a, c, i);
-        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        St[u] = gather_stats2(a, c, i);
-        B[u] = load_bias<G>(a, c, i, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float qf[VEC], gf[VEC];
-            Elem<typename G::T>::unpack(Q[u], qf);
-            Elem<typename G::T>::unpack(Gd[u], gf);
-            const float s = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(qf, k2), a.lph), B[u]);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, vv), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
-            const float ds = p * (dp - St[u][1]);
-            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                dv[i] = fmaf(p, gf[i], dv[i]);
-                dk[i] = fmaf(ds, qf[i], dk[i]);
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dv[i] = slot_sum<G::LPE>(dv[i]); }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
-        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dv);
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(w, P.v0[i], dk[i]); dv[i] = fmaf(w, P.v1[i], dv[i]); }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = a.scale * dk[i];
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_k) + c.off, o);
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_v) + c.off, dv);
-    }
-};
-
-// =============================================================================================
-// GAT (add-SDDMM, Sec. 5.1): s_ij = LeakyReLU(el_i + er_j); el, er are per-node scalars per head
-// =============================================================================================
+// ---------------------------------------------------------------------------------------------
+// helpers shared by the GAT-family passes
+// ---------------------------------------------------------------------------------------------
 __device__ inline float leaky(float z, float slope) { return z > 0.f ? z : slope * z; }
 
 // this lane's slice of a [H, D] fp32 attention vector, times mul (zeros for lanes without features)
@@ -657,676 +436,6 @@ template <class G> __device__ inline void load_attention(const float* v, const C
         for (int i = 0; i < G::VEC; ++i) out[i] *= mul;
     }
 }
-
-template <class G, int U> struct GatFwd {
-    static constexpr int VEC = G::VEC;
-    float el2, ar2[VEC];  // el_i * log2e; this lane's slice of a_r * log2e
-    float B[U];
-    SoftmaxAcc<G, U> sm;
-    u32x4 V[U];
-    // el_i comes from the row's own features and er_j from the gathered neighbour row (one dot product
-    // over the head's lanes), so no per-node scalar has to be gathered from memory
-    __device__ void init(const Args& a, const Ctx& c) {
-        float x[VEC], al[VEC];
-        load_row<G>(a.x, c, x);
-        load_attention<G>(a.a_l, c, kLog2e, al);
-        load_attention<G>(a.a_r, c, kLog2e, ar2);
-        el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
-        sm.reset();
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[VEC];
-            Elem<typename G::T>::unpack(V[u], vf);
-            s[u] = with_bias<G>(leaky(el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph), a.neg_slope), B[u]);
-            if (!FULL && j[u] < 0) s[u] = -INFINITY;
-        }
-        if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
-    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
-};
-
-// d_el_i = sum_j dS_ij LeakyReLU'(z_ij)
-template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
-    static constexpr int VEC = G::VEC;
-    static constexpr bool kExact = RowBackwardBase<G>::kExact;
-    float el2, ar2[VEC], d_el, pl;  // pl = sum_j p LeakyReLU'(z) (kExact only)
-    float B[U];
-    int Ep[U];
-    u32x4 V[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        float x[VEC], al[VEC];
-        load_row<G>(a.x, c, x);
-        load_attention<G>(a.a_l, c, kLog2e, al);
-        load_attention<G>(a.a_r, c, kLog2e, ar2);
-        el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
-        d_el = 0.f;
-        pl = 0.f;
-        this->init_row(a, c);
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[VEC];
-            Elem<typename G::T>::unpack(V[u], vf);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float z = el2 + head_sum<G::LPH>(dotv<VEC>(vf, ar2), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(leaky(z, a.neg_slope), B[u]) - this->lse2) : 0.f;
-            const float slope = z > 0.f ? 1.f : a.neg_slope;
-            if constexpr (kExact) {
-                const float t = p * dp;
-                this->dsum += t;
-                d_el = fmaf(t, slope, d_el);
-                pl = fmaf(p, slope, pl);
-            } else {
-                const float ds = p * (dp - this->delta);
-                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-                d_el = fmaf(ds, slope, d_el);
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-        d_el = slot_sum<G::LPE>(d_el);
-        if constexpr (kExact) {
-            pl = slot_sum<G::LPE>(pl);
-            this->dsum = slot_sum<G::LPE>(this->dsum);
-        }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.head0) return;
-        a.part_s0[(size_t)item * a.H + c.h] = d_el;
-        if constexpr (kExact) {
-            a.part_s1[(size_t)item * a.H + c.h] = pl;
-            a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
-        }
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
-        if constexpr (kExact) {
-            P.s1 = a.part_s1[(size_t)chunk * a.H + c.h];
-            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
-        }
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-        d_el = fmaf(w, P.s0, d_el);
-        if constexpr (kExact) {
-            pl = fmaf(w, P.s1, pl);
-            this->dsum = fmaf(w, P.s2, this->dsum);
-        }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.head0) return;
-        if constexpr (kExact) {
-            this->delta = this->dsum;
-            d_el -= this->delta * pl;
-        }
-        const size_t nh = (size_t)c.node * a.H + c.h;
-        a.d_el[nh] = d_el;
-        f32x4 st = {el2, this->lse2, this->delta, 0.f};
-        *reinterpret_cast<f32x4*>(a.stats + 4 * nh) = st;
-    }
-};
-
-// dWh_j = sum_i p_ij dO_i + d_el_j a_l + d_er_j a_r ;  d_er_j = sum_i dS_ij LeakyReLU'(z_ij)
-template <class G, int U> struct GatBwdCol {
-    static constexpr int VEC = G::VEC;
-    float wh[VEC], dwh[VEC];
-    float er2, d_er;
-    float B[U];
-    int Ep[U];
-    u32x4 Gd[U];
-    f32x4 St[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, wh);
-        float ar[VEC];
-        load_attention<G>(a.a_r, c, kLog2e, ar);
-        er2 = head_sum<G::LPH>(dotv<VEC>(wh, ar), a.lph);
-        d_er = 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dwh[i] = 0.f;
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
-        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        St[u] = gather_stats4(a, c, i);
-        B[u] = load_bias<G>(a, c, i, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float gf[VEC];
-            Elem<typename G::T>::unpack(Gd[u], gf);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, wh), a.lph);
-            const float z = St[u][0] + er2;
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(leaky(z, a.neg_slope), B[u]) - St[u][1]) : 0.f;
-            const float ds = p * (dp - St[u][2]);
-            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-            d_er += ds * (z > 0.f ? 1.f : a.neg_slope);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) dwh[i] = fmaf(p, gf[i], dwh[i]);
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-        d_er = slot_sum<G::LPE>(d_er);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dwh[i] = slot_sum<G::LPE>(dwh[i]);
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dwh);
-        if (c.head0) a.part_s0[(size_t)item * a.H + c.h] = d_er;
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dwh[i] = fmaf(w, P.v0[i], dwh[i]);
-        d_er = fmaf(w, P.s0, d_er);
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        const size_t nh = (size_t)c.node * a.H + c.h;
-        const float del = a.d_el[nh];
-        float al[VEC], ar[VEC], o[VEC];
-        load_f32<VEC>(a.a_l + c.f0, al);
-        load_f32<VEC>(a.a_r + c.f0, ar);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = dwh[i] + del * al[i] + d_er * ar[i];
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
-        if (c.head0) a.d_er[nh] = d_er;
-    }
-};
-
-// =============================================================================================
-// GATv2 (the second member of the GAT family cited in Sec. 1): s_ij = sum_d a_d LeakyReLU(x_i,d + k_j,d),
-// x = destination-side and k = source-side projection; the aggregated value is k_j.  The score is not a
-// sum of two per-node scalars, so every edge costs a D-wide elementwise pass over the gathered row; the
-// memory traffic is that of GAT (one neighbour row per edge).
-// =============================================================================================
-template <class G, int U> struct GatV2Fwd {
-    static constexpr int VEC = G::VEC;
-    float x[VEC], al2[VEC];  // destination features; this lane's slice of a * log2e
-    float B[U];
-    SoftmaxAcc<G, U> sm;
-    u32x4 K[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, x);
-        load_attention<G>(a.a_l, c, kLog2e, al2);
-        sm.reset();
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        K[u] = gather_raw<G>(a.k, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[VEC], t = 0.f;
-            Elem<typename G::T>::unpack(K[u], kf);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) t = fmaf(al2[i], leaky(x[i] + kf[i], a.neg_slope), t);
-            s[u] = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
-            if (!FULL && j[u] < 0) s[u] = -INFINITY;
-        }
-        if (!FULL && j[0] < 0) return;
-        sm.update(s, K);
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
-    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
-};
-
-// Row side: with z_d = x_i,d + k_j,d,  dX_i,d = a_d sum_j dS_ij LeakyReLU'(z_d)  and the row's share of
-// da_d = sum_ij dS_ij LeakyReLU(z_d)  (summed over rows afterwards).  The factor a_d is applied once at the end.
-template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
-    static constexpr int VEC = G::VEC;
-    static constexpr bool kExact = RowBackwardBase<G>::kExact;
-    static constexpr int kMergeBatch = kExact ? 2 : 4;  // four partial vectors per chunk: keep the merge in registers
-    float x[VEC], al2[VEC], dx[VEC], da[VEC];
-    float px[VEC], pa[VEC];  // sum_j p LeakyReLU'(z), sum_j p LeakyReLU(z)  (kExact only)
-    float B[U];
-    int Ep[U];
-    u32x4 K[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, x);
-        load_attention<G>(a.a_l, c, kLog2e, al2);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dx[i] = 0.f; da[i] = 0.f; px[i] = 0.f; pa[i] = 0.f; }
-        this->init_row(a, c);
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        K[u] = gather_raw<G>(a.k, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[VEC], lr[VEC], sl[VEC], t = 0.f;
-            Elem<typename G::T>::unpack(K[u], kf);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                const float z = x[i] + kf[i];
-                sl[i] = z > 0.f ? 1.f : a.neg_slope;
-                lr[i] = z * sl[i];
-                t = fmaf(al2[i], lr[i], t);
-            }
-            const float s = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, kf), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
-            if constexpr (kExact) {
-                const float w = p * dp;
-                this->dsum += w;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    dx[i] = fmaf(w, sl[i], dx[i]); da[i] = fmaf(w, lr[i], da[i]);
-                    px[i] = fmaf(p, sl[i], px[i]); pa[i] = fmaf(p, lr[i], pa[i]);
-                }
-            } else {
-                const float ds = p * (dp - this->delta);
-                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) { dx[i] = fmaf(ds, sl[i], dx[i]); da[i] = fmaf(ds, lr[i], da[i]); }
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dx[i] = slot_sum<G::LPE>(dx[i]); da[i] = slot_sum<G::LPE>(da[i]); }
-        if constexpr (kExact) {
-            this->dsum = slot_sum<G::LPE>(this->dsum);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) { px[i] = slot_sum<G::LPE>(px[i]); pa[i] = slot_sum<G::LPE>(pa[i]); }
-        }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        const size_t o = (size_t)item * a.HD + c.f0;
-        store_f32<VEC>(a.part_v0 + o, dx);
-        store_f32<VEC>(a.part_v1 + o, da);
-        if constexpr (kExact) {
-            store_f32<VEC>(a.part_v2 + o, px);
-            store_f32<VEC>(a.part_v3 + o, pa);
-            if (c.head0) a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
-        }
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        const size_t o = (size_t)chunk * a.HD + c.f0;
-        load_f32<VEC>(a.part_v0 + o, P.v0);
-        load_f32<VEC>(a.part_v1 + o, P.v1);
-        if constexpr (kExact) {
-            load_f32<VEC>(a.part_v2 + o, P.v2);
-            load_f32<VEC>(a.part_v3 + o, P.v3);
-            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
-        }
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dx[i] = fmaf(w, P.v0[i], dx[i]); da[i] = fmaf(w, P.v1[i], da[i]); }
-        if constexpr (kExact) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) { px[i] = fmaf(w, P.v2[i], px[i]); pa[i] = fmaf(w, P.v3[i], pa[i]); }
-            this->dsum = fmaf(w, P.s2, this->dsum);
-        }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        if constexpr (kExact) {
-            this->delta = this->dsum;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) { dx[i] -= this->delta * px[i]; da[i] -= this->delta * pa[i]; }
-        }
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = al2[i] * kLn2 * dx[i];
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
-        store_f32<VEC>(a.da_row + c.woff, da);
-        if (c.head0) {
-            f32x2 st = {this->lse2, this->delta};
-            *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)c.node * a.H + c.h)) = st;
-        }
-    }
-};
-
-// Column side: dK_j = sum_i p_ij dO_i + a (.) sum_i dS_ij LeakyReLU'(z_ij), p and dS recomputed per edge
-template <class G, int U> struct GatV2BwdCol {
-    static constexpr int VEC = G::VEC;
-    float kk[VEC], al2[VEC], dk[VEC], dz[VEC];
-    float B[U];
-    int Ep[U];
-    u32x4 X[U], Gd[U];
-    f32x2 St[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.k, c, kk);
-        load_attention<G>(a.a_l, c, kLog2e, al2);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] = 0.f; dz[i] = 0.f; }
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
-        X[u] = gather_raw<G>(a.x, a, c, i);
-        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        St[u] = gather_stats2(a, c, i);
-        B[u] = load_bias<G>(a, c, i, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float xf[VEC], gf[VEC], sl[VEC], t = 0.f;
-            Elem<typename G::T>::unpack(X[u], xf);
-            Elem<typename G::T>::unpack(Gd[u], gf);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                const float z = xf[i] + kk[i];
-                sl[i] = z > 0.f ? 1.f : a.neg_slope;
-                t = fmaf(al2[i], z * sl[i], t);
-            }
-            const float s = with_bias<G>(head_sum<G::LPH>(t, a.lph), B[u]);
-            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, kk), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(s - St[u][0]) : 0.f;
-            const float ds = p * (dp - St[u][1]);
-            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(p, gf[i], dk[i]); dz[i] = fmaf(ds, sl[i], dz[i]); }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dz[i] = slot_sum<G::LPE>(dz[i]); }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, dk);
-        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, dz);
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { dk[i] = fmaf(w, P.v0[i], dk[i]); dz[i] = fmaf(w, P.v1[i], dz[i]); }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = fmaf(al2[i] * kLn2, dz[i], dk[i]);
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_k) + c.off, o);
-    }
-};
-
-// =============================================================================================
-// AGNN (Sec. 5.1): s_ij = beta * cos(h_i, h_j); aggregated value is the raw feature row
-// =============================================================================================
-// 1 / max(|h|, eps) from the squared norm.  The norm of a neighbour is taken from its gathered row
-// (one more dot product over the head's lanes) instead of being gathered as a 4-byte scalar, which
-// would cost a whole memory sector per edge.
-__device__ inline float inv_norm(float n2, float inv_eps) { return fminf(__builtin_amdgcn_rsqf(n2), inv_eps); }
-
-template <class G, int U> struct AgnnFwd {
-    static constexpr int VEC = G::VEC;
-    float x2[VEC], B[U];
-    SoftmaxAcc<G, U> sm;
-    u32x4 V[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, x2);
-        const float rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(x2, x2), a.lph), a.inv_eps);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
-        sm.reset();
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[VEC];
-            Elem<typename G::T>::unpack(V[u], vf);
-            const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
-            s[u] = with_bias<G>(head_sum<G::LPH>(dotv<VEC>(x2, vf), a.lph) * rnj, B[u]);
-            if (!FULL && j[u] < 0) s[u] = -INFINITY;
-        }
-        if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
-    __device__ void load_partial(const Args& a, const Ctx& c, int chunk, PartialRegs<VEC>& P) const { sm.load_partial(a, c, chunk, P); }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
-    __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
-};
-
-// row side: g_i = beta sum_j dS_ij xhat_j ;  dbeta_i = sum_j dS_ij cos_ij
-template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
-    static constexpr int VEC = G::VEC;
-    static constexpr bool kExact = RowBackwardBase<G>::kExact;
-    float xh[VEC], ga[VEC], px[VEC];  // px = sum_j p xhat_j (kExact only)
-    float rn, dbeta, pc;              // pc = sum_j p cos_ij (kExact only)
-    float B[U];
-    int Ep[U];
-    u32x4 V[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, xh);
-        rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(xh, xh), a.lph), a.inv_eps);
-        dbeta = 0.f;
-        pc = 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { xh[i] *= rn; ga[i] = 0.f; px[i] = 0.f; }
-        this->init_row(a, c);
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
-        V[u] = gather_raw<G>(a.x, a, c, j);
-        B[u] = load_bias<G>(a, c, j, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[VEC];
-            Elem<typename G::T>::unpack(V[u], vf);
-            const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
-            const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * rnj;
-            const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - this->lse2) : 0.f;
-            if constexpr (kExact) {
-                const float t = p * dp;
-                this->dsum += t;
-                dbeta = fmaf(t, cs, dbeta);
-                pc = fmaf(p, cs, pc);
-                const float w1 = t * rnj, w2 = p * rnj;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) { ga[i] = fmaf(w1, vf[i], ga[i]); px[i] = fmaf(w2, vf[i], px[i]); }
-            } else {
-                const float ds = p * (dp - this->delta);
-                store_dbias<G, true>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-                dbeta = fmaf(ds, cs, dbeta);
-                const float w = ds * rnj;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, vf[i], ga[i]);
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-        dbeta = slot_sum<G::LPE>(dbeta);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) ga[i] = slot_sum<G::LPE>(ga[i]);
-        if constexpr (kExact) {
-            pc = slot_sum<G::LPE>(pc);
-            this->dsum = slot_sum<G::LPE>(this->dsum);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) px[i] = slot_sum<G::LPE>(px[i]);
-        }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, ga);
-        if constexpr (kExact) store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, px);
-        if (c.head0) {
-            a.part_s0[(size_t)item * a.H + c.h] = dbeta;
-            if constexpr (kExact) {
-                a.part_s1[(size_t)item * a.H + c.h] = pc;
-                a.part_s2[(size_t)item * a.H + c.h] = this->dsum;
-            }
-        }
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        P.s0 = a.part_s0[(size_t)chunk * a.H + c.h];
-        if constexpr (kExact) {
-            load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
-            P.s1 = a.part_s1[(size_t)chunk * a.H + c.h];
-            P.s2 = a.part_s2[(size_t)chunk * a.H + c.h];
-        }
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) ga[i] = fmaf(w, P.v0[i], ga[i]);
-        dbeta = fmaf(w, P.s0, dbeta);
-        if constexpr (kExact) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) px[i] = fmaf(w, P.v1[i], px[i]);
-            pc = fmaf(w, P.s1, pc);
-            this->dsum = fmaf(w, P.s2, this->dsum);
-        }
-    }
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        if (!c.writer || !c.active) return;
-        if constexpr (kExact) {
-            this->delta = this->dsum;
-            dbeta -= this->delta * pc;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) ga[i] -= this->delta * px[i];
-        }
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = a.scale * ga[i];
-        store_f32<VEC>(a.g_row + c.woff, o);
-        if (c.head0) {
-            const size_t nh = (size_t)c.node * a.H + c.h;
-            a.dbeta_row[nh] = dbeta;
-            f32x4 st = {rn, this->lse2, this->delta, 0.f};
-            *reinterpret_cast<f32x4*>(a.stats + 4 * nh) = st;
-        }
-    }
-};
-
-// column side: value term sum_i p_ij dO_i, key term beta sum_i dS_ij xhat_i, then the derivative of the
-// normalisation x -> x / max(|x|, eps) applied to the summed row+column gradient of xhat_j
-template <class G, int U> struct AgnnBwdCol {
-    static constexpr int VEC = G::VEC;
-    float hj[VEC], xh[VEC], val[VEC], ga[VEC];
-    float rn;
-    float B[U];
-    int Ep[U];
-    u32x4 Xi[U], Gd[U];
-    f32x4 St[U];
-    __device__ void init(const Args& a, const Ctx& c) {
-        load_row<G>(a.x, c, hj);
-        rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph), a.inv_eps);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
-    }
-    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int e) {
-        Xi[u] = gather_raw<G>(a.x, a, c, i);
-        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
-        St[u] = gather_stats4(a, c, i);
-        B[u] = load_bias<G>(a, c, i, e);
-        Ep[u] = e;
-    }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float xf[VEC], gf[VEC];
-            Elem<typename G::T>::unpack(Xi[u], xf);
-            Elem<typename G::T>::unpack(Gd[u], gf);
-            const float cs = head_sum<G::LPH>(dotv<VEC>(xf, xh), a.lph) * St[u][0];
-            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, hj), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - St[u][1]) : 0.f;
-            const float ds = p * (dp - St[u][2]);
-            store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
-            const float w = ds * St[u][0];
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                val[i] = fmaf(p, gf[i], val[i]);
-                ga[i] = fmaf(w, xf[i], ga[i]);
-            }
-        }
-    }
-    __device__ void combine_slots(const Args&, const Ctx&) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { val[i] = slot_sum<G::LPE>(val[i]); ga[i] = slot_sum<G::LPE>(ga[i]); }
-    }
-    __device__ void store_partial(const Args& a, const Ctx& c, int item) {
-        if (!c.writer || !c.active) return;
-        store_f32<VEC>(a.part_v0 + (size_t)item * a.HD + c.f0, val);
-        store_f32<VEC>(a.part_v1 + (size_t)item * a.HD + c.f0, ga);
-    }
-    __device__ void load_partial(const Args& a, const Ctx& c0, int chunk, PartialRegs<VEC>& P) const {
-        const PartialIndex c(c0);
-        load_f32<VEC>(a.part_v0 + (size_t)chunk * a.HD + c.f0, P.v0);
-        load_f32<VEC>(a.part_v1 + (size_t)chunk * a.HD + c.f0, P.v1);
-    }
-    __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) {
-        const float w = valid ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) { val[i] = fmaf(w, P.v0[i], val[i]); ga[i] = fmaf(w, P.v1[i], ga[i]); }
-    }
-    // all lanes of the wave must call this (it reduces over the head's lanes)
-    __device__ void finalize(const Args& a, const Ctx& c) {
-        float gt[VEC];
-        if (c.active) {
-            load_f32<VEC>(a.g_row + c.woff, gt);
-        } else {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) gt[i] = 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) gt[i] = fmaf(a.scale, ga[i], gt[i]);
-        const float proj = head_sum<G::LPH>(dotv<VEC>(gt, xh), a.lph);
-        const float nrm2 = head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph);
-        const bool clamped = !(sqrtf(nrm2) > a.eps);
-        if (!c.writer || !c.active) return;
-        float o[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = (clamped ? gt[i] * rn : rn * (gt[i] - proj * xh[i])) + val[i];
-        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_x) + c.off, o);
-    }
-};
 
 // =============================================================================================
 // kernels

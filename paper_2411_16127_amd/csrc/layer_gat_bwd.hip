@@ -1,5 +1,6 @@
 // GAT backward kernels (Appendix B with the chain rule through LeakyReLU) and the reduction of da_l, da_r.
 #include "layer_launch.hpp"
+#include "pass_gat.hpp"
 
 namespace dfgnn {
 

@@ -1,5 +1,6 @@
 // GAT forward kernels (add-SDDMM score of Sec. 5.1).
 #include "layer_launch.hpp"
+#include "pass_gat.hpp"
 
 namespace dfgnn {
 

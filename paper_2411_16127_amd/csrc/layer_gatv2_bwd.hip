@@ -1,5 +1,6 @@
 // GATv2 backward kernels and the column sum that finishes the gradient of the attention vector.
 #include "layer_launch.hpp"
+#include "pass_gatv2.hpp"
 
 namespace dfgnn {
 

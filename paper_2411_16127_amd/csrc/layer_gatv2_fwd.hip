@@ -1,5 +1,6 @@
 // GATv2 forward kernels (the second member of the GAT family cited in Sec. 1).
 #include "layer_launch.hpp"
+#include "pass_gatv2.hpp"
 
 namespace dfgnn {
 

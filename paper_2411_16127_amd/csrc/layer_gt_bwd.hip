@@ -1,5 +1,6 @@
 // GT backward kernels (Appendix B: row pass over the CSR, column pass over the CSC).
 #include "layer_launch.hpp"
+#include "pass_gt.hpp"
 
 namespace dfgnn {
 

@@ -1,5 +1,6 @@
 // GT forward kernels (Eq. 1 with the dot-product score of Sec. 5.1) and the two-kernel comparator of Sec. 3.
 #include "layer_launch.hpp"
+#include "pass_gt.hpp"
 
 namespace dfgnn {
 
