@@ -172,3 +172,52 @@ def test_cfg5_full_size_sampled():
     compare_all(res, ref, w, rows=sample, keys=["out", "row_max", "row_sum", "d_x"])
     compare_all(res, ref, w, rows=light, keys=["d_k", "d_v"])
     g.close()
+
+
+def test_node_tensors_just_below_4_gib():
+    """Gathers address node rows with 32-bit byte offsets: a graph whose tensors end 300 KB below 4 GiB,
+    checked on rows and columns at both ends of the node range.  Tensors are drawn on the GPU; the oracle
+    gets the compact sub-problem of the sampled rows (whole neighbourhoods) and of every row that feeds a
+    sampled column."""
+    import torch
+    from dfgnn_synth import from_edge_list
+    N, H, D = 8388000, 8, 16  # N * 512 bytes = 2^32 - 311,296
+    rng = np.random.default_rng(21)
+    src = rng.integers(0, N, size=(N, 2), dtype=np.int64)
+    src[-4:, 0] = np.array([N - 1, 0, N - 2, 1])  # the last rows read the first and the last rows
+    src[:4, 1] = np.array([N - 1, N - 2, N - 3, N - 4])
+    indptr = np.arange(0, 2 * N + 1, 2, dtype=np.int32)
+    indices = src.reshape(-1).astype(np.int32)
+    g = dfgnn.Graph(indptr, indices)
+    L = dfgnn.Layer("gt", H, D, scale=0.25)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    q, k, v, d_out = (torch.randn((N, H, D), device="cuda", generator=gen) for _ in range(4))
+    out, rmax, rsum = g.forward(L, q, k, v)
+    grads = g.backward(L, q, k, v, None, None, out, rmax, rsum, d_out)
+    torch.cuda.synchronize()
+
+    rows = np.unique(np.concatenate([np.arange(4), np.arange(N - 4, N), rng.integers(0, N, 24)]))
+    cols = np.array([0, 1, N - 2, N - 1, int(src[12345, 0])])
+    edge_rows = np.repeat(np.arange(N, dtype=np.int64), 2)
+    feed = np.unique(edge_rows[np.isin(indices, cols)])
+    need = np.union1d(rows, feed)  # rows whose neighbourhoods the oracle evaluates
+    nb = src[need].reshape(-1)
+    nodes, inv = np.unique(np.concatenate([need, cols, nb]), return_inverse=True)
+    new_rows = inv[:need.size]
+    new_nb = inv[need.size + cols.size:]
+    sub = from_edge_list(nodes.size, new_nb, np.repeat(new_rows, 2), sort=False)
+    pick = torch.from_numpy(nodes).cuda()
+    f64 = lambda t: t[pick].cpu().numpy().astype(np.float64)
+    import oracle
+    OL = oracle.Layer("gt", H, D, scale=0.25)
+    kw = dict(x=f64(q), k=f64(k), v=f64(v))
+    fw = oracle.forward(OL, sub.indptr, sub.indices, **kw)
+    bw = oracle.backward(OL, sub.indptr, sub.indices, d_out=f64(d_out), **kw)
+    from gpu_harness import assert_close
+    at = lambda ids: np.searchsorted(nodes, ids)
+    assert_close("out", f64(out)[at(rows)], fw["out"][at(rows)], "f32")
+    assert_close("row_sum", rsum[pick].cpu().numpy()[at(rows)], fw["row_sum"][at(rows)], "f32")
+    assert_close("d_x", f64(grads["d_x"])[at(rows)], bw["d_x"][at(rows)], "f32")
+    assert_close("d_k", f64(grads["d_k"])[at(cols)], bw["d_k"][at(cols)], "f32")
+    assert_close("d_v", f64(grads["d_v"])[at(cols)], bw["d_v"][at(cols)], "f32")
+    g.close()
