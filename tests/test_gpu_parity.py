@@ -221,3 +221,49 @@ def test_node_tensors_just_below_4_gib():
     assert_close("d_k", f64(grads["d_k"])[at(cols)], bw["d_k"][at(cols)], "f32")
     assert_close("d_v", f64(grads["d_v"])[at(cols)], bw["d_v"][at(cols)], "f32")
     g.close()
+
+
+def test_edge_count_just_below_the_int32_limit():
+    """2.14 billion edges (99.7 % of the documented maximum of 2^31 - 2^20): every row is a super row, so the
+    scheduler, the CSC transpose, the chunk pass and the merge all run at the largest index values.  The
+    graph is drawn on the GPU; the oracle evaluates sampled rows and every row that feeds a sampled column."""
+    import torch
+    import oracle
+    from gpu_harness import assert_close
+    N, deg, H, D = 1000000, 2140, 1, 4
+    E = N * deg
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    indices = torch.randint(0, N, (E,), dtype=torch.int32, device="cuda", generator=gen)
+    indptr = torch.arange(0, E + 1, deg, dtype=torch.int64, device="cuda").to(torch.int32)
+    g = dfgnn.Graph(indptr, indices)
+    assert g.query("n_super_rows") == N
+    L = dfgnn.Layer("gt", H, D, scale=0.5)
+    q, k, v, d_out = (torch.randn((N, H, D), device="cuda", generator=gen) for _ in range(4))
+    out, rmax, rsum = g.forward(L, q, k, v)
+    grads = g.backward(L, q, k, v, None, None, out, rmax, rsum, d_out)
+    torch.cuda.synchronize()
+
+    rows = np.array([0, 1, 499999, N - 2, N - 1])
+    cols = np.array([int(indices[0]), int(indices[E - 1])])  # sources of the first and of the last edge
+    feed = []
+    quarter = N // 4 * deg  # positions are searched in four slices to stay far below 2^31 elements per call
+    for j in cols:
+        for part in range(4):
+            pos = (indices[part * quarter:(part + 1) * quarter] == int(j)).nonzero().flatten() + part * quarter
+            feed.append(torch.div(pos, deg, rounding_mode="floor").unique().cpu().numpy())
+    need = np.unique(np.concatenate([rows] + feed))
+    lists = indices.view(N, deg)[torch.from_numpy(need).cuda()].cpu().numpy()  # whole neighbourhoods of those rows
+    sub_ptr = np.zeros(N + 1, dtype=np.int64)
+    sub_ptr[need + 1] = deg
+    sub_ptr = np.cumsum(sub_ptr)
+    f64 = lambda t: t.cpu().numpy().astype(np.float64)
+    OL = oracle.Layer("gt", H, D, scale=0.5)
+    kw = dict(x=f64(q), k=f64(k), v=f64(v))
+    fw = oracle.forward(OL, sub_ptr, lists.reshape(-1), **kw)
+    bw = oracle.backward(OL, sub_ptr, lists.reshape(-1), d_out=f64(d_out), **kw)
+    assert_close("out", f64(out)[rows], fw["out"][rows], "f32")
+    assert_close("row_sum", f64(rsum)[rows], fw["row_sum"][rows], "f32")
+    assert_close("d_x", f64(grads["d_x"])[rows], bw["d_x"][rows], "f32")
+    assert_close("d_k", f64(grads["d_k"])[cols], bw["d_k"][cols], "f32")
+    assert_close("d_v", f64(grads["d_v"])[cols], bw["d_v"][cols], "f32")
+    g.close()
