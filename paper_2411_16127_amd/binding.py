@@ -274,6 +274,29 @@ class Graph:
             graph_set_batch(self.handle, self.batch_ptr, n_graphs, self.batch_meta, nbytes, stream)
         self._ws: Dict[tuple, object] = {}
 
+    @classmethod
+    def from_edge_index(cls, src, dst, num_nodes: int, sched: Optional[SchedParams] = None, device="cuda:0",
+                        stream=None):
+        """Graph from an unsorted edge list (edge e goes from src[e] to dst[e]; any integer dtype, host or
+        device).  Edges are grouped by destination with a stable sort, so the sources of a row keep their
+        order in the list.  Returns (graph, perm): perm[t] is the list position of the edge stored at CSR
+        position t, i.e. per-edge data in list order becomes CSR order by `data[perm]` (edge terms), and CSR
+        order goes back with `out[perm] = data_csr`."""
+        import torch
+        dev = torch.device(device)
+        src = torch.as_tensor(src).to(dev).flatten().long()
+        dst = torch.as_tensor(dst).to(dev).flatten().long()
+        if src.numel() != dst.numel():
+            raise ValueError("src and dst differ in length")
+        if src.numel() and (int(src.min()) < 0 or int(dst.min()) < 0 or int(src.max()) >= num_nodes
+                            or int(dst.max()) >= num_nodes):
+            raise ValueError("edge endpoint out of range")
+        order = torch.sort(dst, stable=True).indices
+        counts = torch.bincount(dst, minlength=num_nodes)
+        indptr = torch.zeros(num_nodes + 1, dtype=torch.int64, device=dev)
+        indptr[1:] = torch.cumsum(counts, 0)
+        return cls(indptr.to(torch.int32), src[order].to(torch.int32), sched, device, stream), order
+
     def close(self) -> None:
         if getattr(self, "handle", None) is not None:
             graph_destroy(self.handle)

@@ -57,3 +57,20 @@ def test_tiny_graphs(kind, T, C):
 def test_workload_graphs(name, shrink, T, C):
     # spans many sort tiles (4096 keys) with a ragged tail and several radix passes
     check_metadata(make_graph(make_workload(name, shrink=shrink)), T, C)
+
+
+def test_graph_from_an_unsorted_edge_list():
+    """from_edge_index groups edges by destination (stable) and returns the permutation to CSR order."""
+    import torch
+    from dfgnn_synth import from_edge_list
+    rng = np.random.default_rng(6)
+    n, e = 300, 2500
+    src, dst = rng.integers(0, n, e), rng.integers(0, n, e)
+    g, perm = dfgnn.Graph.from_edge_index(torch.from_numpy(src), torch.from_numpy(dst), n)
+    ref = from_edge_list(n, src, dst, sort=False)
+    assert np.array_equal(g.indptr.cpu().numpy(), ref.indptr) and np.array_equal(g.indices.cpu().numpy(), ref.indices)
+    p = perm.cpu().numpy()
+    assert np.array_equal(src[p], ref.indices) and np.array_equal(dst[p], ref.rows_of_edges())
+    with pytest.raises(ValueError):
+        dfgnn.Graph.from_edge_index(torch.tensor([0, n]), torch.tensor([1, 2]), n)
+    g.close()
