@@ -136,6 +136,14 @@ static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Arg
     }
 }
 
+__global__ void k_zero(float* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+static void launch_zero(float* p, int n, hipStream_t st) {
+    hipLaunchKernelGGL(k_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+}
+
 // the edge term is read with 32-bit byte offsets
 static bool edge_term_fits(const dfgnn_graph* g, const dfgnn_layer* L) {
     return (int64_t)g->E * L->H * 4 < ((int64_t)1 << 32) - 4096;
@@ -295,12 +303,11 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN,
                v2 = layer->model == DFGNN_GATV2;
     if (graph->N == 0) {  // no nodes: node tensors have no elements and may be NULL; parameter gradients are zero
-        if (gat && d_a_l && d_a_r) {
-            DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
-            DFGNN_HIP(hipMemsetAsync(d_a_r, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
-        }
-        if (v2 && d_a_l) DFGNN_HIP(hipMemsetAsync(d_a_l, 0, sizeof(float) * layer->H * layer->D, (hipStream_t)stream));
-        if (agnn && d_scale) DFGNN_HIP(hipMemsetAsync(d_scale, 0, sizeof(float), (hipStream_t)stream));
+        // cleared by a kernel, not a memset: layer calls may be recorded into a HIP graph
+        if ((gat || v2) && d_a_l) launch_zero(d_a_l, layer->H * layer->D, (hipStream_t)stream);
+        if (gat && d_a_r) launch_zero(d_a_r, layer->H * layer->D, (hipStream_t)stream);
+        if (agnn && d_scale) launch_zero(d_scale, 1, (hipStream_t)stream);
+        DFGNN_HIP(hipGetLastError());
         return DFGNN_OK;
     }
     DFGNN_REQUIRE(x && out && row_max && row_sum && d_out && d_x, DFGNN_EINVAL,
