@@ -90,7 +90,7 @@ def test_layer_argument_checks():
     g.close()
 
 
-@pytest.mark.parametrize("model", ["gt", "gat", "agnn"])
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
 def test_graph_without_edges_and_empty_graph(model):
     import torch
     H, D = 2, 8
@@ -98,8 +98,9 @@ def test_graph_without_edges_and_empty_graph(model):
     for n in (0, 9):
         g = dfgnn.Graph(np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32))
         x = torch.randn(n, H, D, device="cuda")
-        kv = (x.clone(), x.clone()) if model == "gt" else (None, None)
-        att = (torch.randn(H, D, device="cuda"), torch.randn(H, D, device="cuda")) if model == "gat" else (None, None)
+        kv = (x.clone(), x.clone()) if model == "gt" else ((x.clone(), None) if model == "gatv2" else (None, None))
+        att = (torch.randn(H, D, device="cuda"), torch.randn(H, D, device="cuda")) if model == "gat" else (
+            (torch.randn(H, D, device="cuda"), None) if model == "gatv2" else (None, None))
         out, rmax, rsum = g.forward(L, x, kv[0], kv[1], att[0], att[1])
         grads = g.backward(L, x, kv[0], kv[1], att[0], att[1], out, rmax, rsum, torch.randn_like(x))
         torch.cuda.synchronize()
