@@ -50,7 +50,7 @@ typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
  * edge-parallel treatment of super nodes (Sec. 3, Sec. 4.2 "SDDMM") is taken per row here: a row with
  * at least super_threshold neighbours is cut into chunks of chunk_edges edges whose partial softmax
  * statistics are merged in a second pass.  0 selects the library default for either field:
- * chunk_edges = E / 16384 rounded up to a power of two and clamped to [64, 512] (E = edges of the
+ * chunk_edges = E / 16384 rounded up to a power of two and clamped to [128, 512] (E = edges of the
  * graph), super_threshold = 2 * chunk_edges.  The values in use can be read with dfgnn_graph_query.
  */
 typedef struct {

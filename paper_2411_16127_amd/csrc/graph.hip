@@ -368,12 +368,13 @@ static ScratchLayout scratch_layout(int64_t N, int64_t E, int T) {
     return L;
 }
 
-// Defaults grow with the graph: a chunk should be long enough to amortise its start-up (>= 64 edges)
-// and short enough that the chunks of the super rows alone can fill the GPU (256 CUs x 4 SIMDs x
-// several wavefronts): chunk_edges = E / 16384 rounded up to a power of two, clamped to [64, 512];
-// super_threshold = 2 * chunk_edges.
+// Defaults grow with the graph: a chunk should be long enough to amortise its start-up and short enough
+// that the chunks of the super rows alone can fill the GPU (256 CUs x 4 SIMDs x several wavefronts):
+// chunk_edges = E / 16384 rounded up to a power of two, clamped to [128, 512]; super_threshold =
+// 2 * chunk_edges.  Below 256 edges a row is not worth splitting: one wavefront walks it in a few
+// microseconds, about what the merge launch costs that the first super row of a graph brings with it.
 static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, int* C, int* flags = nullptr) {
-    int c = 64;
+    int c = 128;
     while (c < 512 && (int64_t)c * 16384 < E) c <<= 1;
     *C = c;
     *T = 0;

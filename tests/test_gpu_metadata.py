@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 def default_params(E):
     """Defaults documented in include/dfgnn.h."""
-    c = 64
+    c = 128
     while c < 512 and c * 16384 < E:
         c *= 2
     return 2 * c, c
