@@ -684,20 +684,28 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
     }
 }
 
-[[maybe_unused]] static __global__ __launch_bounds__(256) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
-                                                         float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
-    // thread t: feature t % HD of (a_l | a_r); partials are loaded 16 at a time, then added in order
-    for (int t = threadIdx.x; t < 2 * HD; t += blockDim.x) {
-        const int which = t / HD, f = t % HD;
-        float sum = 0.f;
-        for (int b = 0; b < nblocks; b += 16) {
+// second stage: 1024 threads; thread t owns column t % wf of the 2 * HD columns (a_l | a_r) and every
+// (1024 / wf)-th partial row, the groups are then added in order through LDS (wf = a power of two >= 2 * HD)
+[[maybe_unused]] static __global__ __launch_bounds__(1024) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
+                                                          int wf, float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
+    __shared__ float red[1024];
+    const int groups = 1024 / wf, bs = threadIdx.x / wf, t = threadIdx.x % wf;
+    float sum = 0.f;
+    if (t < 2 * HD) {
+        for (int b = bs; b < nblocks; b += 16 * groups) {
             float v[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) v[k] = b + k < nblocks ? partial[((size_t)(b + k) * 2 + which) * HD + f] : 0.f;
+            for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * 2 * HD + t] : 0.f;
 #pragma unroll
             for (int k = 0; k < 16; ++k) sum += v[k];
         }
-        (which ? d_a_r : d_a_l)[f] = sum;
+    }
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    if (bs == 0 && t < 2 * HD) {
+        float total = 0.f;
+        for (int k = 0; k < groups; ++k) total += red[k * wf + t];
+        (t < HD ? d_a_l : d_a_r)[t < HD ? t : t - HD] = total;
     }
 }
 

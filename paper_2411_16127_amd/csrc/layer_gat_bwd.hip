@@ -10,7 +10,9 @@ static void run(const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d
     run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
     KernelTimer t("param_reduce", st);
     hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
-    hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(256), 0, st, reduce_tmp, kReduceBlocks, a.HD, d_a_l, d_a_r);
+    int wf = 8;  // columns of the second stage: a power of two >= 2 * HD (HD <= 512)
+    while (wf < 2 * a.HD) wf <<= 1;
+    hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(1024), 0, st, reduce_tmp, kReduceBlocks, a.HD, wf, d_a_l, d_a_r);
 }
 
 int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
