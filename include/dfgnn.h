@@ -68,7 +68,7 @@ typedef struct {
 #define DFGNN_SCHED_NO_DENSE_BATCH 2
 /* Use the dense-tile kernels whenever they apply, also below the tile fill from which they pay. */
 #define DFGNN_SCHED_FORCE_DENSE_BATCH 4
-/* Comparator for the fusion study (Sec. 3, "parallelism maximization fusion"; ablation of Sec. 5.5):
+/* Comparator for the fusion study (Sec. 3, "parallelism maximization fusion"; ablation of Appendix C):
  * the GT forward pass runs as two kernels, an edge-parallel SDDMM over a COO row array that writes the
  * E x H fp32 scores to the workspace, and a softmax + SpMM kernel that reads them back.  Costs one more
  * int32 per edge of graph metadata and E*H*4 bytes of forward workspace; results are the same up to

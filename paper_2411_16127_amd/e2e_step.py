@@ -1,6 +1,6 @@
 """End-to-end training step of a small attention-GNN model on a synthetic workload graph: torch Linear
 projections, ReLU and the optimiser around the fused graph convolutions of this library (the shape of the
-paper's end-to-end comparison, Sec. 5.4: forward + backward + update of a few layers on one graph).
+paper's end-to-end comparison, Sec. 5.3: forward + backward + update of a few layers on one graph).
 
     python -m paper_2411_16127_amd.e2e_step --workload cfg3 --model gat --layers 2 --steps 20
 
