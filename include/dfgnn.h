@@ -229,6 +229,19 @@ int dfgnn_backward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer,
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Attention weights (the normalised scores P = Softmax(S) of Eq. 1, which the fused layer never writes):
+ * p[t, h] = exp(s_ij - row_max[i, h]) / row_sum[i, h] for the edge i <- j stored at CSR position t, from
+ * the inputs and the statistics of a finished dfgnn_forward (or dfgnn_forward_edge_bias; pass the same
+ * edge_bias, or NULL) call.  p: [E, H] fp32 device, caller-owned, every entry is overwritten.  Tensor
+ * arguments as in dfgnn_forward for the model (v is not needed).  Needs no workspace.  One gather pass
+ * over the CSR; meant for inspection and for losses on the attention itself, not for the layer's own
+ * backward pass.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ */
+int dfgnn_attention_weights(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                            const float* a_l, const float* a_r, const float* edge_bias, const float* row_max,
+                            const float* row_sum, float* p, void* stream);
+
+/*
  * Optional per-kernel timing for benchmarks (the measurement protocol of Sec. 5.2 reports kernel time).
  * dfgnn_timing_enable(1) makes every later layer call record a pair of HIP events around each kernel
  * it launches, on the stream of that call; dfgnn_timing_enable(0) stops it.  Either call discards

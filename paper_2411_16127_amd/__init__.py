@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     backward,
     forward_edge_bias,
     backward_edge_bias,
+    attention_weights,
     timing_enable,
     timing_collect,
     QUERY,

@@ -96,13 +96,14 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
         L.dfgnn_backward.argtypes = [vp, vp] + [vp] * 15 + [vp, sz, vp]
         L.dfgnn_forward_edge_bias.argtypes = [vp, vp] + [vp] * 9 + [vp, sz, vp]
+        L.dfgnn_attention_weights.argtypes = [vp, vp] + [vp] * 8 + [vp]
         L.dfgnn_backward_edge_bias.argtypes = [vp, vp] + [vp] * 17 + [vp, sz, vp]
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
         for name in ("dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward",
-                     "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias"):
+                     "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias", "dfgnn_attention_weights"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -231,6 +232,13 @@ def backward_edge_bias(handle, layer: Layer, x, k, v, a_l, a_r, edge_bias, out, 
                                           _ptr(d_x), _ptr(d_k), _ptr(d_v), _ptr(d_a_l), _ptr(d_a_r), _ptr(d_scale),
                                           _ptr(d_edge_bias), _ptr(workspace), workspace_bytes_, _stream(stream)),
            "dfgnn_backward_edge_bias")
+
+
+def attention_weights(handle, layer: Layer, x, k, a_l, a_r, edge_bias, row_max, row_sum, p, stream=None) -> None:
+    cl = layer._c()
+    _check(lib().dfgnn_attention_weights(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(a_l), _ptr(a_r),
+                                         _ptr(edge_bias), _ptr(row_max), _ptr(row_sum), _ptr(p), _stream(stream)),
+           "dfgnn_attention_weights")
 
 
 def timing_enable(enable: bool) -> None:
@@ -367,6 +375,15 @@ class Graph:
             forward_edge_bias(self.handle, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, ws, ws.numel(),
                               stream)
         return out, row_max, row_sum
+
+    def attention(self, layer: Layer, x, k, a_l, a_r, row_max, row_sum, stream=None, edge_bias=None):
+        """Attention weights [E, H] (fp32, CSR edge order) from the statistics of a forward call."""
+        import torch
+        self._check_tensors(layer, (x, k), (a_l, a_r), (row_max, row_sum))
+        self._check_edge_tensor(layer, edge_bias)
+        p = torch.empty((self.E, layer.H), dtype=torch.float32, device=self.device)
+        attention_weights(self.handle, layer, x, k, a_l, a_r, edge_bias, row_max, row_sum, p, stream)
+        return p
 
     def backward(self, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, stream=None, edge_bias=None,
                  want_d_edge_bias: bool = True):

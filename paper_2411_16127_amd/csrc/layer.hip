@@ -126,6 +126,15 @@ static int dispatch_forward(int geo, const dfgnn_graph* g, int model, const Args
     }
 }
 
+static int dispatch_attention(int geo, const dfgnn_graph* g, int model, const Args& a, hipStream_t st) {
+    switch (model) {
+    case DFGNN_GT: return launch_attention_gt(geo, g, a, st);
+    case DFGNN_GAT: return launch_attention_gat(geo, g, a, st);
+    case DFGNN_GATV2: return launch_attention_gatv2(geo, g, a, st);
+    default: return launch_attention_agnn(geo, g, a, st);
+    }
+}
+
 static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l,
                              float* d_a_r, float* d_scale, bool add_to_scale, hipStream_t st) {
     switch (model) {
@@ -203,7 +212,7 @@ static void select_group(Args& a, const Args& whole, const dfgnn_layer* L, const
     a.a_l = shift(whole.a_l, pb); a.a_r = shift(whole.a_r, pb);
     a.row_max = shift(whole.row_max, sb); a.row_sum = shift(whole.row_sum, sb);
     a.o_max = shift(whole.o_max, sb); a.o_sum = shift(whole.o_sum, sb);
-    a.bias = shift(whole.bias, sb); a.d_bias = shift(whole.d_bias, sb);
+    a.bias = shift(whole.bias, sb); a.d_bias = shift(whole.d_bias, sb); a.p_out = shift(whole.p_out, sb);
     a.tensor_bytes = whole.tensor_bytes - (uint32_t)tb;
     a.bias_bytes = whole.bias_bytes - (uint32_t)sb;
 }
@@ -270,6 +279,42 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
         Args ag;
         select_group(ag, a, layer, geo, gi);
         rc = dispatch_forward(geo.id, graph, layer->model, ag, (hipStream_t)stream);
+        if (rc != DFGNN_OK) return rc;
+    }
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+extern "C" int dfgnn_attention_weights(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                                       const float* a_l, const float* a_r, const float* edge_bias,
+                                       const float* row_max, const float* row_sum, float* p, void* stream) {
+    clear_error();
+    Geometry geo;
+    int rc = check_layer(graph, layer, &geo);
+    if (rc != DFGNN_OK) return rc;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2;
+    if (graph->N == 0 || graph->E == 0) return DFGNN_OK;  // no edge, nothing to write
+    DFGNN_REQUIRE(x && row_max && row_sum && p, DFGNN_EINVAL, "x / row_max / row_sum / p is NULL");
+    DFGNN_REQUIRE((gt || v2) == (k != nullptr), DFGNN_EINVAL, "k is needed by GT and GATv2 and by no other model");
+    DFGNN_REQUIRE((gat || v2) == (a_l != nullptr) && gat == (a_r != nullptr), DFGNN_EINVAL,
+                  "GAT needs a_l and a_r, GATv2 a_l, the other models neither");
+    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(a_l) && aligned16(a_r), DFGNN_EUNSUPPORTED,
+                  "device pointers must be 16-byte aligned");
+    DFGNN_REQUIRE((((uintptr_t)edge_bias | (uintptr_t)p) & 3u) == 0, DFGNN_EUNSUPPORTED, "edge_bias / p must be 4-byte aligned");
+    DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
+                  "edge term of E*H*4 bytes must stay below 4 GiB");
+    Args a{};
+    fill_common(a, graph, layer, geo);
+    a.x = x; a.k = k; a.v = k;  // no value tensor is read; GT's value gathers are dropped by the compiler
+    a.a_l = a_l; a.a_r = a_r;
+    a.row_max = row_max; a.row_sum = row_sum;
+    a.bias = edge_bias;
+    a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
+    a.p_out = p;
+    for (int gi = 0; gi < geo.groups; ++gi) {
+        Args ag;
+        select_group(ag, a, layer, geo, gi);
+        rc = dispatch_attention(geo.id, graph, layer->model, ag, (hipStream_t)stream);
         if (rc != DFGNN_OK) return rc;
     }
     DFGNN_HIP(hipGetLastError());

@@ -203,6 +203,7 @@ struct Args {
     uint32_t bias_bytes;  // E * H * 4 (< 4 GiB)
     float* d_bias;   // its gradient dS (may be null)
     const int* eid;  // column pass only, when there is an edge term: CSR position of every CSC entry
+    float* p_out;    // attention-weight output [E, bias_stride] (dfgnn_attention_weights)
     // scores-through-memory comparator
     float* scores;        // [E, H] scaled scores in log2 units
     const int* edge_row;  // [E] destination row of every CSR position
@@ -316,6 +317,12 @@ template <class G, int U> struct SoftmaxAcc {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
     }
+    // the interface a forward pass drives (see also AttentionOut below)
+    __device__ void init(const Args&, const Ctx&) { reset(); }
+    __device__ void absorb(const Args&, const Ctx&, const float (&s)[U], const u32x4 (&val)[U], const int (&)[U],
+                           const int (&)[U]) {
+        update(s, val);
+    }
     // s[u] = -inf for slots without an edge (their value registers hold zeros); s[0] must be finite
     __device__ void update(const float (&s)[U], const u32x4 (&val)[U]) {
         float mn = m;
@@ -390,6 +397,34 @@ template <class G, int U> struct SoftmaxAcc {
             a.o_sum[(size_t)c.node * a.stat_stride + c.h] = l;
         }
     }
+};
+
+// Drop-in for SoftmaxAcc that turns a forward pass into "write the attention weights": with the row
+// statistics of a finished forward call, p_ij = exp(s_ij - max_i) / sum_i is stored for every edge at its
+// CSR position (the normalised scores P of Eq. 1, which the fused layer itself never materialises).
+// Nothing is accumulated, so there is nothing to combine, merge or finalise.
+template <class G, int U> struct AttentionOut {
+    static constexpr int VEC = G::VEC;
+    float lse2;
+    __device__ void init(const Args& a, const Ctx& c) {
+        float mx = 0.f, sm = 1.f;
+        if (c.active) {
+            mx = a.row_max[(size_t)c.node * a.stat_stride + c.h];
+            sm = a.row_sum[(size_t)c.node * a.stat_stride + c.h];
+        }
+        lse2 = mx * kLog2e + fast_log2(sm);
+    }
+    __device__ void absorb(const Args& a, const Ctx& c, const float (&s)[U], const u32x4 (&)[U], const int (&ep)[U],
+                           const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (j[u] >= 0 && c.head0) a.p_out[(size_t)ep[u] * a.bias_stride + c.h] = fast_exp2(s[u] - lse2);
+    }
+    __device__ void combine_slots() {}
+    __device__ void store_partial(const Args&, const Ctx&, int) const {}
+    __device__ void load_partial(const Args&, const Ctx&, int, PartialRegs<VEC>&) const {}
+    __device__ void fold_partial(const PartialRegs<VEC>&, bool) {}
+    __device__ void finalize(const Args&, const Ctx&) const {}
 };
 
 // Row-side quantities every backward row pass starts from: lse2 = log2 of the softmax denominator

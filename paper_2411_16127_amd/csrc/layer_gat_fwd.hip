@@ -14,4 +14,15 @@ int launch_forward_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream_t
     return DFGNN_OK;
 }
 
+// chunks of super rows write their own edges, so there is nothing to merge
+int launch_attention_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st) {
+    switch (geo) {
+#define X(ID, T, LPE, LPH) case ID: run_pass<Geo<T, LPE, LPH>, GatAttention>(g, false, a, kAttentionLabels, st, false); break;
+        DFGNN_GEOMETRIES(X)
+#undef X
+    default: DFGNN_REQUIRE(false, DFGNN_EUNSUPPORTED, "no kernel for geometry %d", geo);
+    }
+    return DFGNN_OK;
+}
+
 }  // namespace dfgnn

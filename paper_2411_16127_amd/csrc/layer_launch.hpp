@@ -31,7 +31,8 @@ static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kW
 
 // chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
 template <class G, template <class, int> class PassT>
-static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st) {
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st,
+                     bool merge = true) {
     a.ptr = columns ? g->t_indptr : g->indptr;
     a.idx = columns ? g->t_indices : g->indices;
     a.order = columns ? g->col_order : g->row_order;
@@ -67,7 +68,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
         if (a.bias) hipLaunchKernelGGL((k_pass<with_edge_term<G>, PassT, kUnroll>), dim3(total), block, 0, st, a);
         else hipLaunchKernelGGL((k_pass<G, PassT, kUnroll>), dim3(total), block, 0, st, a);
     }
-    if (n_super > 0) {
+    if (n_super > 0 && merge) {
         a.n_items = n_super;
         KernelTimer t(labels[1], st);
         hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
@@ -76,6 +77,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
 
 [[maybe_unused]] static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};
 [[maybe_unused]] static const char* const kStoredLabels[2] = {"fwd_softmax_spmm", "fwd_softmax_spmm_merge"};
+[[maybe_unused]] static const char* const kAttentionLabels[2] = {"attention_weights", "attention_weights"};
 [[maybe_unused]] static const char* const kRowLabels[2] = {"bwd_row", "bwd_row_merge"};
 [[maybe_unused]] static const char* const kColLabels[2] = {"bwd_col", "bwd_col_merge"};
 
@@ -85,6 +87,11 @@ int launch_forward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t 
 int launch_forward_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_forward_gatv2(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_forward_agnn(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+// attention weights of every edge from the statistics of a finished forward call (a.p_out)
+int launch_attention_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_attention_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_attention_gatv2(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
+int launch_attention_agnn(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_backward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
                         hipStream_t st);

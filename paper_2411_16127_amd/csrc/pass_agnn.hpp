@@ -12,23 +12,25 @@ namespace dfgnn {
 // would cost a whole memory sector per edge.
 __device__ inline float inv_norm(float n2, float inv_eps) { return fminf(__builtin_amdgcn_rsqf(n2), inv_eps); }
 
-template <class G, int U> struct AgnnFwd {
+template <class G, int U, class Acc> struct AgnnFwdT {
     static constexpr int VEC = G::VEC;
     float x2[VEC], B[U];
-    SoftmaxAcc<G, U> sm;
+    Acc sm;  // SoftmaxAcc: the layer itself; AttentionOut: write the attention weights instead
+    int Ep[U];
     u32x4 V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, x2);
         const float rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(x2, x2), a.lph), a.inv_eps);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
-        sm.reset();
+        sm.init(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         V[u] = gather_raw<G>(a.x, a, c, j);
         B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -39,7 +41,7 @@ template <class G, int U> struct AgnnFwd {
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
+        sm.absorb(a, c, s, V, Ep, j);
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
@@ -47,6 +49,9 @@ template <class G, int U> struct AgnnFwd {
     __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
+template <class G, int U> using AgnnFwd = AgnnFwdT<G, U, SoftmaxAcc<G, U>>;
+template <class G, int U> using AgnnAttention = AgnnFwdT<G, U, AttentionOut<G, U>>;
+
 
 // row side: g_i = beta sum_j dS_ij xhat_j ;  dbeta_i = sum_j dS_ij cos_ij
 template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {

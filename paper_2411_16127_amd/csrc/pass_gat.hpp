@@ -7,11 +7,12 @@ namespace dfgnn {
 // =============================================================================================
 // GAT (add-SDDMM, Sec. 5.1): s_ij = LeakyReLU(el_i + er_j); el, er are per-node scalars per head
 // =============================================================================================
-template <class G, int U> struct GatFwd {
+template <class G, int U, class Acc> struct GatFwdT {
     static constexpr int VEC = G::VEC;
     float el2, ar2[VEC];  // el_i * log2e; this lane's slice of a_r * log2e
     float B[U];
-    SoftmaxAcc<G, U> sm;
+    Acc sm;  // SoftmaxAcc: the layer itself; AttentionOut: write the attention weights instead
+    int Ep[U];
     u32x4 V[U];
     // el_i comes from the row's own features and er_j from the gathered neighbour row (one dot product
     // over the head's lanes), so no per-node scalar has to be gathered from memory
@@ -21,13 +22,14 @@ template <class G, int U> struct GatFwd {
         load_attention<G>(a.a_l, c, kLog2e, al);
         load_attention<G>(a.a_r, c, kLog2e, ar2);
         el2 = head_sum<G::LPH>(dotv<VEC>(x, al), a.lph);
-        sm.reset();
+        sm.init(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         V[u] = gather_raw<G>(a.x, a, c, j);
         B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -37,7 +39,7 @@ template <class G, int U> struct GatFwd {
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
+        sm.absorb(a, c, s, V, Ep, j);
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
@@ -45,6 +47,9 @@ template <class G, int U> struct GatFwd {
     __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
+template <class G, int U> using GatFwd = GatFwdT<G, U, SoftmaxAcc<G, U>>;
+template <class G, int U> using GatAttention = GatFwdT<G, U, AttentionOut<G, U>>;
+
 
 // d_el_i = sum_j dS_ij LeakyReLU'(z_ij)
 template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {

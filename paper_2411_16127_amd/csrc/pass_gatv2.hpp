@@ -10,22 +10,24 @@ namespace dfgnn {
 // sum of two per-node scalars, so every edge costs a D-wide elementwise pass over the gathered row; the
 // memory traffic is that of GAT (one neighbour row per edge).
 // =============================================================================================
-template <class G, int U> struct GatV2Fwd {
+template <class G, int U, class Acc> struct GatV2FwdT {
     static constexpr int VEC = G::VEC;
     float x[VEC], al2[VEC];  // destination features; this lane's slice of a * log2e
     float B[U];
-    SoftmaxAcc<G, U> sm;
+    Acc sm;  // SoftmaxAcc: the layer itself; AttentionOut: write the attention weights instead
+    int Ep[U];
     u32x4 K[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, x);
         load_attention<G>(a.a_l, c, kLog2e, al2);
-        sm.reset();
+        sm.init(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -37,7 +39,7 @@ template <class G, int U> struct GatV2Fwd {
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
-        sm.update(s, K);
+        sm.absorb(a, c, s, K, Ep, j);
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
@@ -45,6 +47,9 @@ template <class G, int U> struct GatV2Fwd {
     __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
+template <class G, int U> using GatV2Fwd = GatV2FwdT<G, U, SoftmaxAcc<G, U>>;
+template <class G, int U> using GatV2Attention = GatV2FwdT<G, U, AttentionOut<G, U>>;
+
 
 // Row side: with z_d = x_i,d + k_j,d,  dX_i,d = a_d sum_j dS_ij LeakyReLU'(z_d)  and the row's share of
 // da_d = sum_ij dS_ij LeakyReLU(z_d)  (summed over rows afterwards).  The factor a_d is applied once at the end.

@@ -7,23 +7,25 @@ namespace dfgnn {
 // =============================================================================================
 // GT (dot-SDDMM, Sec. 5.1): s_ij = scale q_i.k_j
 // =============================================================================================
-template <class G, int U> struct GtFwd {
+template <class G, int U, class Acc> struct GtFwdT {
     static constexpr int VEC = G::VEC;
     float q[VEC], B[U];
-    SoftmaxAcc<G, U> sm;
+    Acc sm;  // SoftmaxAcc: the layer itself; AttentionOut: write the attention weights instead
+    int Ep[U];
     u32x4 K[U], V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, q);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) q[i] *= a.c_score;
-        sm.reset();
+        sm.init(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
         K[u] = gather_raw<G>(a.k, a, c, j);
         V[u] = gather_raw<G>(a.v, a, c, j);
         B[u] = load_bias<G>(a, c, j, e);
+        Ep[u] = e;
     }
-    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx& c, const int (&j)[U]) {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -33,7 +35,7 @@ template <class G, int U> struct GtFwd {
             if (!FULL && j[u] < 0) s[u] = -INFINITY;
         }
         if (!FULL && j[0] < 0) return;
-        sm.update(s, V);
+        sm.absorb(a, c, s, V, Ep, j);
     }
     __device__ void combine_slots(const Args&, const Ctx&) { sm.combine_slots(); }
     __device__ void store_partial(const Args& a, const Ctx& c, int item) { sm.store_partial(a, c, item); }
@@ -41,6 +43,9 @@ template <class G, int U> struct GtFwd {
     __device__ void fold_partial(const PartialRegs<VEC>& P, bool valid) { sm.fold_partial(P, valid); }
     __device__ void finalize(const Args& a, const Ctx& c) { sm.finalize(a, c); }
 };
+template <class G, int U> using GtFwd = GtFwdT<G, U, SoftmaxAcc<G, U>>;
+template <class G, int U> using GtAttention = GtFwdT<G, U, AttentionOut<G, U>>;
+
 
 // Forward pass of the two-kernel comparator (Sec. 3, parallelism maximization fusion): the scores were
 // written by k_edge_scores; this pass reads them back and does the softmax and the aggregation.
