@@ -89,6 +89,26 @@ def algorithmic_bytes(w, graph, edge_bias=False):
     return res
 
 
+SCRUB_BYTES = 512 << 20  # twice the 256 MB Infinity Cache; written before a call to start it with cold caches
+
+
+def compulsory_bytes(w, graph, edge_bias=False):
+    """Bytes of one forward + backward step if every array were moved exactly once (perfect caches): the
+    floor under the gather model of algorithmic_bytes.  Forward reads the input tensors and the CSR and
+    writes the output and the statistics; backward reads inputs, output, upstream gradient, statistics,
+    CSR and CSC and writes one gradient per input tensor."""
+    b = 4 if w.dtype == "f32" else 2
+    T, S = graph.n * w.H * w.D * b, graph.n * 4 * w.H
+    n_in = {"gt": 3, "gat": 1, "agnn": 1, "gatv2": 2}[w.model]
+    csr = 4 * (graph.n + 1) + 4 * graph.nnz
+    fwd = (n_in + 1) * T + 2 * S + csr
+    bwd = (2 * n_in + 2) * T + 2 * S + 2 * csr
+    if edge_bias:  # read forward and backward (with its CSC positions), gradient written once
+        fwd += graph.nnz * 4 * w.H
+        bwd += graph.nnz * (8 * w.H + 4)
+    return fwd + bwd
+
+
 def sample_subproblem(graph, feats, target_edges: int, seed: int):
     """Random rows of the graph (whole neighbourhoods) until ~target_edges edges, relabelled compactly.
 
@@ -157,6 +177,11 @@ def main() -> int:
     ap.add_argument("--cpu-edges", type=int, default=0, help="edges in the CPU-baseline sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-kernel HIP events")
+    ap.add_argument("--attention-weights", action="store_true",
+                    help="also time the attention-weight output (normalised scores per edge from a forward call's statistics)")
+    ap.add_argument("--cold", action="store_true",
+                    help="cold-cache timings (512 MiB overwritten before every call) also for the workloads whose tensors "
+                         "exceed the caches; they are always taken for cfg1-cfg3")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (scale reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -254,11 +279,32 @@ def main() -> int:
         fwd(); bwd()
     torch.cuda.synchronize()
 
-    # separate fwd / bwd split (not the headline number): events around each call
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    ev[0].record(stream); fwd(); ev[1].record(stream); bwd(); ev[2].record(stream)
-    torch.cuda.synchronize()
-    fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+    # separate fwd / bwd split (not the headline number): events around each call, K iterations, median and
+    # minimum.  With `scrub` a buffer twice the size of the Infinity Cache is overwritten before every call,
+    # outside the events, so the call starts with none of its operands in any cache.
+    scrub_buf = None
+
+    def per_call_times(scrub: bool):
+        nonlocal scrub_buf
+        if scrub and scrub_buf is None:
+            scrub_buf = torch.empty(SCRUB_BYTES // 4, dtype=torch.float32, device="cuda")
+        rec = []
+        for it in range(args.steps):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            if scrub:
+                scrub_buf.fill_(float(it))
+            e[0].record(stream); fwd(); e[1].record(stream)
+            if scrub:
+                scrub_buf.fill_(float(it) + 0.5)
+            e[2].record(stream); bwd(); e[3].record(stream)
+            rec.append(e)
+        torch.cuda.synchronize()
+        f = np.array([e[0].elapsed_time(e[1]) for e in rec])
+        b = np.array([e[2].elapsed_time(e[3]) for e in rec])
+        return f, b
+
+    f_warm, b_warm = per_call_times(False)
+    fwd_ms, bwd_ms = float(np.median(f_warm)), float(np.median(b_warm))
 
     # ---- timed region: exactly K steps between synchronisations ----
     # Per-kernel HIP events are recorded by the library on the launch stream.  Two event records per kernel
@@ -322,6 +368,7 @@ def main() -> int:
                     # counters were collected for the workloads as defined, not for variants of them
                     "traffic": None if (args.set or args.edge_bias or args.scores_in_memory) else MEASURED_TRAFFIC.get((w.name, dom)),
                     "algorithmic_bytes_per_launch": model_bytes.get(dom), "avg_ms": kern[dom]["avg_ms"]}
+    compulsory = compulsory_bytes(w, graph, args.edge_bias)
     total_model = sum(model_bytes.get(name, 0) for name in ("fwd", "bwd_row", "bwd_col", "param_reduce"))
 
     result = {
@@ -332,13 +379,49 @@ def main() -> int:
         "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else "") + (" + edge term" if args.edge_bias else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
                    "super_threshold": T, "chunk_edges": C, "stands_in_for": w.stands_in_for},
         "roofline": roofline,
-        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "preprocess_ms": round(preprocess_ms, 2),
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+        "fwd_ms_min": round(float(f_warm.min()), 4), "bwd_ms_min": round(float(b_warm.min()), 4),
+        "preprocess_ms": round(preprocess_ms, 2),
         "step_algorithmic_GB": round(total_model / 1e9, 3),
         "step_effective_GBps": round(total_model / 1e9 / (ms_per_step * 1e-3), 1),
+        "compulsory_GB": round(compulsory / 1e9, 4),
+        "compulsory_time_frac": round(compulsory / (HBM_PEAK_GBPS * 1e9) / (ms_per_step * 1e-3), 4),
         "kernel_events": events_where, "launch": "hip graph replay" if args.hip_graph else "eager",
         "kernels": kern,
     }
 
+    if args.attention_weights:
+        p_out = torch.empty((graph.nnz, H), dtype=torch.float32, device="cuda")
+        att = lambda: dfgnn.attention_weights(g.handle, L, x, k, a_l, a_r, bias, row_max, row_sum, p_out, stream)
+        att()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            att()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        att_ms = e0.elapsed_time(e1) / args.steps
+        # the neighbour row the score needs (GT: K_j without V_j; the other models score and aggregate the same
+        # row), the index and the stored weight; per row the destination features, the two statistics and the
+        # row pointer
+        b_el = 4 if w.dtype == "f32" else 2
+        R, s_ = w.H * w.D * b_el, 4 * w.H
+        per_edge = {"gt": R + 4, "gat": R + 4, "agnn": R + s_ + 4, "gatv2": R + 4}[w.model] + s_ + (s_ if bias is not None else 0)
+        att_bytes = per_edge * graph.nnz + (R + 2 * s_ + 4) * graph.n
+        result["attention_weights"] = {"avg_ms": round(att_ms, 4), "algorithmic_GB": round(att_bytes / 1e9, 4),
+                                       "GBps": round(att_bytes / 1e9 / (att_ms * 1e-3), 1),
+                                       "GEdges_per_s": round(graph.nnz / (att_ms * 1e-3) / 1e9, 3)}
+        del p_out
+    if args.cold or w.name in ("cfg1", "cfg2", "cfg3"):
+        f_cold, b_cold = per_call_times(True)
+        cold_ms = float(np.median(f_cold) + np.median(b_cold))
+        result["cold_cache"] = {
+            "scrub_bytes_before_every_call": SCRUB_BYTES,
+            "fwd_ms": round(float(np.median(f_cold)), 4), "fwd_ms_min": round(float(f_cold.min()), 4),
+            "bwd_ms": round(float(np.median(b_cold)), 4), "bwd_ms_min": round(float(b_cold.min()), 4),
+            "GEdges_per_s": round(graph.nnz / (cold_ms * 1e-3) / 1e9, 4),
+            "compulsory_time_frac": round(compulsory / (HBM_PEAK_GBPS * 1e9) / (cold_ms * 1e-3), 4)}
+        log(f"cold caches: fwd {np.median(f_cold):.3f} + bwd {np.median(b_cold):.3f} ms (warm {fwd_ms:.3f} + {bwd_ms:.3f})")
     if not args.no_cpu_baseline and not args.edge_bias:
         target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 8000000, "cfg5": 10000000}[w.name]
         info, (rows, new_rows, fw, bw) = cpu_baseline(w, graph, feats, target)
