@@ -234,8 +234,8 @@ int dfgnn_backward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer,
  * the inputs and the statistics of a finished dfgnn_forward (or dfgnn_forward_edge_bias; pass the same
  * edge_bias, or NULL) call.  p: [E, H] fp32 device, caller-owned, every entry is overwritten.  Tensor
  * arguments as in dfgnn_forward for the model (v is not needed).  Needs no workspace.  One gather pass
- * over the CSR; meant for inspection and for losses on the attention itself, not for the layer's own
- * backward pass.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ * over the CSR; meant for inspection (attention maps): the layer's own backward pass never needs it and
+ * the library has no gradient through this output.  Errors: EINVAL, EUNSUPPORTED, EHIP.
  */
 int dfgnn_attention_weights(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
                             const float* a_l, const float* a_r, const float* edge_bias, const float* row_max,
