@@ -164,6 +164,7 @@ def main() -> int:
     ap.add_argument("--chunk-edges", type=int, default=0)
     ap.add_argument("--no-short-rows", action="store_true", help="ablation: one wavefront for every row below the super threshold")
     ap.add_argument("--no-dense-batch", action="store_true", help="ablation: general kernels also for batches of small graphs")
+    ap.add_argument("--no-xcd-groups", action="store_true", help="ablation: workgroups dealt round-robin to the XCDs for every graph")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one step (forward + backward) into a HIP graph and replay it K times in the timed region")
     ap.add_argument("--force-dense-batch", action="store_true", help="dense-tile batch kernels whenever they apply")
@@ -221,7 +222,8 @@ def main() -> int:
 
     sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges,
                               (1 if args.no_short_rows else 0) | (2 if args.no_dense_batch else 0) |
-                              (4 if args.force_dense_batch else 0) | (8 if args.scores_in_memory else 0))
+                              (4 if args.force_dense_batch else 0) | (8 if args.scores_in_memory else 0) |
+                              (16 if args.no_xcd_groups else 0))
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])
@@ -377,7 +379,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else "") + (" + edge term" if args.edge_bias else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
-                   "super_threshold": T, "chunk_edges": C, "stands_in_for": w.stands_in_for},
+                   "super_threshold": T, "chunk_edges": C, "xcd_group": g.query("n_xcd_group"), "stands_in_for": w.stands_in_for},
         "roofline": roofline,
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
         "fwd_ms_min": round(float(f_warm.min()), 4), "bwd_ms_min": round(float(b_warm.min()), 4),

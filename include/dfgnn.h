@@ -74,6 +74,12 @@ typedef struct {
  * int32 per edge of graph metadata and E*H*4 bytes of forward workspace; results are the same up to
  * rounding order.  Other models, the backward pass and the dense-tile kernels are unaffected. */
 #define DFGNN_SCHED_SCORES_IN_MEMORY 8
+/* Ablation switch.  dfgnn_graph_create samples the edges; when at least half of them connect nodes whose
+ * ids differ by less than 4096 (batches of small graphs, meshes, clustered numberings) the layer launches
+ * keep runs of 32 consecutive workgroups of their work list on one XCD, so that rows which share
+ * neighbours share an L2.  With this bit workgroups are dealt round-robin for every graph.  Results are
+ * bit-identical either way. */
+#define DFGNN_SCHED_NO_XCD_GROUPS 16
 
 /* One layer call's model description. */
 typedef struct {
@@ -110,7 +116,8 @@ typedef enum {
     DFGNN_Q_N_SUPER_COLS = 10, /* count only */
     DFGNN_Q_SUPER_THRESHOLD = 11, /* count only: the super_threshold in use */
     DFGNN_Q_CHUNK_EDGES = 12,     /* count only: the chunk_edges in use */
-    DFGNN_Q_BATCH_DENSE = 13      /* count only: 1 if the dense-tile batch kernels apply to this graph */
+    DFGNN_Q_BATCH_DENSE = 13,     /* count only: 1 if the dense-tile batch kernels apply to this graph */
+    DFGNN_Q_XCD_GROUP = 14        /* count only: workgroups per XCD-local run (0: the numbering is not local) */
 } dfgnn_query;
 
 const char* dfgnn_status_string(int status);
@@ -153,8 +160,7 @@ int dfgnn_graph_destroy(dfgnn_graph* graph);
  * does not decrease and that no edge connects two graphs (EINVAL otherwise), and records for each row
  * and each column its adjacency bits inside its graph.
  * If no edge is repeated, GT layers are then computed by dense-tile kernels when that pays, i.e. when the
- * 16 x 16 score tiles of the graphs are full enough (edges / (256 x number of tiles) at least about 0.17
- * to 0.25 depending on the kernel; below that the general kernels are faster):
+ * 16 x 16 score tiles of the graphs are full enough (edges / (256 x number of tiles) at least about 0.2; below that the general kernels are faster):
  *   bf16, D = 16 or 32, graphs of at most 64 nodes: one wavefront per (graph, head) stages the head's
  *     Q, K, V once into LDS and forms the masked score block with MFMA;
  *   fp32 or bf16, D = 16, 32 or 64, graphs of at most 512 nodes: one wavefront per (graph, head, 16

@@ -19,7 +19,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 QUERY = {
     "row_order": 0, "row_chunk_ptr": 1, "row_chunks": 2, "t_indptr": 3, "t_indices": 4, "t_eid": 5,
     "col_order": 6, "col_chunk_ptr": 7, "col_chunks": 8, "n_super_rows": 9, "n_super_cols": 10,
-    "n_super_threshold": 11, "n_chunk_edges": 12, "n_batch_dense": 13,
+    "n_super_threshold": 11, "n_chunk_edges": 12, "n_batch_dense": 13, "n_xcd_group": 14,
 }
 
 

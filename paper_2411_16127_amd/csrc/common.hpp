@@ -85,6 +85,7 @@ struct dfgnn_graph {
     int32_t* counters;               // device scratch words inside the metadata buffer
     int32_t* edge_row;               // [E] destination row of every CSR position (only with SCORES_IN_MEMORY)
     bool batch_dense;                // no repeated edge and every graph has at most 512 nodes
+    int32_t xcd_group;               // workgroups per XCD-local run of a pass's work list (0: plain round-robin)
 };
 
 namespace dfgnn {
@@ -104,6 +105,7 @@ int dense32_gt_forward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q
 int dense32_gt_backward(const dfgnn_graph* g, const dfgnn_layer* L, const void* q, const void* k, const void* v,
                         const void* out, const float* row_max, const float* row_sum, const void* d_out, void* d_q,
                         void* d_k, void* d_v, float* stats, hipStream_t st);
+constexpr int kXcdGroup = 32;          // run length used for graphs whose numbering is local
 constexpr int kDenseSmallNodes = 64;   // bf16 kernels: a whole graph head per wavefront
 constexpr int kDenseMaxGraphNodes = 512;
 constexpr int kDenseMaxWords = kDenseMaxGraphNodes / 64;

@@ -309,15 +309,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_dense_gt_backward(const DenseArg
 // The dense kernels form every 16 x 16 score tile of a graph whatever its density, the gather kernels pay
 // per edge, so what decides is how full the tiles are: fill = E / (256 * tile pairs).  Measured on MI355X
 // against the gather kernels:
-//   bf16 kernels of this file:   0.83x at fill 0.19, 1.6x at 0.30, 3.6x at 0.94   -> used from 0.22
-//   fp32 streaming kernels:      0.88x at 0.10, 1.16x at 0.19, 1.3x at 0.28, 1.6x at 0.39   -> used from 0.17
-//   bf16 streaming kernels:      0.54x at 0.10, 1.3x at 0.28, 1.5x at 0.39 (2.5x for one head of 64
-//                                features)   -> used from 0.25
+//   bf16 kernels of this file:   0.83x at fill 0.19, 1.5x at 0.24, 3.5x at 0.94   -> used from 0.22
+//   fp32 streaming kernels:      0.70x at 0.10, 0.91x at 0.18, 1.04x at 0.23, 1.2x at 0.28, 1.5x at 0.39
+//                                -> used from 0.22
+//   bf16 streaming kernels:      0.53x at 0.10, 1.06x at 0.18, 1.16x at 0.23, 1.5x at 0.39 (2.5x for one head
+//                                of 64 features)   -> used from 0.20
 // The streaming kernels gain less because they fetch their operands again for every row tile and spend
 // most of their time on the softmax arithmetic of masked-out tile entries.
 constexpr int64_t kDenseMinEdgesPerTileBf16 = 56;        // 0.22 * 256
-constexpr int64_t kDenseMinEdgesPerTileBf16Stream = 64;  // 0.25 * 256
-constexpr int64_t kDenseMinEdgesPerTileF32 = 44;         // 0.17 * 256
+constexpr int64_t kDenseMinEdgesPerTileBf16Stream = 52;  // 0.20 * 256
+constexpr int64_t kDenseMinEdgesPerTileF32 = 56;         // 0.22 * 256
 
 // 1: bf16 kernels of this file (graphs of at most 64 nodes, staged in LDS); 2: fp32 streaming kernels
 // (dense_batch_f32.hip); 3: bf16 streaming kernels (dense_batch_bf16.hip); 0: general kernels

@@ -221,7 +221,7 @@ static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32
 // ------------------------------------------------------------------------------------------------
 // scheduler kernels
 // ------------------------------------------------------------------------------------------------
-enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_BATCH = 9, CNT_BATCH_MAX = 10, CNT_BATCH_PAIRS = 12, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
+enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_NEAR = 4, CNT_BATCH = 9, CNT_BATCH_MAX = 10, CNT_BATCH_PAIRS = 12, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
 
 __global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -325,6 +325,24 @@ __global__ void k_gather_rows(const int* __restrict__ t_eid, const int* __restri
     if (t < e) t_indices[t] = edge_row[t_eid[t]];
 }
 
+// Locality of the numbering: how many of (up to) kLocalitySamples evenly spaced edges connect two nodes whose
+// ids differ by less than kLocalityWindow.  Graphs numbered that way (batches of small graphs, meshes,
+// clustered orderings) reuse neighbour rows among rows that are close in the work list; the layer launches
+// then keep runs of the list on one XCD so that the reuse happens in that XCD's L2.
+constexpr int kLocalitySamples = 1 << 20;
+constexpr int kLocalityWindow = 4096;
+__global__ void k_edge_locality(const int* __restrict__ edge_row, const int* __restrict__ indices, int e, int stride,
+                                int* __restrict__ near) {
+    const int64_t p = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * stride;
+    int hit = 0;
+    if (p < e) {
+        const int d = edge_row[p] - indices[p];
+        hit = (d < 0 ? -d : d) < kLocalityWindow;
+    }
+    const int n = __popcll(__ballot(hit));
+    if (n > 0 && (threadIdx.x & 63) == 0) atomicAdd(near, n);
+}
+
 // ------------------------------------------------------------------------------------------------
 // layout of the caller's buffers
 // ------------------------------------------------------------------------------------------------
@@ -383,7 +401,7 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
         DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH |
-                                         DFGNN_SCHED_SCORES_IN_MEMORY)) == 0,
+                                         DFGNN_SCHED_SCORES_IN_MEMORY | DFGNN_SCHED_NO_XCD_GROUPS)) == 0,
                       DFGNN_EINVAL, "unknown scheduling flag 0x%x", sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;
@@ -513,6 +531,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     if (rc != DFGNN_OK) return rc;
 
     // CSC transpose: stable sort of CSR positions by source id
+    int locality_stride = 1;
     if (E > 0) {
         int bits = 1;
         while (((int64_t)1 << bits) < N) ++bits;
@@ -530,6 +549,10 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
                            (int)E, edge_row);
         hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid, edge_row, (int)E,
                            g.t_indices);
+        locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
+        const int64_t samples = (E + locality_stride - 1) / locality_stride;
+        hipLaunchKernelGGL(k_edge_locality, dim3((unsigned)((samples + tpb - 1) / tpb)), dim3(tpb), 0, st, edge_row,
+                           d_indices, (int)E, locality_stride, d_counters + CNT_NEAR);
         DFGNN_HIP(hipGetLastError());
     } else {
         DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));
@@ -539,7 +562,12 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     rc = build_schedule(g.t_indptr, N, T, C, g.col_order, g.col_chunk_ptr, g.col_chunks, d_counters, CNT_COL_BUCKETS,
                         CNT_COL_CHUNKS, scratch, S, &g.n_super_cols, &g.n_col_chunks, g.col_bucket_ptr, st);
     if (rc != DFGNN_OK) return rc;
+    int near = 0;
+    DFGNN_HIP(hipMemcpyAsync(&near, d_counters + CNT_NEAR, sizeof(int), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
+    // at least half of the sampled edges stay inside the window: runs of kXcdGroup workgroups share an XCD
+    const int64_t samples = E > 0 ? (E + locality_stride - 1) / locality_stride : 0;
+    g.xcd_group = (!(flags & DFGNN_SCHED_NO_XCD_GROUPS) && samples > 0 && 2 * (int64_t)near >= samples) ? kXcdGroup : 0;
 
     dfgnn_graph* h = new (std::nothrow) dfgnn_graph(g);
     DFGNN_REQUIRE(h != nullptr, DFGNN_EINVAL, "out of host memory");
@@ -736,6 +764,7 @@ extern "C" int dfgnn_graph_query(const dfgnn_graph* g, int what, const void** d_
     case DFGNN_Q_SUPER_THRESHOLD: c = g->T; break;
     case DFGNN_Q_CHUNK_EDGES: c = g->C; break;
     case DFGNN_Q_BATCH_DENSE: c = g->batch_dense ? 1 : 0; break;
+    case DFGNN_Q_XCD_GROUP: c = g->xcd_group; break;
     default: DFGNN_REQUIRE(false, DFGNN_EINVAL, "unknown query item %d", what);
     }
     if (d_ptr) *d_ptr = p;

@@ -165,6 +165,7 @@ struct Args {
     int n_direct, blocks_direct;            // whole-row items: order[first_direct + item]
     int n_small, first_small, first_direct; // short rows: order[first_small + r], one per edge slot
     int n_items;                            // merge kernel: super rows
+    int xcd_group;                          // workgroups per XCD-local run of the work list (0: no remapping)
     int n_nodes;
     uint32_t row_bytes;     // bytes of one node row
     uint32_t tensor_bytes;  // bytes of one node tensor (< 4 GiB)
@@ -575,6 +576,18 @@ template <class G, template <class, int> class PassT, int U>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int b = blockIdx.x;
+    // The hardware deals workgroups to the 8 XCDs round-robin.  For graphs whose numbering is local the
+    // work list is cut into runs of xcd_group workgroups and run r of every 8 goes to XCD r, so that rows
+    // which are neighbours in the list (and share neighbour rows) meet in one L2, while all XCDs still
+    // advance through the degree-ordered list at the same pace.
+    if (a.xcd_group > 0) {
+        const int G8 = a.xcd_group << 3;
+        const int whole = (int)(gridDim.x / (unsigned)G8) * G8;
+        if (b < whole) {
+            const int super = b / G8, r = b - super * G8;
+            b = super * G8 + (r & 7) * a.xcd_group + (r >> 3);
+        }
+    }
     if (b < a.blocks_chunk) {
         const int item = b * kWavesPerBlock + wave;
         if (item < a.n_chunks) wave_item<G, PassT, U, true>(a, item, lane);

@@ -63,6 +63,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
     const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
     const dim3 block(64 * kWavesPerBlock);
+    a.xcd_group = g->xcd_group;
     if (total > 0) {
         KernelTimer t(labels[0], st);
         if (a.bias) hipLaunchKernelGGL((k_pass<with_edge_term<G>, PassT, kUnroll>), dim3(total), block, 0, st, a);

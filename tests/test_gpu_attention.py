@@ -99,6 +99,23 @@ def test_workloads(name, shrink):
     check(graph, w, make_features(w, graph.n))
 
 
+def test_cfg4_full_size_sampled():
+    """11.2M edges with the default schedule (the launch configuration the benchmark times): the weights of
+    sampled rows, among them hub rows of 200,000 edges cut into hundreds of chunks."""
+    w = make_workload("cfg4")
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    got = gpu_attention(graph, w, feats)
+    deg = graph.degrees()
+    rng = np.random.default_rng(78)
+    sample = np.unique(np.concatenate([rng.choice(graph.n, 200, replace=False), np.argsort(deg)[-3:]]))
+    ref = oracle.forward(oracle_layer(w), graph.indptr, graph.indices, x=feats["feat"].astype(np.float64),
+                         rows=sample, want_p=True)["p"]
+    edges = np.concatenate([np.arange(graph.indptr[i], graph.indptr[i + 1]) for i in sample])
+    assert np.all(np.isfinite(ref[edges]))
+    assert_close("p", got[edges], ref[edges], "f32")
+
+
 def test_argument_errors():
     import torch
     graph = tiny_graph("random", seed=15, n=30)
