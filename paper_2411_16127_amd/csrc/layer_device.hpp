@@ -251,8 +251,10 @@ template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int n
     c.g = lane / G::LPE;
     c.f0 = c.c * G::VEC;
     c.active = c.f0 < a.HD;
-    c.h = c.active ? c.f0 / a.D : 0;
-    c.head0 = c.active && (c.f0 % a.D) == 0;
+    // head of this lane: lanes per head is a power of two (a compile-time one where the geometry fixes it)
+    const int lph = G::LPH > 0 ? G::LPH : a.lph;
+    c.h = c.active ? c.c >> __builtin_ctz(lph) : 0;
+    c.head0 = c.active && (c.c & (lph - 1)) == 0;
     c.node = node;
     c.off = (size_t)node * a.row_stride + c.f0;
     c.woff = (size_t)node * a.HD + c.f0;
@@ -581,11 +583,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
     // which are neighbours in the list (and share neighbour rows) meet in one L2, while all XCDs still
     // advance through the degree-ordered list at the same pace.
     if (a.xcd_group > 0) {
-        const int G8 = a.xcd_group << 3;
-        const int whole = (int)(gridDim.x / (unsigned)G8) * G8;
-        if (b < whole) {
-            const int super = b / G8, r = b - super * G8;
-            b = super * G8 + (r & 7) * a.xcd_group + (r >> 3);
+        const int sh = __builtin_ctz(a.xcd_group) + 3;  // the run length is a power of two
+        if (b < (int)((gridDim.x >> sh) << sh)) {
+            const int r = b & ((1 << sh) - 1);
+            b = (b - r) + (r & 7) * a.xcd_group + (r >> 3);
         }
     }
     if (b < a.blocks_chunk) {
