@@ -44,7 +44,7 @@ class _CLayer(ctypes.Structure):
 class SchedParams:
     super_threshold: int = 0  # 0 = library default
     chunk_edges: int = 0
-    flags: int = 0            # bits: 1 = no short-row mapping, 2 = no dense-tile batch kernels, 4 = dense-tile kernels whenever they apply, 8 = GT forward with scores through memory (comparator)
+    flags: int = 0            # bits: 1 = no short-row mapping, 2 = no dense-tile batch kernels, 4 = dense-tile kernels whenever they apply, 8 = GT forward with scores through memory (comparator), 16 = no XCD-local runs of the work list
 
     def _c(self) -> _CSched:
         return _CSched(self.super_threshold, self.chunk_edges, self.flags, (ctypes.c_int32 * 5)())
@@ -284,12 +284,13 @@ class Graph:
 
     @classmethod
     def from_edge_index(cls, src, dst, num_nodes: int, sched: Optional[SchedParams] = None, device="cuda:0",
-                        stream=None):
+                        stream=None, batch_ptr=None):
         """Graph from an unsorted edge list (edge e goes from src[e] to dst[e]; any integer dtype, host or
         device).  Edges are grouped by destination with a stable sort, so the sources of a row keep their
         order in the list.  Returns (graph, perm): perm[t] is the list position of the edge stored at CSR
         position t, i.e. per-edge data in list order becomes CSR order by `data[perm]` (edge terms), and CSR
-        order goes back with `out[perm] = data_csr`."""
+        order goes back with `out[perm] = data_csr`.  batch_ptr (optional, [n_graphs + 1]) announces a
+        block-diagonal batch of small graphs."""
         import torch
         dev = torch.device(device)
         src = torch.as_tensor(src).to(dev).flatten().long()
@@ -303,7 +304,37 @@ class Graph:
         counts = torch.bincount(dst, minlength=num_nodes)
         indptr = torch.zeros(num_nodes + 1, dtype=torch.int64, device=dev)
         indptr[1:] = torch.cumsum(counts, 0)
-        return cls(indptr.to(torch.int32), src[order].to(torch.int32), sched, device, stream), order
+        return cls(indptr.to(torch.int32), src[order].to(torch.int32), sched, device, stream,
+                   batch_ptr=batch_ptr), order
+
+    @classmethod
+    def from_graph_list(cls, graphs, sched: Optional[SchedParams] = None, device="cuda:0", stream=None):
+        """One block-diagonal graph from a mini-batch of small graphs (the batch-graph setting of Sec. 5.1).
+        graphs: sequence of (src, dst, num_nodes) with node ids local to each graph.  Returns
+        (graph, perm, batch_ptr): graph b owns nodes batch_ptr[b] .. batch_ptr[b+1]-1 of the batch (node
+        tensors of the graphs concatenated in order), perm as in from_edge_index over the concatenated edge
+        lists.  The batch structure is announced to the library (dfgnn_graph_set_batch)."""
+        import torch
+        dev = torch.device(device)
+        sizes = torch.tensor([int(n) for _, _, n in graphs], dtype=torch.int64)
+        if sizes.numel() == 0 or int(sizes.min()) < 0:
+            raise ValueError("a batch needs at least one graph, and node counts cannot be negative")
+        batch_ptr = torch.zeros(sizes.numel() + 1, dtype=torch.int64)
+        batch_ptr[1:] = torch.cumsum(sizes, 0)
+        srcs, dsts = [], []
+        for b, (src, dst, n) in enumerate(graphs):
+            src = torch.as_tensor(src).to(dev).flatten().long()
+            dst = torch.as_tensor(dst).to(dev).flatten().long()
+            if src.numel() != dst.numel():
+                raise ValueError(f"graph {b}: src and dst differ in length")
+            if src.numel() and (int(src.min()) < 0 or int(dst.min()) < 0 or int(src.max()) >= n or int(dst.max()) >= n):
+                raise ValueError(f"graph {b}: edge endpoint out of range")
+            srcs.append(src + int(batch_ptr[b]))
+            dsts.append(dst + int(batch_ptr[b]))
+        bp = batch_ptr.to(torch.int32).to(dev)
+        g, perm = cls.from_edge_index(torch.cat(srcs), torch.cat(dsts), int(batch_ptr[-1]), sched, device, stream,
+                                      batch_ptr=bp)
+        return g, perm, bp
 
     def close(self) -> None:
         if getattr(self, "handle", None) is not None:

@@ -74,3 +74,37 @@ def test_graph_from_an_unsorted_edge_list():
     with pytest.raises(ValueError):
         dfgnn.Graph.from_edge_index(torch.tensor([0, n]), torch.tensor([1, 2]), n)
     g.close()
+
+
+def test_graph_from_a_list_of_small_graphs():
+    """from_graph_list offsets the node ids of every graph, builds the block-diagonal CSR and announces the
+    batch; the layer on the batch equals the layer on every graph alone."""
+    import torch
+    from dfgnn_synth import from_edge_list
+    from paper_2411_16127_amd.autograd import gt_conv
+    rng = np.random.default_rng(8)
+    graphs, all_src, all_dst, off = [], [], [], 0
+    for _ in range(37):
+        n = int(rng.integers(3, 30))
+        pairs = np.unique(rng.integers(0, n, size=(4 * n, 2)), axis=0)  # no repeated edge
+        graphs.append((torch.from_numpy(pairs[:, 0]), torch.from_numpy(pairs[:, 1]), n))
+        all_src.append(pairs[:, 0] + off); all_dst.append(pairs[:, 1] + off)
+        off += n
+    g, perm, bp = dfgnn.Graph.from_graph_list(graphs)
+    ref = from_edge_list(off, np.concatenate(all_src), np.concatenate(all_dst), sort=False)
+    assert np.array_equal(g.indptr.cpu().numpy(), ref.indptr) and np.array_equal(g.indices.cpu().numpy(), ref.indices)
+    assert np.array_equal(bp.cpu().numpy(), np.cumsum([0] + [n for _, _, n in graphs]))
+    assert np.array_equal(np.concatenate(all_src)[perm.cpu().numpy()], ref.indices)
+    assert g.query("n_batch_dense") == 1 and g.query("n_xcd_group") == 32
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    q, k, v = (torch.randn((off, 2, 16), device="cuda", generator=gen) for _ in range(3))
+    whole = gt_conv(g, q, k, v)
+    for b in (0, 17, 36):
+        lo, hi = int(bp[b]), int(bp[b + 1])
+        single, _ = dfgnn.Graph.from_edge_index(graphs[b][0], graphs[b][1], graphs[b][2])
+        alone = gt_conv(single, q[lo:hi].contiguous(), k[lo:hi].contiguous(), v[lo:hi].contiguous())
+        torch.testing.assert_close(whole[lo:hi], alone, rtol=1e-4, atol=1e-5)
+        single.close()
+    with pytest.raises(ValueError):
+        dfgnn.Graph.from_graph_list([(torch.tensor([0, 3]), torch.tensor([1, 1]), 3)])
+    g.close()
