@@ -30,9 +30,9 @@ HBM_PEAK_GBPS = 8000.0
 # under profiles/ named after the kernel and workload); bytes per launch, None where not measured.
 MEASURED_TRAFFIC = {
     # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB per launch, see profiles/{gt_cfg5,agnn_cfg4,gat_cfg3}_kernels.md
-    ("cfg5", "fwd"): 123951783641, ("cfg5", "bwd_row"): 127055640847, ("cfg5", "bwd_col"): 141948874346,
-    ("cfg4", "fwd"): 3487734738, ("cfg4", "bwd_row"): 4058173831, ("cfg4", "bwd_col"): 5937760112,
-    ("cfg3", "fwd"): 475515075, ("cfg3", "bwd_row"): 590400447, ("cfg3", "bwd_col"): 760446089,
+    ("cfg5", "fwd"): 123928964733, ("cfg5", "bwd_row"): 127089949709, ("cfg5", "bwd_col"): 141920663322,
+    ("cfg4", "fwd"): 3487901460, ("cfg4", "bwd_row"): 4059106342, ("cfg4", "bwd_col"): 5937733470,
+    ("cfg3", "fwd"): 473009336, ("cfg3", "bwd_row"): 591679392, ("cfg3", "bwd_col"): 760945557,
 }
 
 DESCRIPTIONS = {
