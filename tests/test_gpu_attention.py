@@ -99,6 +99,23 @@ def test_workloads(name, shrink):
     check(graph, w, make_features(w, graph.n))
 
 
+def test_statistics_of_the_dense_tile_kernels():
+    """A batch of small graphs whose forward pass ran on the dense-tile (MFMA) kernels: their statistics
+    feed the attention output like those of the general kernels."""
+    import torch
+    w = make_workload("cfg2", shrink=8)
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(flags=4), batch_ptr=graph.batch_ptr)
+    assert g.query("n_batch_dense") == 1
+    L = gpu_layer(w)
+    q, k, v = (to_device(feats[n], w.dtype) for n in ("q", "k", "v"))
+    out, rmax, rsum = g.forward(L, q, k, v)
+    got = to_host(g.attention(L, q, k, None, None, rmax, rsum))
+    g.close()
+    assert_close("p", got, oracle_attention(graph, w, feats), "f32")
+
+
 def test_cfg4_full_size_sampled():
     """11.2M edges with the default schedule (the launch configuration the benchmark times): the weights of
     sampled rows, among them hub rows of 200,000 edges cut into hundreds of chunks."""
