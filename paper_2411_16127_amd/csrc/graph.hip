@@ -329,7 +329,7 @@ __global__ void k_gather_rows(const int* __restrict__ t_eid, const int* __restri
 // ids differ by less than kLocalityWindow.  Graphs numbered that way (batches of small graphs, meshes,
 // clustered orderings) reuse neighbour rows among rows that are close in the work list; the layer launches
 // then keep runs of the list on one XCD so that the reuse happens in that XCD's L2.
-constexpr int kLocalitySamples = 1 << 20;
+constexpr int kLocalitySamples = 1 << 16;
 constexpr int kLocalityWindow = 4096;
 __global__ void k_edge_locality(const int* __restrict__ edge_row, const int* __restrict__ indices, int e, int stride,
                                 int* __restrict__ near) {
@@ -339,8 +339,14 @@ __global__ void k_edge_locality(const int* __restrict__ edge_row, const int* __r
         const int d = edge_row[p] - indices[p];
         hit = (d < 0 ? -d : d) < kLocalityWindow;
     }
+    // one atomic per workgroup: wavefront counts meet in LDS first
+    __shared__ int block_hits;
+    if (threadIdx.x == 0) block_hits = 0;
+    __syncthreads();
     const int n = __popcll(__ballot(hit));
-    if (n > 0 && (threadIdx.x & 63) == 0) atomicAdd(near, n);
+    if (n > 0 && (threadIdx.x & 63) == 0) atomicAdd(&block_hits, n);
+    __syncthreads();
+    if (threadIdx.x == 0 && block_hits > 0) atomicAdd(near, block_hits);
 }
 
 // ------------------------------------------------------------------------------------------------
