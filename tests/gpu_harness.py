@@ -5,8 +5,8 @@ import numpy as np
 import oracle
 import paper_2411_16127_amd as dfgnn
 
-# fp32: |gpu - ref| <= 1e-5 + 1e-4 |ref|.  bf16 tensors: 2e-2 relative plus 2e-2 * rms(ref) absolute
-# (the stated tolerance has no absolute term; see the design notes).
+# fp32: |gpu - ref| <= 1e-5 + 1e-4 |ref|.  bf16 tensors: 2e-2 relative plus max(2e-2 * rms(ref), 1e-5) absolute
+# (the stated tolerance has no absolute term).
 F32_RTOL, F32_ATOL = 1e-4, 1e-5
 BF16_RTOL = 2e-2
 
@@ -84,10 +84,12 @@ def tolerance(name, ref, dtype):
     Parameter gradients (d_a_l, d_a_r, d_scale) are sums of signed terms over all nodes and edges; their
     fp32 error scales with the size of the terms, not of the (partly cancelled) result, so the relative
     part is taken against the rms of the gradient vector when an element is smaller than that.
-    bf16 layers: 2e-2 relative plus 2e-2 * rms(ref) absolute.
+    bf16 layers: 2e-2 relative plus 2e-2 * rms(ref) absolute, the absolute part never below the fp32 one:
+    where the exact result is zero throughout (dS = 0 when every row has a single edge) the computed one is
+    the fp32 rounding of terms that cancel.
     """
     if dtype == "bf16":
-        return BF16_RTOL, BF16_RTOL * _rms(ref), 0.0
+        return BF16_RTOL, max(BF16_RTOL * _rms(ref), F32_ATOL), 0.0
     if name in ("d_a_l", "d_a_r", "d_scale"):
         return F32_RTOL, F32_ATOL, _rms(ref)
     return F32_RTOL, F32_ATOL, 0.0
