@@ -75,3 +75,33 @@ def test_random_case(seed):
     if graph.nnz:
         assert_close("p", p, p_ref, "f32")
     g.close()
+
+
+def draw_batch(seed):
+    rng = np.random.default_rng([2025, seed])
+    dtype = "bf16" if rng.random() < 0.5 else "f32"
+    H = int(rng.choice([1, 2, 3, 4, 8]))
+    D = int(rng.choice([16, 32, 64]))
+    if H * D > (256 if dtype == "f32" else 512):  # keep the row within one wavefront for the general kernels too
+        H = 1
+    n_graphs = int(rng.integers(1, 30))
+    hi = int(rng.choice([5, 16, 17, 40, 64, 65, 130, 300]))
+    lo = int(rng.integers(1, hi + 1))
+    density = float(rng.choice([0.03, 0.1, 0.3, 0.7, 1.0]))
+    return dtype, H, D, n_graphs, lo, hi, density
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("DFGNN_RANDOM_BATCHES", "48"))))
+def test_random_batch_on_the_dense_tile_kernels(seed):
+    """Batches of small graphs on the MFMA kernels (forced, so that sparse batches take them too): LDS-staged
+    bf16 up to 64 nodes, streaming fp32 / bf16 up to 512 nodes."""
+    from dfgnn_synth import batched_small_graphs
+    dtype, H, D, n_graphs, lo, hi, density = draw_batch(seed)
+    graph = batched_small_graphs(n_graphs, lo, hi, density, seed=seed)
+    w = Workload("batch", 700 + seed, "gt", H, D, dtype, float(D) ** -0.5)
+    feats = make_features(w, graph.n)
+    print(f"{dtype} H={H} D={D} graphs={n_graphs} nodes {lo}-{hi} density {density} N={graph.n} E={graph.nnz}", flush=True)
+    res, g = run_gpu(graph, w, feats, sched=dfgnn.SchedParams(flags=4))
+    assert g.query("n_batch_dense") == 1
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
