@@ -54,3 +54,22 @@ def test_oracle_is_not_reachable_from_the_product_package():
             if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
                 text = open(os.path.join(dirpath, f), errors="ignore").read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_layer_calls_reject_missing_handles_before_touching_the_gpu():
+    """NULL graph or layer: EINVAL from the host-side checks (no GPU needed), with a message."""
+    import ctypes
+    L = dfgnn.lib()
+    null = ctypes.c_void_p(None)
+    sz = ctypes.c_size_t()
+    calls = {
+        "dfgnn_workspace_bytes": (null, null, ctypes.byref(sz), ctypes.byref(sz)),
+        "dfgnn_forward": (null, null) + (null,) * 8 + (null, 0, null),
+        "dfgnn_forward_edge_bias": (null, null) + (null,) * 9 + (null, 0, null),
+        "dfgnn_backward": (null, null) + (null,) * 15 + (null, 0, null),
+        "dfgnn_backward_edge_bias": (null, null) + (null,) * 17 + (null, 0, null),
+        "dfgnn_attention_weights": (null, null) + (null,) * 8 + (null,),
+    }
+    for name, args in calls.items():
+        assert getattr(L, name)(*args) == 1, name  # DFGNN_EINVAL
+        assert "NULL" in dfgnn.last_error(), name
