@@ -7,7 +7,8 @@
  * models of Sec. 5.1: GT (dot-SDDMM), GAT (add-SDDMM) and AGNN (dot-SDDMM on L2-normalised features),
  * and for GATv2 (the other member of the GAT family cited in Sec. 1).
  * Per-edge scores and attention weights live only in registers; nothing of size O(edges) is written
- * to memory by the layer calls (except the gradient of an edge term, when the caller asks for one).
+ * to memory by the layer calls (except the gradient of an edge term, when the caller asks for one, and
+ * the output of dfgnn_attention_weights, which exists to write them).
  *
  * General rules
  *  - Every pointer named d_* or documented as "device" is GPU global memory owned by the caller; the
@@ -18,7 +19,7 @@
  *    (sources).  Sources need not be sorted inside a row; repeated edges are separate softmax terms;
  *    empty rows are legal (O = 0, row_max = -inf, row_sum = 0, no gradient contribution).
  *  - All layer calls are asynchronous on the HIP stream passed as `stream` (a hipStream_t; NULL = the
- *    default stream).  Only dfgnn_graph_create synchronises that stream.
+ *    default stream).  Only dfgnn_graph_create and dfgnn_graph_set_batch synchronise that stream.
  *  - Every function returns a dfgnn_status; nothing throws or aborts across this boundary.  On any
  *    error no output buffer has defined contents.  dfgnn_last_error() gives a thread-local detail text.
  *  - Outputs are overwritten, never accumulated into.
