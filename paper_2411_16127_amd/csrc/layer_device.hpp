@@ -577,6 +577,7 @@ __device__ inline void wave_small_rows(const Args& a, int item, int lane) {
 template <class G, template <class, int> class PassT, int U>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wpb = (int)blockDim.x >> 6;  // wavefronts per workgroup (the host picks 1, 2 or 4)
     int b = blockIdx.x;
     // The hardware deals workgroups to the 8 XCDs round-robin.  For graphs whose numbering is local the
     // work list is cut into runs of xcd_group workgroups and run r of every 8 goes to XCD r, so that rows
@@ -590,19 +591,19 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
         }
     }
     if (b < a.blocks_chunk) {
-        const int item = b * kWavesPerBlock + wave;
+        const int item = b * wpb + wave;
         if (item < a.n_chunks) wave_item<G, PassT, U, true>(a, item, lane);
         return;
     }
     b -= a.blocks_chunk;
     if (b < a.blocks_direct) {
-        const int item = b * kWavesPerBlock + wave;
+        const int item = b * wpb + wave;
         if (item < a.n_direct) wave_item<G, PassT, U, false>(a, item, lane);
         return;
     }
     b -= a.blocks_direct;
     if constexpr (G::EPW > 1) {
-        const int item = b * kWavesPerBlock + wave;
+        const int item = b * wpb + wave;
         if (item * G::EPW < a.n_small) wave_small_rows<G, PassT, U>(a, item, lane);
     }
 }

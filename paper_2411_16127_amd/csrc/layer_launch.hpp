@@ -53,6 +53,12 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     }
     const int64_t n_direct = first_small - n_super;
     const int64_t n_small = g->N - first_small;
+    // small launches spread their wavefronts over more compute units with smaller workgroups
+    // (2,708-node graph: 25.2 us per training step with 4 wavefronts per workgroup, 23.5 with 1)
+    const int64_t small_waves = G::EPW > 1 ? (n_small + G::EPW - 1) / G::EPW : 0;
+    const int64_t all_waves = n_chunks + n_direct + small_waves;
+    const int wpb = all_waves <= 1024 ? 1 : (all_waves <= 4096 ? 2 : kWavesPerBlock);
+    auto blocks_for = [&](int64_t waves) { return (unsigned)((waves + wpb - 1) / wpb); };
     a.n_chunks = n_chunks;
     a.blocks_chunk = (int)blocks_for(n_chunks);
     a.n_direct = (int)n_direct;
@@ -62,7 +68,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     a.first_small = (int)first_small;
     const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
     const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
-    const dim3 block(64 * kWavesPerBlock);
+    const dim3 block(64 * wpb);
     a.xcd_group = g->xcd_group;
     if (total > 0) {
         KernelTimer t(labels[0], st);
@@ -72,7 +78,7 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     if (n_super > 0 && merge) {
         a.n_items = n_super;
         KernelTimer t(labels[1], st);
-        hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(blocks_for(n_super)), block, 0, st, a);
+        hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(dfgnn::blocks_for(n_super)), dim3(64 * kWavesPerBlock), 0, st, a);
     }
 }
 
