@@ -22,6 +22,22 @@ KINDS = ["random", "hub", "dups", "unsorted", "chain", "selfloop"]
 SCALES = {"gt": None, "gat": 1.0, "agnn": 1.3, "gatv2": 1.0}
 
 
+def compare_with_oracle(res, ref, w, graph):
+    """compare_all, except where no row has more than one edge.  Then dS = 0 and every gradient that flows
+    through the scores is exactly zero; a bf16 layer computes it as a difference of two equal fp32 terms of
+    size |dP| |k| (the exact-delta form of its row pass), whose rounding residue (some 1e-5 for 64-wide heads)
+    the element-wise bounds, relative to a reference of zero, cannot describe: those tensors get an
+    absolute bound of 1e-4 here."""
+    single = int(np.diff(graph.indptr).max(initial=0)) <= 1 and w.dtype == "bf16"
+    through_scores = [key for key in ("d_a_l", "d_a_r", "d_scale", "d_edge_bias") if key in ref]
+    through_scores += [key for key in ("d_x", "d_k") if key in ref and w.model in ("gt", "gatv2")]
+    if not single:
+        return compare_all(res, ref, w)
+    rest = [key for key in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v") if key in ref and key not in through_scores]
+    compare_all(res, ref, w, keys=rest)
+    compare_all(res, ref, w, keys=through_scores, tol=(2e-2, 1e-4, 0.0))
+
+
 def draw_case(seed):
     rng = np.random.default_rng([2024, seed])
     model = ["gt", "gat", "agnn", "gatv2"][seed % 4]
@@ -50,16 +66,7 @@ def test_random_case(seed):
     case = f"{model} {dtype} H={H} D={D} {kind} n={n} T={T} C={C} flags={flags} bias={bias}"
     print(case, flush=True)
     res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(T, C, flags))
-    ref = run_oracle(graph, w, feats)
-    params = [key for key in ("d_a_l", "d_a_r", "d_scale") if key in ref]
-    compare_all(res, ref, w, keys=[key for key in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v", "d_edge_bias")
-                                   if key in ref])
-    if params:
-        # rows of at most one edge have dS = 0: the exact score-side parameter gradients are zero and the
-        # computed ones are sums over all edges of fp32 rounding residues (|term| * 2^-24 each), which the
-        # element-wise bounds (relative to a reference of zero) cannot describe
-        single = int(np.diff(graph.indptr).max(initial=0)) <= 1
-        compare_all(res, ref, w, keys=params, tol=(2e-2, 1e-4, 0.0) if single and dtype == "bf16" else None)
+    compare_with_oracle(res, run_oracle(graph, w, feats), w, graph)
     # attention weights from the same call's statistics
     L = gpu_layer(w)
     f32 = lambda name: None if name not in feats else torch.from_numpy(feats[name]).cuda()
@@ -103,5 +110,5 @@ def test_random_batch_on_the_dense_tile_kernels(seed):
     print(f"{dtype} H={H} D={D} graphs={n_graphs} nodes {lo}-{hi} density {density} N={graph.n} E={graph.nnz}", flush=True)
     res, g = run_gpu(graph, w, feats, sched=dfgnn.SchedParams(flags=4))
     assert g.query("n_batch_dense") == 1
-    compare_all(res, run_oracle(graph, w, feats), w)
+    compare_with_oracle(res, run_oracle(graph, w, feats), w, graph)
     g.close()
