@@ -85,11 +85,42 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_apply(const int* in, int*
     }
 }
 
+// Short arrays: one workgroup walks the tiles with a running carry, one launch instead of three (the
+// scheduler of a small graph is a chain of dependent launches, and their number is what it costs).
+// in and out may be the same array.
+constexpr int kScanSingleTiles = 32;
+__global__ __launch_bounds__(kScanThreads) void k_scan_single(const int* in, int* out, int n) {
+    int carry = 0;
+    for (int tile = 0; tile * kScanTile < n; ++tile) {
+        const int base = tile * kScanTile + threadIdx.x * kScanItems;
+        int v[kScanItems];
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            v[k] = base + k < n ? in[base + k] : 0;
+            s += v[k];
+        }
+        int total;
+        int run = carry + block_exclusive_scan(s, &total);
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            if (base + k < n) out[base + k] = run;
+            run += v[k];
+        }
+        carry += total;
+    }
+}
+
 inline int64_t scan_blocks(int64_t n) { return (n + kScanTile - 1) / kScanTile; }
 
 static int exclusive_scan(const int* in, int* out, int64_t n, int* sums_tmp, hipStream_t st) {
     if (n <= 0) return DFGNN_OK;
     const int nb = (int)scan_blocks(n);
+    if (nb <= kScanSingleTiles) {
+        hipLaunchKernelGGL(k_scan_single, dim3(1), dim3(kScanThreads), 0, st, in, out, (int)n);
+        DFGNN_HIP(hipGetLastError());
+        return DFGNN_OK;
+    }
     hipLaunchKernelGGL(k_scan_block_sums, dim3(nb), dim3(kScanThreads), 0, st, in, (int)n, sums_tmp);
     hipLaunchKernelGGL(k_scan_sums_inplace, dim3(1), dim3(kScanThreads), 0, st, sums_tmp, nb);
     hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(kScanThreads), 0, st, in, out, (int)n, sums_tmp);
@@ -270,9 +301,10 @@ __global__ void k_chunk_counts(const int* __restrict__ order, const int* __restr
 }
 
 __global__ void k_fill_chunks(const int* __restrict__ order, const int* __restrict__ ptr,
-                              const int* __restrict__ chunk_ptr, int n_super, int n_chunks, int C, int* __restrict__ chunks) {
+                              const int* __restrict__ chunk_ptr, int n_super, const int* __restrict__ n_chunks, int C,
+                              int* __restrict__ chunks) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= n_chunks) return;
+    if (c >= *n_chunks) return;
     int lo = 0, hi = n_super;  // last s with chunk_ptr[s] <= c
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -417,42 +449,40 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
     return DFGNN_OK;
 }
 
-// Row (or column) order and super chunks for one pointer array.
-static int build_schedule(const int* ptr, int64_t n, int T, int C, int* order, int* chunk_ptr, int* chunks,
-                          int* d_counters, int slot_buckets, int slot_chunks, char* scratch, const ScratchLayout& S,
-                          int* n_super_out, int* n_chunks_out, int32_t (&bucket_ptr)[36], hipStream_t st) {
-    *n_super_out = 0;
-    *n_chunks_out = 0;
-    for (int& b : bucket_ptr) b = 0;
+// Row (or column) order for one pointer array: the degree-class sort and, in the device counters, where
+// each class starts in the order.  Nothing is read back here; the caller reads all counters at once.
+static int schedule_order(const int* ptr, int64_t n, int T, int* order, int* d_counters, int slot_buckets, char* scratch,
+                          const ScratchLayout& S, hipStream_t st) {
     if (n == 0) return DFGNN_OK;
     uint32_t* keys_a = (uint32_t*)(scratch + S.keys_a);
     uint32_t* keys_b = (uint32_t*)(scratch + S.keys_b);
-    int* vals = (int*)(scratch + S.vals);
-    int* counts = (int*)(scratch + S.counts);
-    int* scan_tmp = (int*)(scratch + S.scan_tmp);
-    int* cnt = (int*)(scratch + S.cnt);
     const int tpb = 256;
     hipLaunchKernelGGL(k_degree_keys, dim3((unsigned)((n + tpb - 1) / tpb)), dim3(tpb), 0, st, ptr, (int)n, T, keys_a);
     const uint32_t* sorted = nullptr;
-    int rc = radix_sort_pairs(keys_a, n, 6, keys_b, keys_a, order, vals, counts, scan_tmp, &sorted, st);
+    int rc = radix_sort_pairs(keys_a, n, 6, keys_b, keys_a, order, (int*)(scratch + S.vals), (int*)(scratch + S.counts),
+                              (int*)(scratch + S.scan_tmp), &sorted, st);
     if (rc != DFGNN_OK) return rc;
     hipLaunchKernelGGL(k_bucket_ptr, dim3(1), dim3(64), 0, st, sorted, (int)n, d_counters + slot_buckets);
-    DFGNN_HIP(hipMemcpyAsync(bucket_ptr, d_counters + slot_buckets, 36 * sizeof(int), hipMemcpyDeviceToHost, st));
-    DFGNN_HIP(hipStreamSynchronize(st));
-    const int n_super = bucket_ptr[1];
-    *n_super_out = n_super;
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+// Chunks of the n_super super rows (or columns) at the head of `order`.  The number of chunks stays on the
+// device (counter slot_chunks, which k_fill_chunks reads; its grid covers max_chunks); the caller reads it
+// back with the other counters.
+static int schedule_chunks(const int* ptr, int n_super, int C, const int* order, int* chunk_ptr, int* chunks,
+                           int64_t max_chunks, int* d_counters, int slot_chunks, char* scratch, const ScratchLayout& S,
+                           hipStream_t st) {
     if (n_super == 0) return DFGNN_OK;
+    int* cnt = (int*)(scratch + S.cnt);
+    const int tpb = 256;
     hipLaunchKernelGGL(k_chunk_counts, dim3((unsigned)((n_super + 1 + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
                        n_super, C, cnt);
-    rc = exclusive_scan(cnt, chunk_ptr, (int64_t)n_super + 1, scan_tmp, st);
+    int rc = exclusive_scan(cnt, chunk_ptr, (int64_t)n_super + 1, (int*)(scratch + S.scan_tmp), st);
     if (rc != DFGNN_OK) return rc;
-    int n_chunks = 0;
-    DFGNN_HIP(hipMemcpyAsync(&n_chunks, chunk_ptr + n_super, sizeof(int), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipMemcpyAsync(d_counters + slot_chunks, chunk_ptr + n_super, sizeof(int), hipMemcpyDeviceToDevice, st));
-    DFGNN_HIP(hipStreamSynchronize(st));
-    *n_chunks_out = n_chunks;
-    hipLaunchKernelGGL(k_fill_chunks, dim3((unsigned)((n_chunks + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
-                       chunk_ptr, n_super, n_chunks, C, chunks);
+    hipLaunchKernelGGL(k_fill_chunks, dim3((unsigned)((max_chunks + tpb - 1) / tpb)), dim3(tpb), 0, st, order, ptr,
+                       chunk_ptr, n_super, d_counters + slot_chunks, C, chunks);
     DFGNN_HIP(hipGetLastError());
     return DFGNN_OK;
 }
@@ -531,9 +561,8 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
                       "range, 16 index out of range)", flags);
     }
 
-    // rows: order and chunks
-    rc = build_schedule(d_indptr, N, T, C, g.row_order, g.row_chunk_ptr, g.row_chunks, d_counters, CNT_ROW_BUCKETS,
-                        CNT_ROW_CHUNKS, scratch, S, &g.n_super_rows, &g.n_row_chunks, g.row_bucket_ptr, st);
+    // rows: order (their chunks follow once the counters have been read)
+    rc = schedule_order(d_indptr, N, T, g.row_order, d_counters, CNT_ROW_BUCKETS, scratch, S, st);
     if (rc != DFGNN_OK) return rc;
 
     // CSC transpose: stable sort of CSR positions by source id
@@ -564,13 +593,36 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
         DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));
     }
 
-    // columns: order and chunks
-    rc = build_schedule(g.t_indptr, N, T, C, g.col_order, g.col_chunk_ptr, g.col_chunks, d_counters, CNT_COL_BUCKETS,
-                        CNT_COL_CHUNKS, scratch, S, &g.n_super_cols, &g.n_col_chunks, g.col_bucket_ptr, st);
+    // columns: order
+    rc = schedule_order(g.t_indptr, N, T, g.col_order, d_counters, CNT_COL_BUCKETS, scratch, S, st);
     if (rc != DFGNN_OK) return rc;
-    int near = 0;
-    DFGNN_HIP(hipMemcpyAsync(&near, d_counters + CNT_NEAR, sizeof(int), hipMemcpyDeviceToHost, st));
+
+    // one read-back of all counters: where the degree classes start (and with that the super rows and
+    // columns), and the locality sample
+    int host_counters[CNT_TOTAL];
+    DFGNN_HIP(hipMemcpyAsync(host_counters, d_counters, sizeof(host_counters), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
+    for (int k = 0; k < 36; ++k) {
+        g.row_bucket_ptr[k] = N > 0 ? host_counters[CNT_ROW_BUCKETS + k] : 0;
+        g.col_bucket_ptr[k] = N > 0 ? host_counters[CNT_COL_BUCKETS + k] : 0;
+    }
+    g.n_super_rows = g.row_bucket_ptr[1];
+    g.n_super_cols = g.col_bucket_ptr[1];
+    const int near = host_counters[CNT_NEAR];
+    if (g.n_super_rows > 0 || g.n_super_cols > 0) {
+        const int64_t max_chunks = chunk_capacity(E, T, C);
+        rc = schedule_chunks(d_indptr, g.n_super_rows, C, g.row_order, g.row_chunk_ptr, g.row_chunks, max_chunks, d_counters,
+                             CNT_ROW_CHUNKS, scratch, S, st);
+        if (rc != DFGNN_OK) return rc;
+        rc = schedule_chunks(g.t_indptr, g.n_super_cols, C, g.col_order, g.col_chunk_ptr, g.col_chunks, max_chunks,
+                             d_counters, CNT_COL_CHUNKS, scratch, S, st);
+        if (rc != DFGNN_OK) return rc;
+        int n_chunks[4] = {0, 0, 0, 0};  // counters CNT_ROW_CHUNKS .. CNT_COL_CHUNKS
+        DFGNN_HIP(hipMemcpyAsync(n_chunks, d_counters + CNT_ROW_CHUNKS, 3 * sizeof(int), hipMemcpyDeviceToHost, st));
+        DFGNN_HIP(hipStreamSynchronize(st));
+        g.n_row_chunks = n_chunks[0];
+        g.n_col_chunks = n_chunks[CNT_COL_CHUNKS - CNT_ROW_CHUNKS];
+    }
     // at least half of the sampled edges stay inside the window: runs of kXcdGroup workgroups share an XCD
     const int64_t samples = E > 0 ? (E + locality_stride - 1) / locality_stride : 0;
     g.xcd_group = (!(flags & DFGNN_SCHED_NO_XCD_GROUPS) && samples > 0 && 2 * (int64_t)near >= samples) ? kXcdGroup : 0;
