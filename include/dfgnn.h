@@ -81,6 +81,12 @@ typedef struct {
  * neighbours share an L2.  With this bit workgroups are dealt round-robin for every graph.  Results are
  * bit-identical either way. */
 #define DFGNN_SCHED_NO_XCD_GROUPS 16
+/* Forward-only graph (inference): dfgnn_graph_create builds neither the CSC transpose nor the column
+ * schedule, which are most of its work and the two edge-sized arrays of its metadata
+ * (dfgnn_graph_meta_bytes shrinks accordingly).  dfgnn_forward*, dfgnn_attention_weights and
+ * dfgnn_graph_set_batch work as usual; dfgnn_backward* return EINVAL; the CSC items of dfgnn_graph_query
+ * have count 0. */
+#define DFGNN_SCHED_FORWARD_ONLY 32
 
 /* One layer call's model description. */
 typedef struct {

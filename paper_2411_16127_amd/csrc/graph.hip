@@ -388,15 +388,16 @@ MetaLayout meta_layout(int64_t N, int64_t E, int T, int C, int flags) {
     MetaLayout L{};
     size_t off = 0;
     auto take = [&](int64_t count) { size_t o = off; off += align_up((size_t)(count > 0 ? count : 1) * sizeof(int32_t)); return o; };
+    const bool fwd_only = flags & DFGNN_SCHED_FORWARD_ONLY;  // no CSC, no column schedule
     L.row_order = take(N);
-    L.col_order = take(N);
-    L.t_indptr = take(N + 1);
-    L.t_indices = take(E);
-    L.t_eid = take(E);
+    L.col_order = take(fwd_only ? 0 : N);
+    L.t_indptr = take(fwd_only ? 0 : N + 1);
+    L.t_indices = take(fwd_only ? 0 : E);
+    L.t_eid = take(fwd_only ? 0 : E);
     L.row_chunk_ptr = take(super_capacity(E, T) + 1);
     L.row_chunks = take(3 * chunk_capacity(E, T, C));
-    L.col_chunk_ptr = take(super_capacity(E, T) + 1);
-    L.col_chunks = take(3 * chunk_capacity(E, T, C));
+    L.col_chunk_ptr = take(fwd_only ? 0 : super_capacity(E, T) + 1);
+    L.col_chunks = take(fwd_only ? 0 : 3 * chunk_capacity(E, T, C));
     L.counters = take(CNT_TOTAL);
     L.edge_row = take((flags & DFGNN_SCHED_SCORES_IN_MEMORY) ? E : 0);
     L.total = off;
@@ -439,7 +440,8 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
         DFGNN_REQUIRE(sched->super_threshold >= 0 && sched->chunk_edges >= 0, DFGNN_EINVAL,
                       "negative scheduling parameter");
         DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH |
-                                         DFGNN_SCHED_SCORES_IN_MEMORY | DFGNN_SCHED_NO_XCD_GROUPS)) == 0,
+                                         DFGNN_SCHED_SCORES_IN_MEMORY | DFGNN_SCHED_NO_XCD_GROUPS |
+                                         DFGNN_SCHED_FORWARD_ONLY)) == 0,
                       DFGNN_EINVAL, "unknown scheduling flag 0x%x", sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;
@@ -567,7 +569,21 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
 
     // CSC transpose: stable sort of CSR positions by source id
     int locality_stride = 1;
-    if (E > 0) {
+    const bool fwd_only = flags & DFGNN_SCHED_FORWARD_ONLY;
+    if (fwd_only) {
+        g.col_order = g.t_indptr = g.t_indices = g.t_eid = g.col_chunk_ptr = g.col_chunks = nullptr;
+        if (E > 0) {  // the COO row array is still needed for the locality sample
+            int* edge_row = g.edge_row ? g.edge_row : (int*)(scratch + S.vals);
+            const int64_t row_threads = (E + kRowsPerThread - 1) / kRowsPerThread;
+            hipLaunchKernelGGL(k_edge_rows, dim3((unsigned)((row_threads + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr,
+                               (int)N, (int)E, edge_row);
+            locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
+            const int64_t samples = (E + locality_stride - 1) / locality_stride;
+            hipLaunchKernelGGL(k_edge_locality, dim3((unsigned)((samples + tpb - 1) / tpb)), dim3(tpb), 0, st, edge_row,
+                               d_indices, (int)E, locality_stride, d_counters + CNT_NEAR);
+            DFGNN_HIP(hipGetLastError());
+        }
+    } else if (E > 0) {
         int bits = 1;
         while (((int64_t)1 << bits) < N) ++bits;
         const uint32_t* sorted = nullptr;
@@ -594,8 +610,10 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     }
 
     // columns: order
-    rc = schedule_order(g.t_indptr, N, T, g.col_order, d_counters, CNT_COL_BUCKETS, scratch, S, st);
-    if (rc != DFGNN_OK) return rc;
+    if (!fwd_only) {
+        rc = schedule_order(g.t_indptr, N, T, g.col_order, d_counters, CNT_COL_BUCKETS, scratch, S, st);
+        if (rc != DFGNN_OK) return rc;
+    }
 
     // one read-back of all counters: where the degree classes start (and with that the super rows and
     // columns), and the locality sample
@@ -604,7 +622,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     DFGNN_HIP(hipStreamSynchronize(st));
     for (int k = 0; k < 36; ++k) {
         g.row_bucket_ptr[k] = N > 0 ? host_counters[CNT_ROW_BUCKETS + k] : 0;
-        g.col_bucket_ptr[k] = N > 0 ? host_counters[CNT_COL_BUCKETS + k] : 0;
+        g.col_bucket_ptr[k] = (N > 0 && !fwd_only) ? host_counters[CNT_COL_BUCKETS + k] : 0;
     }
     g.n_super_rows = g.row_bucket_ptr[1];
     g.n_super_cols = g.col_bucket_ptr[1];
@@ -776,8 +794,9 @@ extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr,
         const dim3 grid((unsigned)((g->N + tpb - 1) / tpb));
         hipLaunchKernelGGL(k_batch_masks, grid, dim3(tpb), 0, st, d_batch_ptr, (int)n_graphs, g->indptr, g->indices,
                            (int)g->N, words, mask, flags);
-        hipLaunchKernelGGL(k_batch_masks, grid, dim3(tpb), 0, st, d_batch_ptr, (int)n_graphs, g->t_indptr, g->t_indices,
-                           (int)g->N, words, mask_t, flags);
+        if (!(g->flags & DFGNN_SCHED_FORWARD_ONLY))  // the column masks serve the backward kernels only
+            hipLaunchKernelGGL(k_batch_masks, grid, dim3(tpb), 0, st, d_batch_ptr, (int)n_graphs, g->t_indptr, g->t_indices,
+                               (int)g->N, words, mask_t, flags);
         DFGNN_HIP(hipMemcpyAsync(host, flags, sizeof(int), hipMemcpyDeviceToHost, st));
         DFGNN_HIP(hipStreamSynchronize(st));
     }
@@ -811,10 +830,10 @@ extern "C" int dfgnn_graph_query(const dfgnn_graph* g, int what, const void** d_
     case DFGNN_Q_ROW_ORDER: p = g->row_order; c = g->N; break;
     case DFGNN_Q_ROW_CHUNK_PTR: p = g->row_chunk_ptr; c = g->n_super_rows ? g->n_super_rows + 1 : 0; break;
     case DFGNN_Q_ROW_CHUNKS: p = g->row_chunks; c = 3 * (int64_t)g->n_row_chunks; break;
-    case DFGNN_Q_T_INDPTR: p = g->t_indptr; c = g->N + 1; break;
-    case DFGNN_Q_T_INDICES: p = g->t_indices; c = g->E; break;
-    case DFGNN_Q_T_EID: p = g->t_eid; c = g->E; break;
-    case DFGNN_Q_COL_ORDER: p = g->col_order; c = g->N; break;
+    case DFGNN_Q_T_INDPTR: p = g->t_indptr; c = p ? g->N + 1 : 0; break;  // absent in a forward-only graph
+    case DFGNN_Q_T_INDICES: p = g->t_indices; c = p ? g->E : 0; break;
+    case DFGNN_Q_T_EID: p = g->t_eid; c = p ? g->E : 0; break;
+    case DFGNN_Q_COL_ORDER: p = g->col_order; c = p ? g->N : 0; break;
     case DFGNN_Q_COL_CHUNK_PTR: p = g->col_chunk_ptr; c = g->n_super_cols ? g->n_super_cols + 1 : 0; break;
     case DFGNN_Q_COL_CHUNKS: p = g->col_chunks; c = 3 * (int64_t)g->n_col_chunks; break;
     case DFGNN_Q_N_SUPER_ROWS: c = g->n_super_rows; break;

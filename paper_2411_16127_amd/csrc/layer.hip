@@ -347,6 +347,8 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     if (rc != DFGNN_OK) return rc;
     const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, agnn = layer->model == DFGNN_AGNN,
                v2 = layer->model == DFGNN_GATV2;
+    DFGNN_REQUIRE(!(graph->flags & DFGNN_SCHED_FORWARD_ONLY), DFGNN_EINVAL,
+                  "the graph was created forward-only (DFGNN_SCHED_FORWARD_ONLY): it has no CSC for the backward pass");
     if (graph->N == 0) {  // no nodes: node tensors have no elements and may be NULL; parameter gradients are zero
         // cleared by a kernel, not a memset: layer calls may be recorded into a HIP graph
         if ((gat || v2) && d_a_l) launch_zero(d_a_l, layer->H * layer->D, (hipStream_t)stream);
