@@ -67,3 +67,44 @@ def test_every_planted_mistake_fails_a_pin(tmp_path):
         survived = list(pool.map(lambda m: pins_pass(original.replace(m[1][0], m[1][1]), str(tmp_path), str(m[0])),
                                  enumerate(MUTANTS)))
     assert not any(survived), [MUTANTS[i] for i, s in enumerate(survived) if s]
+
+
+SCHED_SRC = os.path.join(ROOT, "oracle", "sched_oracle.py")
+SCHED_MUTANTS = [
+    # super rows from T + 1 instead of T (in the sort key; in the count)
+    ("key = np.where(deg >= T, 0, 33 - _bit_length(deg))", "key = np.where(deg > T, 0, 33 - _bit_length(deg))"),
+    ("n_super = int(np.count_nonzero(deg >= T))", "n_super = int(np.count_nonzero(deg > T))"),
+    # equal keys in descending instead of ascending id order (rows; CSC entries)
+    ('order = np.argsort(key, kind="stable")',
+     'order = np.argsort(key)[::-1][np.argsort(key[np.argsort(key)[::-1]], kind="stable")]'),
+    ('t_eid = np.argsort(indices, kind="stable")',
+     't_eid = np.argsort(indices, kind="stable")[::-1][np.argsort(indices[np.argsort(indices, kind="stable")[::-1]], kind="stable")]'),
+    # chunk count rounded down; last chunk not clipped; chunk stride off by one; short rows before long ones
+    ("n_chunks = -(-deg[sup] // C)", "n_chunks = deg[sup] // C"),
+    ("chunks[pos] = (row, b, min(b + C, indptr[row + 1]))", "chunks[pos] = (row, b, b + C)"),
+    ("b = indptr[row] + c * C", "b = indptr[row] + c * (C - 1)"),
+    ("33 - _bit_length(deg)", "_bit_length(deg)"),
+    # CSC lists sources instead of destinations
+    ('"t_indices": rows[t_eid]', '"t_indices": indices[t_eid]'),
+]
+
+
+def sched_pins_pass(source: str, workdir, tag: str) -> bool:
+    py_file = os.path.join(workdir, f"sched_oracle_{tag}.py")
+    with open(py_file, "w") as f:
+        f.write(source)
+    env = dict(os.environ, DFGNN_SCHED_ORACLE_FILE=py_file)
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_sched_oracle.py"), "-x", "-q",
+                          "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    return run.returncode == 0
+
+
+def test_every_planted_mistake_in_the_metadata_oracle_fails_a_pin(tmp_path):
+    original = open(SCHED_SRC).read()
+    for old, _ in SCHED_MUTANTS:
+        assert original.count(old) >= 1, f"the metadata oracle no longer contains: {old}"
+    assert sched_pins_pass(original, str(tmp_path), "unchanged")
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        survived = list(pool.map(lambda m: sched_pins_pass(original.replace(m[1][0], m[1][1]), str(tmp_path), str(m[0])),
+                                 enumerate(SCHED_MUTANTS)))
+    assert not any(survived), [SCHED_MUTANTS[i] for i, s in enumerate(survived) if s]
