@@ -109,33 +109,43 @@ def compulsory_bytes(w, graph, edge_bias=False):
     return fwd + bwd
 
 
-def sample_subproblem(graph, feats, target_edges: int, seed: int):
-    """Random rows of the graph (whole neighbourhoods) until ~target_edges edges, relabelled compactly.
+def sample_subproblem(graph, feats, target_edges: int, seed: int, n_cols: int = 8, max_out_degree: int = 64):
+    """Random rows of the graph (whole neighbourhoods) until ~target_edges edges, relabelled compactly, plus
+    a few random source nodes of small out-degree with their own row and every row they feed, so that the
+    sub-problem also holds complete column-side gradients (dK, dV, or dWh / dh) for those nodes.
 
     The sampled rows keep their neighbour lists; nodes that only appear as neighbours become empty rows.
+    Returns the sub-graph, its features, the sampled rows and the complete columns (original and new ids).
     """
     from dfgnn_synth import from_edge_list
     rng = np.random.default_rng(seed)
     deg = graph.degrees()
     order = rng.permutation(graph.n)
     take = int(np.searchsorted(np.cumsum(deg[order]), target_edges)) + 1
-    rows = np.sort(order[:take])
+    rows = order[:take]
+    out_deg = np.bincount(graph.indices, minlength=graph.n)
+    cand = order[::-1][:4096]
+    cols = np.sort(cand[(out_deg[cand] > 0) & (out_deg[cand] <= max_out_degree)][:n_cols])
+    if cols.size:
+        edge_pos = np.flatnonzero(np.isin(graph.indices, cols))
+        feed = np.searchsorted(graph.indptr, edge_pos, side="right") - 1  # destination row of those edges
+        rows = np.concatenate([rows, cols, feed])
+    rows = np.unique(rows)
     starts, ends = graph.indptr[rows].astype(np.int64), graph.indptr[rows + 1].astype(np.int64)
     pos = np.concatenate([np.arange(a, b_) for a, b_ in zip(starts, ends)]) if rows.size else np.empty(0, np.int64)
     src = graph.indices[pos].astype(np.int64)
-    dst = np.repeat(rows, (ends - starts))
     nodes, inv = np.unique(np.concatenate([rows, src]), return_inverse=True)
     new_rows = inv[:rows.size]
     new_src = inv[rows.size:]
     new_dst = np.repeat(new_rows, (ends - starts))
     sub = from_edge_list(nodes.size, new_src, new_dst, sort=False)
     sub_feats = {k: (v[nodes] if v.ndim == 3 else v) for k, v in feats.items()}
-    return sub, sub_feats, rows, new_rows, int(src.size)
+    return sub, sub_feats, rows, new_rows, cols, np.searchsorted(nodes, cols), int(src.size)
 
 
 def cpu_baseline(w, graph, feats, target_edges: int):
     import oracle
-    sub, sf, rows, new_rows, n_edges = sample_subproblem(graph, feats, target_edges, seed=w.seed + 7)
+    sub, sf, rows, new_rows, cols, new_cols, n_edges = sample_subproblem(graph, feats, target_edges, seed=w.seed + 7)
     L = oracle.Layer(w.model, w.H, w.D, scale=w.scale, neg_slope=w.neg_slope, eps=w.eps)
     kw = dict(x=sf["q"] if w.model == "gt" else sf["feat"], k=sf.get("k"), v=sf.get("v"), a_l=sf.get("a_l"),
               a_r=sf.get("a_r"))
@@ -151,7 +161,38 @@ def cpu_baseline(w, graph, feats, target_edges: int):
     info = {"value": n_edges / secs / 1e9, "unit": "GEdges/s", "cores": 1, "kind": "oracle",
             "sample": f"{rows.size} random rows with their whole neighbourhoods ({n_edges} edges) of the same graph, "
                       f"fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, fp64, one thread of {os.cpu_count()} host cores"}
-    return info, (rows, new_rows, fw, bw)
+    return info, (rows, new_rows, cols, new_cols, fw, bw)
+
+
+def sample_parity(w, timed, sample) -> dict:
+    """Spot check of the buffers the timed steps left behind against the oracle's sub-problem: the output and
+    the statistics of the sampled rows, the gradients that are complete inside the sub-problem (row-side ones
+    of the sampled rows, every gradient of the complete columns).  Bounds as in the parity tests: fp32
+    1e-5 + 1e-4 |ref|, bf16 1e-5 + 2e-2 |ref|, fp16 1e-5 + 2e-3 |ref|."""
+    import torch
+    rows, new_rows, cols, new_cols, fw, bw = sample
+    rtol = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-3}[w.dtype]
+    at_rows = {"out": fw["out"], "row_max": fw["row_max"], "row_sum": fw["row_sum"]}
+    at_cols = {}
+    if w.model in ("gt", "gatv2"):
+        at_rows["d_x"] = bw["d_x"]
+        at_cols["d_k"] = bw["d_k"]
+        if w.model == "gt":
+            at_cols["d_v"] = bw["d_v"]
+    else:  # GAT, AGNN: the gradient of a node's features has a row-side and a column-side part
+        at_cols["d_x"] = bw["d_x"]
+    checked = {}
+    for where, ids, new_ids in ((at_rows, rows, new_rows), (at_cols, cols, new_cols)):
+        pick = torch.from_numpy(np.asarray(ids)).cuda()
+        for name, ref_all in where.items():
+            if ids.size == 0:
+                continue
+            got = timed[name][pick].float().cpu().numpy().astype(np.float64)
+            ref = ref_all[new_ids]
+            fin = np.isfinite(ref)
+            ok = np.array_equal(fin, np.isfinite(got)) and bool(np.all(np.abs(got[fin] - ref[fin]) <= 1e-5 + rtol * np.abs(ref[fin])))
+            checked[name] = ok
+    return checked
 
 
 def main() -> int:
@@ -193,8 +234,7 @@ def main() -> int:
     import torch
     import paper_2411_16127_amd as dfgnn
     from paper_2411_16127_amd import build as lib_build
-    if not os.path.exists(lib_build.lib_path()):  # load what is built; build only if nothing is
-        lib_build.build()
+    lib_build.require_current()  # load what is built; build only if nothing is; refuse a stale library
     from dfgnn_synth import make_workload, make_features
     from dfgnn_synth.workloads import make_graph
 
@@ -224,7 +264,7 @@ def main() -> int:
                               (1 if args.no_short_rows else 0) | (2 if args.no_dense_batch else 0) |
                               (4 if args.force_dense_batch else 0) | (8 if args.scores_in_memory else 0) |
                               (16 if args.no_xcd_groups else 0))
-    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[w.dtype]
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])
     k = dev(feats["k"]) if w.model in ("gt", "gatv2") else None
@@ -390,7 +430,7 @@ def main() -> int:
         "metric": "fused AT-GNN layer fwd+bwd GEdges/s at 1 GPU; achieved HBM GB/s vs peak",
         "value": round(gedges, 4), "unit": "GEdges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "dtype": "f32" if w.dtype == "f32" else f"{w.dtype} storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[w.name] + (" VARIANT " + ",".join(args.set) if args.set else "") + (" + edge term" if args.edge_bias else ""), "N": graph.n, "E": graph.nnz, "H": w.H, "D": w.D,
                    "super_threshold": T, "chunk_edges": C, "xcd_group": g.query("n_xcd_group"), "stands_in_for": w.stands_in_for},
         "roofline": roofline,
@@ -439,12 +479,11 @@ def main() -> int:
         log(f"cold caches: fwd {np.median(f_cold):.3f} + bwd {np.median(b_cold):.3f} ms (warm {fwd_ms:.3f} + {bwd_ms:.3f})")
     if not args.no_cpu_baseline and not args.edge_bias:
         target = args.cpu_edges or {"cfg1": 1 << 30, "cfg2": 1 << 30, "cfg3": 1 << 30, "cfg4": 8000000, "cfg5": 10000000}[w.name]
-        info, (rows, new_rows, fw, bw) = cpu_baseline(w, graph, feats, target)
-        # the sampled rows double as a parity spot check of the buffers that were just timed
-        got = out[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
-        ref = fw["out"][new_rows]
-        tol = (1e-5 + 1e-4 * np.abs(ref)) if w.dtype == "f32" else 2e-2 * (np.abs(ref) + np.sqrt(np.mean(ref ** 2)))
-        info["sample_parity_ok"] = bool(np.all(np.abs(got - ref) <= tol))
+        info, sample = cpu_baseline(w, graph, feats, target)
+        # the sample doubles as a parity spot check of the buffers that were just timed (output, statistics, gradients)
+        checked = sample_parity(w, {"out": out, "row_max": row_max, "row_sum": row_sum, "d_x": d_x, "d_k": d_k, "d_v": d_v}, sample)
+        info["sample_parity"] = checked
+        info["sample_parity_ok"] = bool(checked) and all(checked.values())
         info["gpu_over_cpu"] = round(gedges / info["value"], 1)
         info["value"] = float(f"{info['value']:.6g}")
         result["cpu_baseline"] = info

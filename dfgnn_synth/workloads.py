@@ -23,7 +23,7 @@ class Workload:
     model: str  # 'gt' | 'gat' | 'agnn' | 'gatv2'
     H: int
     D: int
-    dtype: str  # 'f32' | 'bf16' (storage type of node tensors)
+    dtype: str  # 'f32' | 'bf16' | 'f16' (storage type of node tensors)
     scale: float  # GT: multiplies q.k ; AGNN: beta ; GAT: unused (1.0)
     neg_slope: float = 0.2
     eps: float = 1e-12
@@ -106,7 +106,7 @@ def _normal(seed: int, stream: int, shape, std: float = 1.0) -> np.ndarray:
 
 
 def make_features(w: Workload, n: int, seed: Optional[int] = None, threads: int = 4) -> Dict[str, np.ndarray]:
-    """Node tensors [n, H, D] float32 (bf16 workloads: values already rounded to bf16).
+    """Node tensors [n, H, D] float32 (bf16 / f16 workloads: values already rounded to that type).
 
     GT: q, k, v;  GAT: feat (=Wh), a_l, a_r [H, D] fp32;  AGNN: feat (=h);  GATv2: feat (destination-side
     projection), k (source-side projection), a_l (= a) [H, D] fp32.
@@ -134,6 +134,8 @@ def make_features(w: Workload, n: int, seed: Optional[int] = None, threads: int 
         x = _normal(seed_, stream, shp, std)
         if w.dtype == "bf16" and key in ("q", "k", "v", "feat", "d_out"):
             x = round_to_bf16(x)
+        if w.dtype == "f16" and key in ("q", "k", "v", "feat", "d_out"):
+            x = x.astype(np.float16).astype(np.float32)  # round to nearest even
         return key, x
 
     with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:

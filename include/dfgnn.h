@@ -14,7 +14,9 @@
  *  - Every pointer named d_* or documented as "device" is GPU global memory owned by the caller; the
  *    library never allocates or frees device memory and keeps only a small host-side handle.
  *  - Node tensors are [N, H, D] row-major (one node's H*D values contiguous), in the layer's dtype
- *    (fp32 or bf16); statistics and attention vectors are fp32.  Device pointers must be 16-byte aligned.
+ *    (fp32, bf16 or fp16; the 16-bit types are storage types: all arithmetic and accumulation is fp32 and
+ *    results are rounded to nearest even when stored); statistics and attention vectors are fp32.  Device
+ *    pointers must be 16-byte aligned.
  *  - Row i of the CSR is destination i; indices[indptr[i] .. indptr[i+1]) are its in-neighbours
  *    (sources).  Sources need not be sorted inside a row; repeated edges are separate softmax terms;
  *    empty rows are legal (O = 0, row_max = -inf, row_sum = 0, no gradient contribution).
@@ -44,7 +46,7 @@ typedef enum {
 } dfgnn_status;
 
 typedef enum { DFGNN_GT = 0, DFGNN_GAT = 1, DFGNN_AGNN = 2, DFGNN_GATV2 = 3 } dfgnn_model;
-typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1 } dfgnn_dtype;
+typedef enum { DFGNN_F32 = 0, DFGNN_BF16 = 1, DFGNN_F16 = 2 } dfgnn_dtype;
 
 /*
  * Degree-aware scheduling parameters.  The switch between one fused node-parallel pass and an
@@ -94,8 +96,8 @@ typedef struct {
     int32_t dtype;   /* dfgnn_dtype of node tensors (inputs, outputs and their gradients) */
     int32_t H;       /* heads */
     int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
-                        of two (vec = 4 for fp32, 8 for bf16) and at most 64 (one head fits one wavefront of
-                        16-byte lanes: D <= 256 in fp32, 512 in bf16), and one node tensor (N*H*D elements)
+                        of two (vec = 4 for fp32, 8 for bf16 and fp16) and at most 64 (one head fits one wavefront of
+                        16-byte lanes: D <= 256 in fp32, 512 in bf16 / fp16), and one node tensor (N*H*D elements)
                         must stay below 4 GiB.  Rows of more than 64 such lanes (H*D/vec > 64) are processed
                         in groups of heads, one launch sequence per group.  Other head widths (a classifier
                         layer with 7 outputs, say) are used zero-padded to the next accepted width: zero
@@ -130,6 +132,9 @@ typedef enum {
 const char* dfgnn_status_string(int status);
 const char* dfgnn_last_error(void); /* never NULL; valid until the calling thread's next library call */
 int dfgnn_version(int* major, int* minor);
+/* Hash of the source files, this header and the compiler flags the library was built from (set by the build
+ * script; "unknown" for other builds).  Lets a test harness refuse a library that is older than the sources. */
+const char* dfgnn_build_id(void);
 
 /*
  * Scheduler metadata (the preprocessing step of Sec. 5.3: CSR for the forward pass, CSC for the
@@ -181,6 +186,23 @@ int dfgnn_graph_batch_bytes(int64_t N, int64_t n_graphs, size_t* batch_bytes);
 int dfgnn_graph_set_batch(dfgnn_graph* graph, const int32_t* d_batch_ptr, int64_t n_graphs, void* d_batch,
                           size_t batch_bytes, void* stream);
 int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, int64_t* count);
+
+/*
+ * dfgnn_graph_create and dfgnn_graph_set_batch in one call, for the batch-graph setting of Sec. 5.1, where
+ * the preprocessing of Sec. 5.3 (CSR, CSC, schedule) is paid for every mini-batch and has to cost about
+ * what a training step costs.  Arguments as in those two calls; the result (every metadata array, the
+ * batch tables) is bit for bit what they would produce.  When every graph of the batch has at most 4096
+ * nodes and 262144 edges the metadata is built by one workgroup per graph in three launches with one
+ * synchronisation of `stream` (two when the batch has super rows or columns); other batches, forward-only
+ * graphs and the scores-in-memory comparator go through the two general calls internally.
+ * dfgnn_graph_create itself builds a graph of at most 4096 nodes and 262144 edges (without batch
+ * structure) the same way, in one launch.
+ * Errors: those of dfgnn_graph_create and dfgnn_graph_set_batch.
+ */
+int dfgnn_graph_create_batch(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr, const int32_t* d_indices,
+                             const int32_t* d_batch_ptr, int64_t n_graphs, const dfgnn_sched_params* sched, void* d_meta,
+                             size_t meta_bytes, void* d_batch, size_t batch_bytes, void* d_scratch, size_t scratch_bytes,
+                             void* stream);
 
 /*
  * Bytes of device workspace one forward / one backward call needs for this graph and layer (partial

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     version,
     graph_meta_bytes,
     graph_create,
+    graph_create_batch,
     graph_destroy,
     graph_set_batch,
     graph_batch_bytes,

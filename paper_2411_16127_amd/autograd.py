@@ -5,7 +5,7 @@ from __future__ import annotations
 
 import torch
 
-from .binding import Graph, Layer
+from .binding import Graph, Layer, dtype_name
 
 
 class _FusedConv(torch.autograd.Function):
@@ -50,7 +50,7 @@ def gt_conv(graph: Graph, q, k, v, scale=None, edge_bias=None):
     CSR edge order, if given), applied to v.  [N,H,D]."""
     H, D = q.shape[1], q.shape[2]
     W = _kernel_width(D, q.dtype)
-    layer = Layer("gt", H, W, dtype="bf16" if q.dtype == torch.bfloat16 else "f32",
+    layer = Layer("gt", H, W, dtype=dtype_name(q.dtype),
                   scale=float(D) ** -0.5 if scale is None else float(scale))
     return _FusedConv.apply(graph, layer, _pad(q, W), _pad(k, W), _pad(v, W), None, None, edge_bias)[..., :D]
 
@@ -59,7 +59,7 @@ def gat_conv(graph: Graph, wh, a_l, a_r, neg_slope: float = 0.2):
     """GAT convolution on projected features Wh [N,H,D] with attention vectors a_l, a_r [H,D] (fp32)."""
     H, D = wh.shape[1], wh.shape[2]
     W = _kernel_width(D, wh.dtype)
-    layer = Layer("gat", H, W, dtype="bf16" if wh.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    layer = Layer("gat", H, W, dtype=dtype_name(wh.dtype), neg_slope=float(neg_slope))
     return _FusedConv.apply(graph, layer, _pad(wh, W), None, None, _pad(a_l, W).contiguous(),
                             _pad(a_r, W).contiguous())[..., :D]
 
@@ -69,7 +69,7 @@ def gatv2_conv(graph: Graph, x_dst, x_src, a, neg_slope: float = 0.2):
     the two projections of the node features [N,H,D]; a [H,D] (fp32)."""
     H, D = x_dst.shape[1], x_dst.shape[2]
     W = _kernel_width(D, x_dst.dtype)
-    layer = Layer("gatv2", H, W, dtype="bf16" if x_dst.dtype == torch.bfloat16 else "f32", neg_slope=float(neg_slope))
+    layer = Layer("gatv2", H, W, dtype=dtype_name(x_dst.dtype), neg_slope=float(neg_slope))
     return _FusedConv.apply(graph, layer, _pad(x_dst, W), _pad(x_src, W), None, _pad(a, W).contiguous(), None)[..., :D]
 
 
@@ -78,7 +78,7 @@ class _AgnnConv(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, graph: Graph, h, beta, eps: float):
-        layer = Layer("agnn", h.shape[1], h.shape[2], dtype="bf16" if h.dtype == torch.bfloat16 else "f32",
+        layer = Layer("agnn", h.shape[1], h.shape[2], dtype=dtype_name(h.dtype),
                       scale=float(beta.detach().float().cpu()), eps=eps)
         h = h.contiguous()
         out, row_max, row_sum = graph.forward(layer, h)

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdfgnn.so")
 
 MODEL = {"gt": 0, "gat": 1, "agnn": 2, "gatv2": 3}
-DTYPE = {"f32": 0, "bf16": 1}
+DTYPE = {"f32": 0, "bf16": 1, "f16": 2}
 QUERY = {
     "row_order": 0, "row_chunk_ptr": 1, "row_chunks": 2, "t_indptr": 3, "t_indices": 4, "t_eid": 5,
     "col_order": 6, "col_chunk_ptr": 7, "col_chunks": 8, "n_super_rows": 9, "n_super_cols": 10,
@@ -55,7 +55,7 @@ class Layer:
     model: str          # 'gt' | 'gat' | 'agnn' | 'gatv2'
     H: int
     D: int
-    dtype: str = "f32"  # 'f32' | 'bf16'
+    dtype: str = "f32"  # 'f32' | 'bf16' | 'f16' (storage type of node tensors; arithmetic is fp32)
     scale: float = 1.0  # GT: score scale; AGNN: beta
     neg_slope: float = 0.2
     eps: float = 1e-12
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is not built: run `python -m paper_2411_16127_amd.build` "
                                "(there is no fallback implementation)")
+        import torch  # noqa: F401  (first, so that the process uses the HIP runtime torch ships: device memory and streams come from it)
         L = ctypes.CDLL(_LIB_PATH)
         vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
         L.dfgnn_status_string.restype = ctypes.c_char_p
@@ -88,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_version.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.dfgnn_graph_meta_bytes.argtypes = [i64, i64, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.dfgnn_graph_create_batch.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, i64, vp, vp, sz, vp, sz, vp, sz, vp]
         L.dfgnn_graph_destroy.argtypes = [vp]
         L.dfgnn_graph_set_batch.argtypes = [vp, vp, i64, vp, sz, vp]
         L.dfgnn_graph_batch_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
@@ -101,7 +103,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
-        for name in ("dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
+        for name in ("dfgnn_graph_create_batch", "dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward",
                      "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias", "dfgnn_attention_weights"):
             getattr(L, name).restype = ctypes.c_int
@@ -126,6 +128,15 @@ def version() -> Tuple[int, int]:
 def _check(rc: int, where: str) -> None:
     if rc != 0:
         raise DfgnnError(rc, where)
+
+
+def dtype_name(torch_dtype) -> str:
+    """Layer dtype string of a torch dtype (float32 / bfloat16 / float16)."""
+    import torch
+    try:
+        return {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[torch_dtype]
+    except KeyError:
+        raise ValueError(f"node tensors must be float32, bfloat16 or float16, not {torch_dtype}") from None
 
 
 def _ptr(t) -> ctypes.c_void_p:
@@ -165,6 +176,18 @@ def graph_create(N: int, E: int, d_indptr, d_indices, sched: Optional[SchedParam
     _check(lib().dfgnn_graph_create(ctypes.byref(handle), N, E, _ptr(d_indptr), _ptr(d_indices),
                                     ctypes.byref(cs) if cs else None, _ptr(d_meta), meta_bytes, _ptr(d_scratch),
                                     scratch_bytes, _stream(stream)), "dfgnn_graph_create")
+    return handle
+
+
+def graph_create_batch(N: int, E: int, d_indptr, d_indices, d_batch_ptr, n_graphs: int, sched: Optional[SchedParams],
+                       d_meta, meta_bytes: int, d_batch, batch_bytes: int, d_scratch, scratch_bytes: int,
+                       stream=None) -> ctypes.c_void_p:
+    handle = ctypes.c_void_p()
+    cs = sched._c() if sched else None
+    _check(lib().dfgnn_graph_create_batch(ctypes.byref(handle), N, E, _ptr(d_indptr), _ptr(d_indices), _ptr(d_batch_ptr),
+                                          n_graphs, ctypes.byref(cs) if cs else None, _ptr(d_meta), meta_bytes,
+                                          _ptr(d_batch), batch_bytes, _ptr(d_scratch), scratch_bytes, _stream(stream)),
+           "dfgnn_graph_create_batch")
     return handle
 
 
@@ -270,16 +293,18 @@ class Graph:
         meta_b, scratch_b = graph_meta_bytes(self.N, self.E, sched)
         self.meta = torch.empty(meta_b, dtype=torch.uint8, device=self.device)
         scratch = torch.empty(scratch_b, dtype=torch.uint8, device=self.device)
-        self.handle = graph_create(self.N, self.E, self.indptr, self.indices, sched, self.meta, meta_b, scratch,
-                                   scratch_b, stream)
-        del scratch
         self.batch_ptr = None
-        if batch_ptr is not None:
+        if batch_ptr is None:
+            self.handle = graph_create(self.N, self.E, self.indptr, self.indices, sched, self.meta, meta_b, scratch,
+                                       scratch_b, stream)
+        else:  # metadata and batch structure in one call
             self.batch_ptr = torch.as_tensor(batch_ptr, dtype=torch.int32).to(self.device).contiguous()
             n_graphs = int(self.batch_ptr.numel() - 1)
             nbytes = graph_batch_bytes(self.N, n_graphs)
             self.batch_meta = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-            graph_set_batch(self.handle, self.batch_ptr, n_graphs, self.batch_meta, nbytes, stream)
+            self.handle = graph_create_batch(self.N, self.E, self.indptr, self.indices, self.batch_ptr, n_graphs, sched,
+                                             self.meta, meta_b, self.batch_meta, nbytes, scratch, scratch_b, stream)
+        del scratch
         self._ws: Dict[tuple, object] = {}
 
     @classmethod
@@ -372,7 +397,7 @@ class Graph:
     def _check_tensors(self, layer: Layer, node_tensors, head_tensors=(), stat_tensors=()) -> None:
         """Host-side shape / dtype checks: the C ABI carries no tensor sizes, so a wrong one would fault."""
         import torch
-        want = torch.float32 if layer.dtype == "f32" else torch.bfloat16
+        want = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[layer.dtype]
         for t in node_tensors:
             if t is None:
                 continue

@@ -89,6 +89,13 @@ extern "C" const char* dfgnn_status_string(int status) {
 
 extern "C" const char* dfgnn_last_error(void) { return dfgnn::g_error; }
 
+#ifndef DFGNN_BUILD_ID
+#define DFGNN_BUILD_ID "unknown"
+#endif
+// the tag makes the id readable from the library file without loading it
+static const char kBuildTag[] = "DFGNN_BUILD_ID=" DFGNN_BUILD_ID;
+extern "C" const char* dfgnn_build_id(void) { return kBuildTag + sizeof("DFGNN_BUILD_ID=") - 1; }
+
 extern "C" int dfgnn_version(int* major, int* minor) {
     if (major) *major = 0;
     if (minor) *minor = 1;

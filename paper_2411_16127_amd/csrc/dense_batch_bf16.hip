@@ -80,11 +80,6 @@ __device__ inline s16x4 transpose_tile(uint16_t* patch, s16x4 frag, int l16, int
     __builtin_amdgcn_wave_barrier();
     return z;
 }
-__device__ inline s16x4 pack_bf16x4(const float (&x)[4]) {
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    return __builtin_bit_cast(s16x4, u32x2{cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3])});
-}
-
 template <int KB> __device__ inline f32x4 tile_product16(const s16x4 (&a)[KB], const s16x4 (&b)[KB]) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -155,9 +150,9 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense16_forward(const Dens
             p[r] = ((c2.bits >> r) & 1u) ? fast_exp2(fmaf(s[r], a.c_score, -m)) : 0.f;
             l += p[r];
         }
-        const s16x4 pf = pack_bf16x4(p);
+        const SplitFrag pf = split_bf16x4(p[0], p[1], p[2], p[3]);  // bf16 head + remainder: the sum l above is of the fp32 weights
 #pragma unroll
-        for (int nt = 0; nt < KB; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pf, c2.vc[nt], acc[nt], 0, 0, 0);
+        for (int nt = 0; nt < KB; ++nt) acc[nt] = mfma_split(pf, c2.vc[nt], acc[nt]);
         c2 = n2;
     }
     l = sum_q(l);
@@ -206,6 +201,7 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense16_backward_rows(cons
         lse = a.row_max[(size_t)(u.base + i) * a.H + u.h] * kLog2e + fast_log2(a.row_sum[(size_t)(u.base + i) * a.H + u.h]);
     f32x4 acc_t[KB], acc_p[KB];  // sum_j p dP k_j and sum_j p k_j
     float dsum = 0.f;            // this lane's share of delta_i = sum_j p dP
+    int edges = 0;               // this lane's share of the row's neighbour count
 #pragma unroll
     for (int nt = 0; nt < KB; ++nt) { acc_t[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; acc_p[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     // operands of tile jt + 1 are requested before tile jt is worked on (a tile past the end reads as zeros)
@@ -233,6 +229,7 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense16_backward_rows(cons
             t[r] = p[r] * dp[r];
             dsum += t[r];
         }
+        edges += __popc(c.bits & 0xfu);
         const SplitFrag pf = split_bf16x4(p[0], p[1], p[2], p[3]);
         const SplitFrag tf = split_bf16x4(t[0], t[1], t[2], t[3]);
 #pragma unroll
@@ -244,6 +241,7 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense16_backward_rows(cons
         c = nx;
     }
     const float delta = sum_q(dsum);
+    const int degree = (int)sum_q((float)edges);  // at most 512 neighbours: exact in fp32
     if (q == 0 && i < u.n) {
         f32x2 st = {lse, delta};
         *reinterpret_cast<f32x2*>(a.stats + 2 * ((size_t)(u.base + i) * a.H + u.h)) = st;
@@ -251,12 +249,15 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense16_backward_rows(cons
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const float dr = __shfl(delta, 4 * q + r);  // delta of result row 4q + r
+        // a row with a single neighbour has dS = 0 exactly; the difference below would leave the fp32
+        // rounding of two equal terms instead
+        const bool single = __shfl(degree, 4 * q + r) <= 1;
         const int row = u.t * 16 + 4 * q + r;
         if (row < u.n) {
 #pragma unroll
             for (int nt = 0; nt < KB; ++nt)
                 a.d_q[(size_t)(u.base + row) * a.HD + u.h * D + nt * 16 + l16] =
-                    to_bf16(a.scale * (acc_t[nt][r] - dr * acc_p[nt][r]));
+                    to_bf16(single ? 0.f : a.scale * (acc_t[nt][r] - dr * acc_p[nt][r]));
         }
     }
 }

@@ -6,7 +6,8 @@
 // All integer work; results are unique and are compared bit for bit with a CPU reference in the tests.
 // Primitives (exclusive scan, stable LSD radix sort) are written here so that buffer sizes are plain
 // formulas and no device query is needed to size them.
-#include "common.hpp"
+#include "graph_device.hpp"
+#include "graph_local.hpp"
 
 #include <cstring>
 #include <new>
@@ -152,18 +153,6 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_hist(const uint32_t* __r
     counts[threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];
 }
 
-// lanes of the wave whose (valid) digit equals this lane's digit
-__device__ inline unsigned long long match_digit(unsigned d, bool valid) {
-    unsigned long long mask = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const unsigned long long bal = __ballot(valid && bit);
-        mask &= bit ? bal : ~bal;
-    }
-    return mask;
-}
-
 // Each wave owns 1024 consecutive keys of the tile and places them in index order, so equal digits keep
 // their relative order (stability).  values_in == nullptr means value = index (first pass).
 __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t* __restrict__ keys_in,
@@ -212,6 +201,10 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t* 
             vals_out[first + rank] = v[s];
             if (rank == 0) hist[wave][d] = first + __popcll(same);
         }
+        // the next round reads the running offsets this round's first lanes just wrote: keep the LDS
+        // accesses of the two rounds in program order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -252,7 +245,6 @@ static int radix_sort_pairs(const uint32_t* keys_in, int64_t n, int bits, uint32
 // ------------------------------------------------------------------------------------------------
 // scheduler kernels
 // ------------------------------------------------------------------------------------------------
-enum { CNT_ROW_CHUNKS = 1, CNT_COL_CHUNKS = 3, CNT_ERROR = 8, CNT_NEAR = 4, CNT_BATCH = 9, CNT_BATCH_MAX = 10, CNT_BATCH_PAIRS = 12, CNT_ROW_BUCKETS = 16, CNT_COL_BUCKETS = 56, CNT_TOTAL = 96 };
 
 __global__ void k_validate(const int* __restrict__ indptr, const int* __restrict__ indices, int n, int e, int* flags) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -276,7 +268,7 @@ __global__ void k_degree_keys(const int* __restrict__ ptr, int n, int T, uint32_
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int deg = ptr[i + 1] - ptr[i];
-    keys[i] = deg >= T ? 0u : (uint32_t)(33 - (32 - __clz(deg)));
+    keys[i] = degree_key(deg, T);
 }
 
 // out[k] = position of the first key >= k in the sorted key array, k = 0..35
@@ -362,7 +354,6 @@ __global__ void k_gather_rows(const int* __restrict__ t_eid, const int* __restri
 // clustered orderings) reuse neighbour rows among rows that are close in the work list; the layer launches
 // then keep runs of the list on one XCD so that the reuse happens in that XCD's L2.
 constexpr int kLocalitySamples = 1 << 16;
-constexpr int kLocalityWindow = 4096;
 __global__ void k_edge_locality(const int* __restrict__ edge_row, const int* __restrict__ indices, int e, int stride,
                                 int* __restrict__ near) {
     const int64_t p = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * stride;
@@ -507,10 +498,22 @@ extern "C" int dfgnn_graph_meta_bytes(int64_t N, int64_t E, const dfgnn_sched_pa
     return DFGNN_OK;
 }
 
-extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr,
-                                  const int32_t* d_indices, const dfgnn_sched_params* sched, void* d_meta,
-                                  size_t meta_bytes, void* d_scratch, size_t scratch_bytes, void* stream) {
-    clear_error();
+namespace dfgnn {
+
+// Everything a builder needs: the checked arguments, the layouts of the caller's buffers and the handle
+// under construction (its arrays already point into the metadata buffer).
+struct Build {
+    dfgnn_graph g;
+    MetaLayout M;
+    ScratchLayout S;
+    char* scratch;
+    int* d_counters;
+    hipStream_t st;
+};
+
+static int prepare_build(Build& B, dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr,
+                         const int32_t* d_indices, const dfgnn_sched_params* sched, void* d_meta, size_t meta_bytes,
+                         void* d_scratch, size_t scratch_bytes, void* stream) {
     DFGNN_REQUIRE(out != nullptr, DFGNN_EINVAL, "out is NULL");
     *out = nullptr;
     size_t need_meta = 0, need_scratch = 0;
@@ -526,41 +529,56 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     int T, C, flags = 0;
     rc = resolve_params(sched, E, &T, &C, &flags);
     if (rc != DFGNN_OK) return rc;
-
-    hipStream_t st = (hipStream_t)stream;
-    const MetaLayout M = meta_layout(N, E, T, C, flags);
-    const ScratchLayout S = scratch_layout(N, E, T);
+    B.st = (hipStream_t)stream;
+    B.M = meta_layout(N, E, T, C, flags);
+    B.S = scratch_layout(N, E, T);
     char* meta = (char*)d_meta;
-    char* scratch = (char*)d_scratch;
-
-    dfgnn_graph g{};
+    B.scratch = (char*)d_scratch;
+    dfgnn_graph& g = B.g;
+    g = dfgnn_graph{};
     g.N = N; g.E = E; g.T = T; g.C = C; g.flags = flags;
     g.indptr = d_indptr; g.indices = d_indices;
-    g.row_order = (int*)(meta + M.row_order);
-    g.col_order = (int*)(meta + M.col_order);
-    g.t_indptr = (int*)(meta + M.t_indptr);
-    g.t_indices = (int*)(meta + M.t_indices);
-    g.t_eid = (int*)(meta + M.t_eid);
-    g.row_chunk_ptr = (int*)(meta + M.row_chunk_ptr);
-    g.row_chunks = (int*)(meta + M.row_chunks);
-    g.col_chunk_ptr = (int*)(meta + M.col_chunk_ptr);
-    g.col_chunks = (int*)(meta + M.col_chunks);
-    int* d_counters = (int*)(meta + M.counters);
-    g.counters = d_counters;
-    g.edge_row = (flags & DFGNN_SCHED_SCORES_IN_MEMORY) ? (int*)(meta + M.edge_row) : nullptr;
+    g.row_order = (int*)(meta + B.M.row_order);
+    g.col_order = (int*)(meta + B.M.col_order);
+    g.t_indptr = (int*)(meta + B.M.t_indptr);
+    g.t_indices = (int*)(meta + B.M.t_indices);
+    g.t_eid = (int*)(meta + B.M.t_eid);
+    g.row_chunk_ptr = (int*)(meta + B.M.row_chunk_ptr);
+    g.row_chunks = (int*)(meta + B.M.row_chunks);
+    g.col_chunk_ptr = (int*)(meta + B.M.col_chunk_ptr);
+    g.col_chunks = (int*)(meta + B.M.col_chunks);
+    B.d_counters = (int*)(meta + B.M.counters);
+    g.counters = B.d_counters;
+    g.edge_row = (flags & DFGNN_SCHED_SCORES_IN_MEMORY) ? (int*)(meta + B.M.edge_row) : nullptr;
+    return DFGNN_OK;
+}
 
+static const char kCsrErrorText[] =
+    "malformed CSR (flags 0x%x: 1 indptr[0]!=0, 2 indptr[N]!=E, 4 indptr decreases, 8 indptr out of range, 16 index out "
+    "of range)";
+
+// The general builder: any graph; global scans and radix sorts, about twenty launches.  Leaves the degree
+// class pointers and the locality sample in the device counters.
+static int build_general(Build& B, int* locality_stride) {
+    dfgnn_graph& g = B.g;
+    const int64_t N = g.N, E = g.E;
+    const int T = g.T, flags = g.flags;
+    hipStream_t st = B.st;
+    char* scratch = B.scratch;
+    const ScratchLayout& S = B.S;
+    int* d_counters = B.d_counters;
+    const int32_t *d_indptr = g.indptr, *d_indices = g.indices;
     const int tpb = 256;
+    int rc;
     DFGNN_HIP(hipMemsetAsync(d_counters, 0, CNT_TOTAL * sizeof(int), st));
     {
         const int64_t span = (N + 1 > E ? N + 1 : E);
         hipLaunchKernelGGL(k_validate, dim3((unsigned)((span + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr, d_indices,
                            (int)N, (int)E, d_counters + CNT_ERROR);
-        int flags = 0;
-        DFGNN_HIP(hipMemcpyAsync(&flags, d_counters + CNT_ERROR, sizeof(int), hipMemcpyDeviceToHost, st));
+        int bad = 0;
+        DFGNN_HIP(hipMemcpyAsync(&bad, d_counters + CNT_ERROR, sizeof(int), hipMemcpyDeviceToHost, st));
         DFGNN_HIP(hipStreamSynchronize(st));
-        DFGNN_REQUIRE(flags == 0, DFGNN_EINVAL,
-                      "malformed CSR (flags 0x%x: 1 indptr[0]!=0, 2 indptr[N]!=E, 4 indptr decreases, 8 indptr out of "
-                      "range, 16 index out of range)", flags);
+        DFGNN_REQUIRE(bad == 0, DFGNN_EINVAL, kCsrErrorText, bad);
     }
 
     // rows: order (their chunks follow once the counters have been read)
@@ -568,7 +586,7 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
     if (rc != DFGNN_OK) return rc;
 
     // CSC transpose: stable sort of CSR positions by source id
-    int locality_stride = 1;
+    *locality_stride = 1;
     const bool fwd_only = flags & DFGNN_SCHED_FORWARD_ONLY;
     if (fwd_only) {
         g.col_order = g.t_indptr = g.t_indices = g.t_eid = g.col_chunk_ptr = g.col_chunks = nullptr;
@@ -577,10 +595,10 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
             const int64_t row_threads = (E + kRowsPerThread - 1) / kRowsPerThread;
             hipLaunchKernelGGL(k_edge_rows, dim3((unsigned)((row_threads + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr,
                                (int)N, (int)E, edge_row);
-            locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
-            const int64_t samples = (E + locality_stride - 1) / locality_stride;
+            *locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
+            const int64_t samples = (E + *locality_stride - 1) / *locality_stride;
             hipLaunchKernelGGL(k_edge_locality, dim3((unsigned)((samples + tpb - 1) / tpb)), dim3(tpb), 0, st, edge_row,
-                               d_indices, (int)E, locality_stride, d_counters + CNT_NEAR);
+                               d_indices, (int)E, *locality_stride, d_counters + CNT_NEAR);
             DFGNN_HIP(hipGetLastError());
         }
     } else if (E > 0) {
@@ -600,10 +618,10 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
                            (int)E, edge_row);
         hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)((E + tpb - 1) / tpb)), dim3(tpb), 0, st, g.t_eid, edge_row, (int)E,
                            g.t_indices);
-        locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
-        const int64_t samples = (E + locality_stride - 1) / locality_stride;
+        *locality_stride = (int)((E + kLocalitySamples - 1) / kLocalitySamples);
+        const int64_t samples = (E + *locality_stride - 1) / *locality_stride;
         hipLaunchKernelGGL(k_edge_locality, dim3((unsigned)((samples + tpb - 1) / tpb)), dim3(tpb), 0, st, edge_row,
-                           d_indices, (int)E, locality_stride, d_counters + CNT_NEAR);
+                           d_indices, (int)E, *locality_stride, d_counters + CNT_NEAR);
         DFGNN_HIP(hipGetLastError());
     } else {
         DFGNN_HIP(hipMemsetAsync(g.t_indptr, 0, (size_t)(N + 1) * sizeof(int), st));
@@ -614,26 +632,71 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
         rc = schedule_order(g.t_indptr, N, T, g.col_order, d_counters, CNT_COL_BUCKETS, scratch, S, st);
         if (rc != DFGNN_OK) return rc;
     }
+    return DFGNN_OK;
+}
 
-    // one read-back of all counters: where the degree classes start (and with that the super rows and
-    // columns), and the locality sample
-    int host_counters[CNT_TOTAL];
-    DFGNN_HIP(hipMemcpyAsync(host_counters, d_counters, sizeof(host_counters), hipMemcpyDeviceToHost, st));
+// A graph the segment-local builder takes: at most kSegMaxNodes nodes per segment is checked on the device
+// for batches (batch_ptr lives there); a graph without batch structure is one segment.
+static bool local_builder_applies(const dfgnn_graph& g, int64_t n_graphs) {
+    if (g.flags & (DFGNN_SCHED_FORWARD_ONLY | DFGNN_SCHED_SCORES_IN_MEMORY)) return false;
+    if (g.N <= 0 || g.E <= 0) return false;
+    if (n_graphs == 0) return g.N <= kSegMaxNodes && g.E <= kSegMaxEdges;
+    return true;
+}
+
+// The segment-local builder (graph_local.hpp): one launch for a small graph, three for a batch.  seg_tmp
+// holds [n_seg][72] + [n_seg][72] + [72] ints.
+static int build_local(Build& B, const int32_t* d_batch_ptr, int64_t n_graphs, int* seg_tmp, int* tile_ptr, int* tile_graph,
+                       unsigned long long* mask, unsigned long long* mask_t) {
+    dfgnn_graph& g = B.g;
+    SegArgs a{};
+    a.indptr = g.indptr; a.indices = g.indices; a.batch_ptr = d_batch_ptr;
+    a.n_nodes = (int)g.N; a.n_edges = (int)g.E; a.n_seg = d_batch_ptr ? (int)n_graphs : 1; a.T = g.T;
+    a.t_indptr = g.t_indptr; a.t_indices = g.t_indices; a.t_eid = g.t_eid;
+    a.row_order = g.row_order; a.col_order = g.col_order;
+    a.keys_tmp = (uint32_t*)(B.scratch + B.S.keys_a);
+    a.vals_tmp = (int*)(B.scratch + B.S.vals);
+    a.seg_hist = seg_tmp;
+    a.seg_off = seg_tmp + (size_t)a.n_seg * kSegKeys;
+    a.key_total = seg_tmp + (size_t)a.n_seg * kSegKeys * 2;
+    a.counters = B.d_counters;
+    a.tile_ptr = tile_ptr; a.tile_graph = tile_graph; a.mask = mask; a.mask_t = mask_t;
+    a.max_words = kDenseMaxWords;
+    DFGNN_HIP(hipMemsetAsync(B.d_counters, 0, CNT_TOTAL * sizeof(int), B.st));
+    launch_local(a, B.st);
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}
+
+// After either builder: one read-back of all counters (where the degree classes start, and with that the
+// super rows and columns; the locality sample; error and batch flags), then the chunk lists of the super
+// rows and columns if there are any, then the handle.
+static int finish_build(Build& B, bool local, int locality_stride, int* host_counters) {
+    dfgnn_graph& g = B.g;
+    const int64_t N = g.N, E = g.E;
+    hipStream_t st = B.st;
+    int* d_counters = B.d_counters;
+    const bool fwd_only = g.flags & DFGNN_SCHED_FORWARD_ONLY;
+    DFGNN_HIP(hipMemcpyAsync(host_counters, d_counters, CNT_TOTAL * sizeof(int), hipMemcpyDeviceToHost, st));
     DFGNN_HIP(hipStreamSynchronize(st));
+    if (local) {
+        if (host_counters[CNT_SEG_FLAGS]) return DFGNN_OK;  // a segment was too large: the caller falls back
+        DFGNN_REQUIRE(host_counters[CNT_ERROR] == 0, DFGNN_EINVAL, kCsrErrorText, host_counters[CNT_ERROR]);
+        if (host_counters[CNT_BATCH] & (BATCH_BAD_PTR | BATCH_CROSS_EDGE)) return DFGNN_OK;  // reported by the caller
+    }
     for (int k = 0; k < 36; ++k) {
         g.row_bucket_ptr[k] = N > 0 ? host_counters[CNT_ROW_BUCKETS + k] : 0;
         g.col_bucket_ptr[k] = (N > 0 && !fwd_only) ? host_counters[CNT_COL_BUCKETS + k] : 0;
     }
     g.n_super_rows = g.row_bucket_ptr[1];
     g.n_super_cols = g.col_bucket_ptr[1];
-    const int near = host_counters[CNT_NEAR];
     if (g.n_super_rows > 0 || g.n_super_cols > 0) {
-        const int64_t max_chunks = chunk_capacity(E, T, C);
-        rc = schedule_chunks(d_indptr, g.n_super_rows, C, g.row_order, g.row_chunk_ptr, g.row_chunks, max_chunks, d_counters,
-                             CNT_ROW_CHUNKS, scratch, S, st);
+        const int64_t max_chunks = chunk_capacity(E, g.T, g.C);
+        int rc = schedule_chunks(g.indptr, g.n_super_rows, g.C, g.row_order, g.row_chunk_ptr, g.row_chunks, max_chunks,
+                                 d_counters, CNT_ROW_CHUNKS, B.scratch, B.S, st);
         if (rc != DFGNN_OK) return rc;
-        rc = schedule_chunks(g.t_indptr, g.n_super_cols, C, g.col_order, g.col_chunk_ptr, g.col_chunks, max_chunks,
-                             d_counters, CNT_COL_CHUNKS, scratch, S, st);
+        rc = schedule_chunks(g.t_indptr, g.n_super_cols, g.C, g.col_order, g.col_chunk_ptr, g.col_chunks, max_chunks,
+                             d_counters, CNT_COL_CHUNKS, B.scratch, B.S, st);
         if (rc != DFGNN_OK) return rc;
         int n_chunks[4] = {0, 0, 0, 0};  // counters CNT_ROW_CHUNKS .. CNT_COL_CHUNKS
         DFGNN_HIP(hipMemcpyAsync(n_chunks, d_counters + CNT_ROW_CHUNKS, 3 * sizeof(int), hipMemcpyDeviceToHost, st));
@@ -641,21 +704,50 @@ extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const
         g.n_row_chunks = n_chunks[0];
         g.n_col_chunks = n_chunks[CNT_COL_CHUNKS - CNT_ROW_CHUNKS];
     }
-    // at least half of the sampled edges stay inside the window: runs of kXcdGroup workgroups share an XCD
+    // at least half of the sampled edges stay inside the window: runs of kXcdGroup workgroups share an XCD.
+    // Every edge of a graph the local builder takes does (segments have at most kSegMaxNodes <= window nodes).
+    static_assert(kSegMaxNodes <= kLocalityWindow, "edges inside a segment must count as local");
     const int64_t samples = E > 0 ? (E + locality_stride - 1) / locality_stride : 0;
-    g.xcd_group = (!(flags & DFGNN_SCHED_NO_XCD_GROUPS) && samples > 0 && 2 * (int64_t)near >= samples) ? kXcdGroup : 0;
+    const int64_t near = local ? samples : host_counters[CNT_NEAR];
+    g.xcd_group = (!(g.flags & DFGNN_SCHED_NO_XCD_GROUPS) && samples > 0 && 2 * near >= samples) ? kXcdGroup : 0;
+    return DFGNN_OK;
+}
 
+static int publish(const dfgnn_graph& g, dfgnn_graph** out) {
     dfgnn_graph* h = new (std::nothrow) dfgnn_graph(g);
     DFGNN_REQUIRE(h != nullptr, DFGNN_EINVAL, "out of host memory");
     *out = h;
     return DFGNN_OK;
 }
 
+}  // namespace dfgnn
+
+extern "C" int dfgnn_graph_create(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr,
+                                  const int32_t* d_indices, const dfgnn_sched_params* sched, void* d_meta,
+                                  size_t meta_bytes, void* d_scratch, size_t scratch_bytes, void* stream) {
+    clear_error();
+    Build B;
+    int rc = prepare_build(B, out, N, E, d_indptr, d_indices, sched, d_meta, meta_bytes, d_scratch, scratch_bytes, stream);
+    if (rc != DFGNN_OK) return rc;
+    int host_counters[CNT_TOTAL];
+    int locality_stride = 1;
+    const bool local = local_builder_applies(B.g, 0);
+    if (local) {
+        // one segment: its 3 x 72 ints of degree-class counts fit the sort's counter area (at least 256 ints)
+        rc = build_local(B, nullptr, 0, (int*)(B.scratch + B.S.counts), nullptr, nullptr, nullptr, nullptr);
+    } else {
+        rc = build_general(B, &locality_stride);
+    }
+    if (rc != DFGNN_OK) return rc;
+    rc = finish_build(B, local, locality_stride, host_counters);
+    if (rc != DFGNN_OK) return rc;
+    return publish(B.g, out);
+}
+
 // ------------------------------------------------------------------------------------------------
 // block-diagonal batches of small graphs
 // ------------------------------------------------------------------------------------------------
 namespace dfgnn {
-enum { BATCH_BAD_PTR = 1, BATCH_CROSS_EDGE = 2, BATCH_TOO_LARGE = 4, BATCH_DUPLICATE = 8 };
 
 // per graph: pointer checks, largest graph, and the number of 16-node tiles (for the tile pointer)
 __global__ void k_batch_check_ptr(const int* __restrict__ bp, int n_graphs, int n_nodes, int* __restrict__ tiles,
@@ -721,7 +813,7 @@ __global__ void k_batch_masks(const int* __restrict__ bp, int n_graphs, const in
 }
 
 struct BatchLayout {
-    size_t adj_mask, adj_mask_t, tile_ptr, tile_graph, scan_tmp, total;
+    size_t adj_mask, adj_mask_t, tile_ptr, tile_graph, scan_tmp, seg_tmp, total;
 };
 static BatchLayout batch_layout(int64_t N, int64_t n_graphs) {
     BatchLayout L{};
@@ -732,6 +824,7 @@ static BatchLayout batch_layout(int64_t N, int64_t n_graphs) {
     L.tile_ptr = take((size_t)(n_graphs + 2) * 4);
     L.tile_graph = take((size_t)(N / 16 + n_graphs + 2) * 4);  // every graph has at most nodes/16 + 1 tiles
     L.scan_tmp = take((size_t)(scan_blocks(n_graphs + 2) + 1) * 4);
+    L.seg_tmp = take(((size_t)(n_graphs + 1) * 2 + 1) * kSegKeys * 4);  // degree-class counts per graph (dfgnn_graph_create_batch)
     L.total = off;
     return L;
 }
@@ -813,6 +906,71 @@ extern "C" int dfgnn_graph_set_batch(dfgnn_graph* g, const int32_t* d_batch_ptr,
     g->adj_mask_t = mask_t;
     g->batch_dense = small_enough && !(host[0] & BATCH_DUPLICATE);
     return DFGNN_OK;
+}
+
+// Graph metadata and batch structure in one call (see graph_local.hpp); falls back to the two general calls
+// for what the segment-local builder does not take.
+extern "C" int dfgnn_graph_create_batch(dfgnn_graph** out, int64_t N, int64_t E, const int32_t* d_indptr,
+                                        const int32_t* d_indices, const int32_t* d_batch_ptr, int64_t n_graphs,
+                                        const dfgnn_sched_params* sched, void* d_meta, size_t meta_bytes, void* d_batch,
+                                        size_t batch_bytes, void* d_scratch, size_t scratch_bytes, void* stream) {
+    clear_error();
+    Build B;
+    int rc = prepare_build(B, out, N, E, d_indptr, d_indices, sched, d_meta, meta_bytes, d_scratch, scratch_bytes, stream);
+    if (rc != DFGNN_OK) return rc;
+    DFGNN_REQUIRE(d_batch_ptr != nullptr && n_graphs >= 0 && n_graphs <= N + 1, DFGNN_EINVAL,
+                  "batch_ptr is NULL or n_graphs = %lld is out of range", (long long)n_graphs);
+    DFGNN_REQUIRE(n_graphs > 0 || N == 0, DFGNN_EINVAL, "a graph with nodes needs at least one batch entry");
+    const BatchLayout L = batch_layout(N, n_graphs);
+    DFGNN_REQUIRE(d_batch != nullptr && ((uintptr_t)d_batch % kAlign) == 0, DFGNN_EINVAL,
+                  "batch buffer is NULL or not 256-byte aligned");
+    DFGNN_REQUIRE(batch_bytes >= L.total, DFGNN_EWORKSPACE, "batch buffer has %zu bytes, needs %zu", batch_bytes, L.total);
+    char* buf = (char*)d_batch;
+    bool done = false;
+    if (local_builder_applies(B.g, n_graphs) && n_graphs > 0) {
+        int* tile_ptr = (int*)(buf + L.tile_ptr);
+        int* tile_graph = (int*)(buf + L.tile_graph);
+        unsigned long long* mask = (unsigned long long*)(buf + L.adj_mask);
+        unsigned long long* mask_t = (unsigned long long*)(buf + L.adj_mask_t);
+        rc = build_local(B, d_batch_ptr, n_graphs, (int*)(buf + L.seg_tmp), tile_ptr, tile_graph, mask, mask_t);
+        if (rc != DFGNN_OK) return rc;
+        int host_counters[CNT_TOTAL];
+        rc = finish_build(B, true, 1, host_counters);
+        if (rc != DFGNN_OK) return rc;
+        if (!host_counters[CNT_SEG_FLAGS]) {  // every graph of the batch fitted a segment
+            const int bf = host_counters[CNT_BATCH];
+            DFGNN_REQUIRE(!(bf & BATCH_BAD_PTR), DFGNN_EINVAL, "batch_ptr must start at 0, end at N and be non-decreasing");
+            DFGNN_REQUIRE(!(bf & BATCH_CROSS_EDGE), DFGNN_EINVAL, "an edge connects nodes of different graphs of the batch");
+            dfgnn_graph& g = B.g;
+            const int max_nodes = host_counters[CNT_BATCH_MAX];
+            int words = (max_nodes + 63) / 64;
+            words = words < 1 ? 1 : (words > kDenseMaxWords ? kDenseMaxWords : words);
+            unsigned long long pairs;
+            memcpy(&pairs, host_counters + CNT_BATCH_PAIRS, sizeof(pairs));
+            g.batch_ptr = d_batch_ptr;
+            g.n_graphs = n_graphs;
+            g.tile_ptr = tile_ptr;
+            g.tile_graph = tile_graph;
+            g.n_tiles = host_counters[CNT_N_TILES];
+            g.tile_pairs = (int64_t)pairs;
+            g.max_graph_nodes = max_nodes;
+            g.mask_words = words;
+            g.adj_mask = mask;
+            g.adj_mask_t = mask_t;
+            g.batch_dense = max_nodes <= kDenseMaxGraphNodes && !(bf & BATCH_DUPLICATE);
+            done = true;
+        }
+    }
+    if (done) return publish(B.g, out);
+    // the general route: any graph sizes, forward-only graphs, the comparator's extra array
+    rc = dfgnn_graph_create(out, N, E, d_indptr, d_indices, sched, d_meta, meta_bytes, d_scratch, scratch_bytes, stream);
+    if (rc != DFGNN_OK) return rc;
+    rc = dfgnn_graph_set_batch(*out, d_batch_ptr, n_graphs, d_batch, batch_bytes, stream);
+    if (rc != DFGNN_OK) {
+        delete *out;
+        *out = nullptr;
+    }
+    return rc;
 }
 
 extern "C" int dfgnn_graph_destroy(dfgnn_graph* graph) {

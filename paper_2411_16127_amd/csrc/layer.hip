@@ -20,11 +20,14 @@ struct Geometry {
     int groups;  // H / heads
 };
 
+static int elem_bytes(int dtype) { return dtype == DFGNN_F32 ? 4 : 2; }
+
 static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
-    DFGNN_REQUIRE(L->dtype == DFGNN_F32 || L->dtype == DFGNN_BF16, DFGNN_EINVAL, "unknown dtype %d", L->dtype);
+    DFGNN_REQUIRE(L->dtype == DFGNN_F32 || L->dtype == DFGNN_BF16 || L->dtype == DFGNN_F16, DFGNN_EINVAL, "unknown dtype %d",
+                  L->dtype);
     DFGNN_REQUIRE(L->H >= 1 && L->D >= 1, DFGNN_EINVAL, "H and D must be positive (H=%d D=%d)", L->H, L->D);
     Geometry g{};
-    g.vec = L->dtype == DFGNN_F32 ? 4 : 8;
+    g.vec = 16 / elem_bytes(L->dtype);
     DFGNN_REQUIRE(L->D % g.vec == 0, DFGNN_EUNSUPPORTED, "D=%d: a head must be a multiple of 16 bytes", L->D);
     g.lph = L->D / g.vec;
     DFGNN_REQUIRE((g.lph & (g.lph - 1)) == 0, DFGNN_EUNSUPPORTED, "D=%d: D/%d must be a power of two", L->D, g.vec);
@@ -36,19 +39,19 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
     const int lanes = g.heads * g.lph;
     g.lpe = 4;
     while (g.lpe < lanes) g.lpe <<= 1;
-    const bool f32 = L->dtype == DFGNN_F32;
     // a compile-time geometry needs the row to fill its lanes exactly; otherwise the run-time one of that width
-    int k = 0;
-    for (int l = 4; l < g.lpe; l <<= 1) ++k;
-    g.id = (f32 ? 0 : 5) + k;
-    struct Entry { int id; bool f32; int lpe, lph; };
+    struct Entry { int id, dtype, lpe, lph; };
     static const Entry table[] = {
-#define X(ID, T, LPE, LPH) {ID, sizeof(T) == 4, LPE, LPH},
+#define X(ID, T, LPE, LPH) {ID, dtype_of<T>::value, LPE, LPH},
         DFGNN_GEOMETRIES(X)
 #undef X
     };
+    g.id = -1;
     for (const Entry& e : table)
-        if (e.lph != 0 && e.f32 == f32 && e.lpe == g.lpe && lanes == g.lpe && e.lph == g.lph) g.id = e.id;
+        if (e.lph == 0 && e.dtype == L->dtype && e.lpe == g.lpe) g.id = e.id;
+    for (const Entry& e : table)
+        if (e.lph != 0 && e.dtype == L->dtype && e.lpe == g.lpe && lanes == g.lpe && e.lph == g.lph) g.id = e.id;
+    DFGNN_REQUIRE(g.id >= 0, DFGNN_EUNSUPPORTED, "no kernel for dtype %d with %d lanes per row", L->dtype, g.lpe);
     *out = g;
     return DFGNN_OK;
 }
@@ -87,7 +90,8 @@ static Workspace workspace_layout(const dfgnn_graph* g, const dfgnn_layer* L, bo
         W.d_er = take(gat ? N * H : 0);
         W.g_row = take(agnn || v2 ? N * HD : 0);
         W.dbeta_row = take(agnn ? N * H : 0);
-        W.reduce = take(gat ? (size_t)kReduceBlocks * 2 * HD : (v2 ? (size_t)kRowsumBlocks * HD : (agnn ? (size_t)kReduceBlocks : 0)));
+        // double-precision partials of the parameter-gradient reductions (AGNN: plus the running total)
+        W.reduce = take(2 * (gat ? (size_t)kReduceBlocks * 2 * HD : (v2 ? (size_t)kRowsumBlocks * HD : (agnn ? (size_t)kReduceBlocks + 1 : 0))));
     }
     if (!backward && scores_in_memory(g, L)) W.scores = take((size_t)g->E * H);
     W.total = off;
@@ -135,7 +139,7 @@ static int dispatch_attention(int geo, const dfgnn_graph* g, int model, const Ar
     }
 }
 
-static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, float* reduce_tmp, float* d_a_l,
+static int dispatch_backward(int geo, const dfgnn_graph* g, int model, const Args& a, double* reduce_tmp, float* d_a_l,
                              float* d_a_r, float* d_scale, bool add_to_scale, hipStream_t st) {
     switch (model) {
     case DFGNN_GT: return launch_backward_gt(geo, g, a, st);
@@ -167,7 +171,7 @@ static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo
     DFGNN_REQUIRE(L->reserved[0] == 0, DFGNN_EINVAL, "dfgnn_layer.reserved must be zero");
     int rc = pick_geometry(L, geo);
     if (rc != DFGNN_OK) return rc;
-    const int64_t elem = L->dtype == DFGNN_F32 ? 4 : 2;
+    const int64_t elem = elem_bytes(L->dtype);
     DFGNN_REQUIRE((int64_t)g->N * L->H * L->D * elem < ((int64_t)1 << 32) - 4096, DFGNN_EUNSUPPORTED,
                   "node tensor of %lld bytes: gathers use 32-bit byte offsets, tensors must stay below 4 GiB",
                   (long long)((int64_t)g->N * L->H * L->D * elem));
@@ -177,7 +181,7 @@ static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo
 
 static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, const Geometry& geo) {
     a.n_nodes = (int)g->N;
-    a.row_bytes = (uint32_t)(L->H * L->D * (L->dtype == DFGNN_F32 ? 4 : 2));
+    a.row_bytes = (uint32_t)(L->H * L->D * elem_bytes(L->dtype));
     a.tensor_bytes = (uint32_t)((uint64_t)g->N * a.row_bytes);
     a.nh_bytes = (uint32_t)((uint64_t)g->N * geo.heads * 4u);
     a.H = geo.heads;
@@ -201,7 +205,7 @@ template <typename T> static const T* shift(const T* p, size_t bytes) { return p
 
 static void select_group(Args& a, const Args& whole, const dfgnn_layer* L, const Geometry& geo, int gi) {
     a = whole;
-    const size_t elem = L->dtype == DFGNN_F32 ? 4 : 2;
+    const size_t elem = (size_t)elem_bytes(L->dtype);
     const size_t first = (size_t)gi * geo.heads;      // first head of the group
     const size_t tb = first * L->D * elem;            // byte offset inside a node row
     const size_t pb = first * L->D * sizeof(float);   // inside an [H, D] fp32 parameter
@@ -409,7 +413,7 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     a.bias = edge_bias; a.d_bias = d_edge_bias;
     a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
     bind_workspace(a, W, workspace, true);
-    float* reduce_tmp = (float*)((char*)workspace + W.reduce);
+    double* reduce_tmp = (double*)((char*)workspace + W.reduce);
     for (int gi = 0; gi < geo.groups; ++gi) {
         Args ag;
         select_group(ag, a, layer, geo, gi);

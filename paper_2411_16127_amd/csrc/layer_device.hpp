@@ -30,6 +30,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct bf16_t { uint16_t bits; };
+struct f16_t { uint16_t bits; };  // IEEE half
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
@@ -70,6 +71,28 @@ template <> struct Elem<bf16_t> {
         u32x4 t;
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = round_bits(x[2 * i]) | (round_bits(x[2 * i + 1]) << 16);
+        *reinterpret_cast<u32x4*>(p) = t;
+    }
+};
+
+template <> struct Elem<f16_t> {
+    static constexpr int VEC = 8;
+    typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+    __device__ static void unpack(const u32x4& r, float (&x)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const h16x2 h = __builtin_bit_cast(h16x2, (uint32_t)r[i]);
+            x[2 * i] = (float)h[0];
+            x[2 * i + 1] = (float)h[1];
+        }
+    }
+    __device__ static void store(f16_t* p, const float (&x)[8]) {  // round to nearest even
+        u32x4 t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const h16x2 h = {(_Float16)x[2 * i], (_Float16)x[2 * i + 1]};
+            t[i] = __builtin_bit_cast(uint32_t, h);
+        }
         *reinterpret_cast<u32x4*>(p) = t;
     }
 };
@@ -222,6 +245,7 @@ template <typename T_, int LPE_, int LPH_, bool EDGE_TERM_ = false> struct Geo {
 
 struct Ctx {
     int lane, c, g, f0, h, node;
+    int deg;      // neighbours of the row this lane finishes (a large value where a row is merged from chunks)
     bool active;  // this lane's features exist (f0 < HD)
     bool head0;   // first lane of its head
     bool writer;  // this lane stores results: edge slot 0 when the wave shares one row, every live slot otherwise
@@ -256,6 +280,7 @@ template <class G> __device__ inline Ctx make_ctx(const Args& a, int lane, int n
     c.h = c.active ? c.c >> __builtin_ctz(lph) : 0;
     c.head0 = c.active && (c.c & (lph - 1)) == 0;
     c.node = node;
+    c.deg = 0x7fffffff;
     c.off = (size_t)node * a.row_stride + c.f0;
     c.woff = (size_t)node * a.HD + c.f0;
     c.writer = c.g == 0;
@@ -436,15 +461,23 @@ template <class G, int U> struct AttentionOut {
 //   bf16 tensors: O was rounded to bf16, which would put a 2^-9 relative error into delta, so the
 //   pass accumulates dsum = sum_j p_ij dP_ij itself and uses  sum_j p (dP - delta) y_j
 //   = sum_j p dP y_j - delta sum_j p y_j  to finish in one sweep (kExact).
+//   A row with a single edge has p = 1 and dS = 0 exactly, while its computed p is 1 only to rounding (the
+//   statistics went through a logarithm).  kExact passes therefore finish such a row with delta = dP of its
+//   edge (dp0, which the column pass recomputes bit for bit, so that its dS is exactly zero too) and write
+//   zeros for every score-side gradient of the row (single_edge / exact_delta below).
 template <class G> struct RowBackwardBase {
     static constexpr int VEC = G::VEC;
     static constexpr bool kExact = sizeof(typename G::T) == 2;
     float g[VEC];  // dO_i
     float delta, lse2, dsum;
+    float dp0;     // kExact: dP of the first edge of this lane's slot in the latest round
+    __device__ static bool single_edge(const Ctx& c) { return c.deg == 1; }
+    __device__ float exact_delta(const Ctx& c) const { return single_edge(c) ? dp0 : dsum; }
     __device__ void init_row(const Args& a, const Ctx& c) {
         load_row<G>(a.d_out, c, g);
         dsum = 0.f;
         delta = 0.f;
+        dp0 = 0.f;
         if constexpr (!kExact) {
             float o[VEC];
             load_row<G>(a.out, c, o);
@@ -511,7 +544,8 @@ __device__ inline void wave_item(const Args& a, int item, int lane) {
     node = __builtin_amdgcn_readfirstlane(node);
     eb = __builtin_amdgcn_readfirstlane(eb);
     ee = __builtin_amdgcn_readfirstlane(ee);
-    const Ctx c = make_ctx<G>(a, lane, node);
+    Ctx c = make_ctx<G>(a, lane, node);
+    if (!PARTIAL) c.deg = ee - eb;
     PassT<G, U> p;
     p.init(a, c);
     constexpr int STEP = G::EPW * U;
@@ -543,6 +577,7 @@ __device__ inline void wave_small_rows(const Args& a, int item, int lane) {
     const int ee = live ? a.ptr[node + 1] : 0;
     Ctx c = make_ctx<G>(a, lane, node);
     c.writer = live;
+    c.deg = ee - eb;
     PassT<G, U> p;
     p.init(a, c);
     int j[U], jn[U], ep[U], epn[U];
@@ -683,21 +718,29 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_edge_scores(const Args 
 }
 
 // ---------------------------------------------------------------------------------------------
-// small deterministic reductions (two stages, fixed summation order)
+// small deterministic reductions (two stages, fixed summation order).  The parameter gradients are signed
+// sums over all nodes and edges whose terms largely cancel, so both stages add in double precision: the
+// result then carries the rounding of its fp32 terms only, not of the summation.
 // ---------------------------------------------------------------------------------------------
 constexpr int kReduceBlocks = 256;
+
+template <int LPE> __device__ inline double slot_sum_f64(double x) {
+#pragma unroll
+    for (int o = LPE; o < 64; o <<= 1) x += __shfl_xor(x, o);
+    return x;
+}
 
 // stage 1 of da_l[h,d] = sum_v d_el[v,h] Wh[v,h,d] and da_r likewise.  Same lane geometry as the passes:
 // an edge slot reads one node row per step; wave w of the grid takes node groups w, w + W, ...;
 // one partial per workgroup.
 template <class G>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const Args a, float* __restrict__ partial) {
-    __shared__ float red[kWavesPerBlock][2][64 * G::VEC];
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const Args a, double* __restrict__ partial) {
+    __shared__ double red[kWavesPerBlock][2][G::LPE * G::VEC];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int waves = gridDim.x * kWavesPerBlock;
-    float sl[G::VEC], sr[G::VEC];
+    double sl[G::VEC], sr[G::VEC];
 #pragma unroll
-    for (int i = 0; i < G::VEC; ++i) { sl[i] = 0.f; sr[i] = 0.f; }
+    for (int i = 0; i < G::VEC; ++i) { sl[i] = 0.0; sr[i] = 0.0; }
     constexpr int B = 4;  // node rows requested per edge slot before the first is used
     const int stride = waves * G::EPW;
     for (int base = (blockIdx.x * kWavesPerBlock + wave) * G::EPW; base < a.n_nodes; base += stride * B) {
@@ -714,11 +757,14 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
 #pragma unroll
         for (int k = 0; k < B; ++k) {
 #pragma unroll
-            for (int i = 0; i < G::VEC; ++i) { sl[i] = fmaf(del[k], x[k][i], sl[i]); sr[i] = fmaf(der[k], x[k][i], sr[i]); }
+            for (int i = 0; i < G::VEC; ++i) {
+                sl[i] = fma((double)del[k], (double)x[k][i], sl[i]);
+                sr[i] = fma((double)der[k], (double)x[k][i], sr[i]);
+            }
         }
     }
 #pragma unroll
-    for (int i = 0; i < G::VEC; ++i) { sl[i] = slot_sum<G::LPE>(sl[i]); sr[i] = slot_sum<G::LPE>(sr[i]); }
+    for (int i = 0; i < G::VEC; ++i) { sl[i] = slot_sum_f64<G::LPE>(sl[i]); sr[i] = slot_sum_f64<G::LPE>(sr[i]); }
     const int f0 = (lane % G::LPE) * G::VEC;
     if (lane < G::LPE) {
 #pragma unroll
@@ -727,7 +773,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
     __syncthreads();
     for (int t = threadIdx.x; t < 2 * a.HD; t += blockDim.x) {
         const int which = t / a.HD, f = t % a.HD;
-        float sum = 0.f;
+        double sum = 0.0;
 #pragma unroll
         for (int w = 0; w < kWavesPerBlock; ++w) sum += red[w][which][f];
         partial[((size_t)blockIdx.x * 2 + which) * a.HD + f] = sum;
@@ -736,16 +782,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
 
 // second stage: 1024 threads; thread t owns column t % wf of the 2 * HD columns (a_l | a_r) and every
 // (1024 / wf)-th partial row, the groups are then added in order through LDS (wf = a power of two >= 2 * HD)
-[[maybe_unused]] static __global__ __launch_bounds__(1024) void k_gat_param_final(const float* __restrict__ partial, int nblocks, int HD,
+[[maybe_unused]] static __global__ __launch_bounds__(1024) void k_gat_param_final(const double* __restrict__ partial, int nblocks, int HD,
                                                           int wf, float* __restrict__ d_a_l, float* __restrict__ d_a_r) {
-    __shared__ float red[1024];
+    __shared__ double red[1024];
     const int groups = 1024 / wf, bs = threadIdx.x / wf, t = threadIdx.x % wf;
-    float sum = 0.f;
+    double sum = 0.0;
     if (t < 2 * HD) {
         for (int b = bs; b < nblocks; b += 16 * groups) {
-            float v[16];
+            double v[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * 2 * HD + t] : 0.f;
+            for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * 2 * HD + t] : 0.0;
 #pragma unroll
             for (int k = 0; k < 16; ++k) sum += v[k];
         }
@@ -753,14 +799,14 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
     red[threadIdx.x] = sum;
     __syncthreads();
     if (bs == 0 && t < 2 * HD) {
-        float total = 0.f;
+        double total = 0.0;
         for (int k = 0; k < groups; ++k) total += red[k * wf + t];
-        (t < HD ? d_a_l : d_a_r)[t < HD ? t : t - HD] = total;
+        (t < HD ? d_a_l : d_a_r)[t < HD ? t : t - HD] = (float)total;
     }
 }
 
-__device__ inline float block_sum_256(float v) {
-    __shared__ float red[256];
+__device__ inline double block_sum_256(double v) {
+    __shared__ double red[256];
     red[threadIdx.x] = v;
     __syncthreads();
 #pragma unroll
@@ -768,36 +814,44 @@ __device__ inline float block_sum_256(float v) {
         if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
-    const float r = red[0];
+    const double r = red[0];
     __syncthreads();
     return r;
 }
 
-[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_partial(const float* __restrict__ in, int64_t n, float* __restrict__ partial) {
-    float s = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) s += in[i];
-    const float t = block_sum_256(s);
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_partial(const float* __restrict__ in, int64_t n, double* __restrict__ partial) {
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) s += (double)in[i];
+    const double t = block_sum_256(s);
     if (threadIdx.x == 0) partial[blockIdx.x] = t;
 }
 
-[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const float* __restrict__ partial, int n, bool add,
-                                                   float* __restrict__ out) {
-    const float t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.f);
-    if (threadIdx.x == 0) *out = add ? *out + t : t;
+// `carry` (one double, device) holds the running total in double across the head groups of a wide layer:
+// the first group writes it, the others add to it; *out always receives the fp32 rounding of the total
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_sum_final(const double* __restrict__ partial, int n, bool add,
+                                                   double* __restrict__ carry, float* __restrict__ out) {
+    const double t = block_sum_256((int)threadIdx.x < n ? partial[threadIdx.x] : 0.0);
+    if (threadIdx.x == 0) {
+        const double total = add ? *carry + t : t;
+        *carry = total;
+        *out = (float)total;
+    }
 }
 
 // Column sums of a row-major [n, hd] fp32 array (hd a multiple of 4) in two stages with a fixed summation
 // order: thread t of a workgroup owns the 4 columns 4 * (t % w) .. +3 and every (256 / w)-th row of the
 // workgroup's rows, four rows in flight at a time.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+__device__ inline f64x4 widen(const f32x4& v) { return f64x4{(double)v[0], (double)v[1], (double)v[2], (double)v[3]}; }
 constexpr int kRowsumBlocks = 1024;
 [[maybe_unused]] static __global__ __launch_bounds__(256) void k_rowsum_partial(const float* __restrict__ in, int64_t n, int hd, int w,
-                                                        float* __restrict__ partial) {
-    __shared__ f32x4 red[256];
+                                                        double* __restrict__ partial) {
+    __shared__ f64x4 red[256];
     const int rows_par = 256 / w, rs = threadIdx.x / w, fc = threadIdx.x % w;
     const int64_t stride = (int64_t)gridDim.x * rows_par;
     for (int f0 = 0; f0 < hd; f0 += 4 * w) {
         const int f = f0 + 4 * fc;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
         if (f < hd) {
             int64_t r = (int64_t)blockIdx.x * rows_par + rs;
             for (; r + 3 * stride < n; r += 4 * stride) {
@@ -805,34 +859,34 @@ constexpr int kRowsumBlocks = 1024;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const f32x4*>(in + (r + k * stride) * hd + f);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) acc += v[k];
+                for (int k = 0; k < 4; ++k) acc += widen(v[k]);
             }
-            for (; r < n; r += stride) acc += *reinterpret_cast<const f32x4*>(in + r * hd + f);
+            for (; r < n; r += stride) acc += widen(*reinterpret_cast<const f32x4*>(in + r * hd + f));
         }
         red[threadIdx.x] = acc;
         __syncthreads();
         if (rs == 0 && f < hd) {
-            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            f64x4 t = {0.0, 0.0, 0.0, 0.0};
             for (int k = 0; k < rows_par; ++k) t += red[k * w + fc];
-            *reinterpret_cast<f32x4*>(partial + (size_t)blockIdx.x * hd + f) = t;
+            *reinterpret_cast<f64x4*>(partial + (size_t)blockIdx.x * hd + f) = t;
         }
         __syncthreads();
     }
 }
 
 // second stage: thread t owns column t % wf and every (256 / wf)-th partial row; fixed order
-[[maybe_unused]] static __global__ __launch_bounds__(256) void k_rowsum_final(const float* __restrict__ partial, int nblocks, int hd,
+[[maybe_unused]] static __global__ __launch_bounds__(256) void k_rowsum_final(const double* __restrict__ partial, int nblocks, int hd,
                                                       int wf, float* __restrict__ out) {
-    __shared__ float red[256];
+    __shared__ double red[256];
     const int groups = 256 / wf, bs = threadIdx.x / wf, fc = threadIdx.x % wf;
     for (int f0 = 0; f0 < hd; f0 += wf) {
         const int f = f0 + fc;
-        float sum = 0.f;
+        double sum = 0.0;
         if (f < hd) {
             for (int b = bs; b < nblocks; b += 16 * groups) {
-                float v[16];
+                double v[16];
 #pragma unroll
-                for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * hd + f] : 0.f;
+                for (int k = 0; k < 16; ++k) v[k] = b + k * groups < nblocks ? partial[(size_t)(b + k * groups) * hd + f] : 0.0;
 #pragma unroll
                 for (int k = 0; k < 16; ++k) sum += v[k];
             }
@@ -840,9 +894,9 @@ constexpr int kRowsumBlocks = 1024;
         red[threadIdx.x] = sum;
         __syncthreads();
         if (bs == 0 && f < hd) {
-            float t = 0.f;
+            double t = 0.0;
             for (int k = 0; k < groups; ++k) t += red[k * wf + fc];
-            out[f] = t;
+            out[f] = (float)t;
         }
         __syncthreads();
     }

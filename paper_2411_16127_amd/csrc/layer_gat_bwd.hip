@@ -5,7 +5,7 @@
 namespace dfgnn {
 
 template <class G>
-static void run(const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r, hipStream_t st) {
+static void run(const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, float* d_a_r, hipStream_t st) {
     run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
     run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
     KernelTimer t("param_reduce", st);
@@ -15,7 +15,7 @@ static void run(const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d
     hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(1024), 0, st, reduce_tmp, kReduceBlocks, a.HD, wf, d_a_l, d_a_r);
 }
 
-int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
+int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, float* d_a_r,
                         hipStream_t st) {
     switch (geo) {
 #define X(ID, T, LPE, LPH) case ID: run<Geo<T, LPE, LPH>>(g, a, reduce_tmp, d_a_l, d_a_r, st); break;

@@ -4,7 +4,7 @@
 
 namespace dfgnn {
 
-template <class G> static void run(const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a, hipStream_t st) {
+template <class G> static void run(const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a, hipStream_t st) {
     run_pass<G, GatV2BwdRow>(g, false, a, kRowLabels, st);
     run_pass<G, GatV2BwdCol>(g, true, a, kColLabels, st);
     KernelTimer t("param_reduce", st);
@@ -20,7 +20,7 @@ template <class G> static void run(const dfgnn_graph* g, const Args& a, float* r
     hipLaunchKernelGGL(k_rowsum_final, dim3(1), dim3(256), 0, st, reduce_tmp, (int)blocks, a.HD, wf, d_a);
 }
 
-int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, hipStream_t st) {
+int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, hipStream_t st) {
     switch (geo) {
 #define X(ID, T, LPE, LPH) case ID: run<Geo<T, LPE, LPH>>(g, a, reduce_tmp, d_a_l, st); break;
         DFGNN_GEOMETRIES(X)

@@ -10,8 +10,8 @@ namespace dfgnn {
 
 constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the first is consumed
 
-// (id, type, LPE, LPH): LPH = 0 handles any head width at run time (ids 0-4 fp32, 5-9 bf16, by LPE);
-// the others are full rows of 64 or 128 features split into 1 to 16 heads, with compile-time DPP
+// (id, type, LPE, LPH): LPH = 0 handles any head width at run time (ids 0-4 fp32, 5-9 bf16, 28-32 fp16, by
+// LPE); the others are full rows of 64 or 128 features split into 1 to 16 heads, with compile-time DPP
 // reductions over the lanes of a head.
 #define DFGNN_GEOMETRIES(X)                                                                          \
     X(0, float, 4, 0) X(1, float, 8, 0) X(2, float, 16, 0) X(3, float, 32, 0) X(4, float, 64, 0)     \
@@ -19,7 +19,16 @@ constexpr int kUnroll = 4;  // neighbour rows requested per edge slot before the
     X(10, float, 16, 16) X(11, float, 16, 8) X(12, float, 16, 4) X(13, float, 16, 2)                 \
     X(14, float, 32, 32) X(15, float, 32, 16) X(16, float, 32, 8) X(17, float, 32, 4) X(18, float, 32, 2) \
     X(19, bf16_t, 16, 16) X(20, bf16_t, 16, 8) X(21, bf16_t, 16, 4) X(22, bf16_t, 16, 2) X(23, bf16_t, 16, 1) \
-    X(24, bf16_t, 8, 8) X(25, bf16_t, 8, 4) X(26, bf16_t, 8, 2) X(27, bf16_t, 8, 1)
+    X(24, bf16_t, 8, 8) X(25, bf16_t, 8, 4) X(26, bf16_t, 8, 2) X(27, bf16_t, 8, 1)                  \
+    X(28, f16_t, 4, 0) X(29, f16_t, 8, 0) X(30, f16_t, 16, 0) X(31, f16_t, 32, 0) X(32, f16_t, 64, 0) \
+    X(33, f16_t, 16, 16) X(34, f16_t, 16, 8) X(35, f16_t, 16, 4) X(36, f16_t, 16, 2) X(37, f16_t, 16, 1) \
+    X(38, f16_t, 8, 8) X(39, f16_t, 8, 4) X(40, f16_t, 8, 2) X(41, f16_t, 8, 1)
+
+// storage type of a geometry's element type as the ABI numbers it (dfgnn_dtype)
+template <typename T> struct dtype_of;
+template <> struct dtype_of<float> { static constexpr int value = DFGNN_F32; };
+template <> struct dtype_of<bf16_t> { static constexpr int value = DFGNN_BF16; };
+template <> struct dtype_of<f16_t> { static constexpr int value = DFGNN_F16; };
 
 // the same geometry with the code for the optional additive edge term compiled in
 template <class G> using with_edge_term = Geo<typename G::T, G::LPE, G::LPH, true>;
@@ -100,10 +109,10 @@ int launch_attention_gat(int geo, const dfgnn_graph* g, const Args& a, hipStream
 int launch_attention_gatv2(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_attention_agnn(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
 int launch_backward_gt(int geo, const dfgnn_graph* g, const Args& a, hipStream_t st);
-int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, float* d_a_r,
+int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, float* d_a_r,
                         hipStream_t st);
-int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_a_l, hipStream_t st);
-int launch_backward_agnn(int geo, const dfgnn_graph* g, const Args& a, float* reduce_tmp, float* d_scale, bool add_to_scale,
+int launch_backward_gatv2(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, hipStream_t st);
+int launch_backward_agnn(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_scale, bool add_to_scale,
                          hipStream_t st);
 
 }  // namespace dfgnn

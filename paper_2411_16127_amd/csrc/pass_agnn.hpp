@@ -87,6 +87,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
+                if (u == 0) this->dp0 = dp;
                 this->dsum += t;
                 dbeta = fmaf(t, cs, dbeta);
                 pc = fmaf(p, cs, pc);
@@ -151,10 +152,10 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.active) return;
         if constexpr (kExact) {
-            this->delta = this->dsum;
-            dbeta -= this->delta * pc;
+            this->delta = this->exact_delta(c);
+            dbeta = this->single_edge(c) ? 0.f : dbeta - this->delta * pc;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) ga[i] -= this->delta * px[i];
+            for (int i = 0; i < VEC; ++i) ga[i] = this->single_edge(c) ? 0.f : ga[i] - this->delta * px[i];
         }
         float o[VEC];
 #pragma unroll

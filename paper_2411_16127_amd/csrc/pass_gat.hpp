@@ -85,6 +85,7 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
             const float slope = z > 0.f ? 1.f : a.neg_slope;
             if constexpr (kExact) {
                 const float t = p * dp;
+                if (u == 0) this->dp0 = dp;
                 this->dsum += t;
                 d_el = fmaf(t, slope, d_el);
                 pl = fmaf(p, slope, pl);
@@ -129,8 +130,8 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.head0) return;
         if constexpr (kExact) {
-            this->delta = this->dsum;
-            d_el -= this->delta * pl;
+            this->delta = this->exact_delta(c);
+            d_el = this->single_edge(c) ? 0.f : d_el - this->delta * pl;
         }
         const size_t nh = (size_t)c.node * a.H + c.h;
         a.d_el[nh] = d_el;

@@ -91,6 +91,7 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float w = p * dp;
+                if (u == 0) this->dp0 = dp;
                 this->dsum += w;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) {
@@ -149,9 +150,12 @@ template <class G, int U> struct GatV2BwdRow : RowBackwardBase<G> {
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.active) return;
         if constexpr (kExact) {
-            this->delta = this->dsum;
+            this->delta = this->exact_delta(c);
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) { dx[i] -= this->delta * px[i]; da[i] -= this->delta * pa[i]; }
+            for (int i = 0; i < VEC; ++i) {
+                dx[i] = this->single_edge(c) ? 0.f : dx[i] - this->delta * px[i];
+                da[i] = this->single_edge(c) ? 0.f : da[i] - this->delta * pa[i];
+            }
         }
         float o[VEC];
 #pragma unroll

@@ -101,6 +101,7 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
+                if (u == 0) this->dp0 = dp;
                 this->dsum += t;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { dq[i] = fmaf(t, kf[i], dq[i]); pk[i] = fmaf(p, kf[i], pk[i]); }
@@ -150,9 +151,9 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
     __device__ void finalize(const Args& a, const Ctx& c) {
         if (!c.writer || !c.active) return;
         if constexpr (kExact) {
-            this->delta = this->dsum;
+            this->delta = this->exact_delta(c);
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) dq[i] -= this->delta * pk[i];
+            for (int i = 0; i < VEC; ++i) dq[i] = this->single_edge(c) ? 0.f : dq[i] - this->delta * pk[i];
         }
         float o[VEC];
 #pragma unroll

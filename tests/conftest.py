@@ -10,10 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
-    # the tests load the library that is built in-tree; only if there is none they build it (hipcc, ~1 min)
+    # the tests load the library that is built in-tree; only if there is none they build it (hipcc, ~1 min);
+    # a library that was built from other sources than the tree holds is refused
     from paper_2411_16127_amd import build as _build
-    if not os.path.exists(_build.lib_path()):
-        _build.build()
+    _build.require_current()
 
 
 def _has_gpu() -> bool:

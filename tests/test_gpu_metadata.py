@@ -18,8 +18,9 @@ def default_params(E):
     return 2 * c, c
 
 
-def check_metadata(graph, T, C):
-    g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(T, C))
+def check_metadata(graph, T, C, batch_ptr=None, flags=0):
+    """batch_ptr: build through dfgnn_graph_create_batch (metadata and batch structure in one call)."""
+    g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(T, C, flags), batch_ptr=batch_ptr)
     if C == 0:
         C = default_params(graph.nnz)[1]
     if T == 0:
@@ -57,6 +58,91 @@ def test_tiny_graphs(kind, T, C):
 def test_workload_graphs(name, shrink, T, C):
     # spans many sort tiles (4096 keys) with a ragged tail and several radix passes
     check_metadata(make_graph(make_workload(name, shrink=shrink)), T, C)
+
+
+def block_diagonal(sizes, density, seed, shuffle_rows=False, repeats=False):
+    """Batch of random graphs of the given node counts (zero allowed); optionally with the sources of every
+    row in random order and with repeated edges."""
+    from dfgnn_synth import from_edge_list
+    rng = np.random.default_rng(seed)
+    bp = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    src, dst = [], []
+    for b, n in enumerate(sizes):
+        if n == 0:
+            continue
+        adj = rng.random((n, n)) < density
+        d, s_ = np.nonzero(adj)
+        if repeats and d.size:
+            extra = rng.integers(0, d.size, d.size // 4)
+            d, s_ = np.concatenate([d, d[extra]]), np.concatenate([s_, s_[extra]])
+        if shuffle_rows:
+            perm = rng.permutation(d.size)
+            d, s_ = d[perm], s_[perm]
+        src.append(s_ + bp[b]); dst.append(d + bp[b])
+    src = np.concatenate(src) if src else np.empty(0, np.int64)
+    dst = np.concatenate(dst) if dst else np.empty(0, np.int64)
+    return from_edge_list(int(bp[-1]), src, dst, sort=not shuffle_rows, batch_ptr=bp)
+
+
+# one workgroup per graph: one radix pass up to 64 nodes, two above; empty graphs; a graph that is too large
+# for a segment sends the whole batch through the general builder; T and C small enough for super rows
+@pytest.mark.parametrize("sizes,density,T,C", [
+    ([5, 1, 17, 64, 0, 33], 0.4, 1024, 512), ([65, 130, 3, 700], 0.1, 16, 8), ([0, 0, 9], 0.5, 4, 3),
+    ([4096, 10], 0.002, 64, 32), ([4097, 10], 0.002, 64, 32), ([40] * 300, 0.3, 0, 0), ([1] * 70, 1.0, 0, 0)])
+@pytest.mark.parametrize("messy", [False, True])
+def test_batches_in_one_call(sizes, density, T, C, messy):
+    graph = block_diagonal(sizes, density, seed=len(sizes), shuffle_rows=messy, repeats=messy)
+    check_metadata(graph, T, C, batch_ptr=graph.batch_ptr)
+
+
+def test_batch_tables_of_the_one_call_route_equal_those_of_the_two_calls():
+    """Tile tables and adjacency bit masks (what the dense-tile kernels read) from dfgnn_graph_create_batch
+    against dfgnn_graph_create + dfgnn_graph_set_batch, byte for byte."""
+    import torch
+    graph = block_diagonal([30, 64, 65, 7, 512, 100, 0, 16], 0.2, seed=3)
+    one = dfgnn.Graph(graph.indptr, graph.indices, None, batch_ptr=graph.batch_ptr)
+    two = dfgnn.Graph(graph.indptr, graph.indices, None)
+    bp = torch.as_tensor(graph.batch_ptr, dtype=torch.int32).cuda()
+    n_graphs = bp.numel() - 1
+    nbytes = dfgnn.graph_batch_bytes(graph.n, n_graphs)
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dfgnn.graph_set_batch(two.handle, bp, n_graphs, buf, nbytes)
+    assert one.query("n_batch_dense") == 1 == two.query("n_batch_dense")
+    words = 8  # the largest graph has 512 nodes
+    mask_bytes = graph.n * words * 8
+    tiles = sum((n + 15) // 16 for n in [30, 64, 65, 7, 512, 100, 0, 16])
+    align = lambda x: (x + 255) // 256 * 256
+    full = align(graph.n * 8 * 8)  # the layout reserves masks of 8 words per node
+    a, b = one.batch_meta.cpu().numpy(), buf.cpu().numpy()
+    assert np.array_equal(a[:mask_bytes], b[:mask_bytes])                          # row masks
+    assert np.array_equal(a[full:full + mask_bytes], b[full:full + mask_bytes])    # column masks
+    off = 2 * full
+    assert np.array_equal(a[off:off + 4 * (n_graphs + 1)], b[off:off + 4 * (n_graphs + 1)])  # tile pointer
+    off += align(4 * (n_graphs + 2))
+    assert np.array_equal(a[off:off + 4 * tiles], b[off:off + 4 * tiles])          # graph of every tile
+    one.close(); two.close()
+
+
+def test_batch_errors_in_one_call():
+    import torch
+    graph = block_diagonal([10, 12, 9], 0.5, seed=1)
+    bad_ptr = graph.batch_ptr.copy(); bad_ptr[1] = 25  # decreasing afterwards
+    with pytest.raises(dfgnn.DfgnnError) as e:
+        dfgnn.Graph(graph.indptr, graph.indices, None, batch_ptr=bad_ptr)
+    assert e.value.status == 1 and "batch_ptr" in str(e.value)
+    cross = graph.indices.copy(); cross[0] = 30  # row 0 (first graph) reads a node of the last graph
+    with pytest.raises(dfgnn.DfgnnError) as e:
+        dfgnn.Graph(graph.indptr, cross, None, batch_ptr=graph.batch_ptr)
+    assert e.value.status == 1 and "different graphs" in str(e.value)
+    out_of_range = graph.indices.copy(); out_of_range[5] = graph.n
+    with pytest.raises(dfgnn.DfgnnError) as e:
+        dfgnn.Graph(graph.indptr, out_of_range, None, batch_ptr=graph.batch_ptr)
+    assert e.value.status == 1 and "malformed CSR" in str(e.value)
+    wrong_end = graph.indptr.copy(); wrong_end[-1] -= 1
+    for kw in ({}, {"batch_ptr": graph.batch_ptr}):  # the small-graph route of dfgnn_graph_create reports the same
+        with pytest.raises(dfgnn.DfgnnError) as e:
+            dfgnn.Graph(wrong_end, graph.indices, None, **kw)  # indptr[N] != E
+        assert e.value.status == 1 and "malformed CSR" in str(e.value)
 
 
 def test_graph_from_an_unsorted_edge_list():

@@ -45,9 +45,22 @@ def test_tiny_graphs_bf16(model, H, D):
     g.close()
 
 
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
+@pytest.mark.parametrize("H,D", SHAPES_BF16)
+@pytest.mark.parametrize("kind", ["hub", "chain", "empty"])
+def test_tiny_graphs_f16(model, H, D, kind):
+    graph = tiny_graph(kind, seed=3, n=70)
+    w = Workload("tiny", 92, model, H, D, "f16", {"gt": float(1.0 / np.sqrt(D)), "agnn": 1.3}.get(model, 1.0))
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(8, 5))
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
 # rows of 64 or 128 features split into 1 to 16 heads: every lane geometry with compile-time head reductions
 FULL_ROW_SHAPES = [("f32", H, 64 // H) for H in (1, 2, 4, 8)] + [("f32", H, 128 // H) for H in (1, 2, 4, 8, 16)] + \
-                  [("bf16", H, 128 // H) for H in (1, 2, 4, 8, 16)] + [("bf16", H, 64 // H) for H in (1, 2, 4, 8)]
+                  [("bf16", H, 128 // H) for H in (1, 2, 4, 8, 16)] + [("bf16", H, 64 // H) for H in (1, 2, 4, 8)] + \
+                  [("f16", H, 128 // H) for H in (1, 2, 4, 8, 16)] + [("f16", H, 64 // H) for H in (1, 2, 4, 8)]
 
 
 @pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
@@ -63,7 +76,7 @@ def test_full_row_geometries(model, dtype, H, D):
 
 # rows wider than one wavefront of 16-byte lanes: the layer runs in groups of heads
 WIDE_SHAPES = [("f32", 8, 64), ("f32", 3, 128), ("f32", 2, 256), ("f32", 16, 32), ("bf16", 16, 64), ("bf16", 3, 256),
-               ("f32", 5, 64)]
+               ("f32", 5, 64), ("f16", 16, 64)]
 
 
 @pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
@@ -142,10 +155,24 @@ def test_workloads_reduced(name, shrink, T, C):
     g.close()
 
 
+# the large workloads with bf16 node tensors (half the row bytes; feature-dimension study of Appendix C)
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("name,shrink,T,C", [("cfg3", 8, 0, 0), ("cfg3", 8, 128, 64), ("cfg4", 16, 0, 0),
+                                             ("cfg5", 256, 0, 0), ("cfg5", 256, 96, 40), ("cfg2", 8, 0, 0)])
+def test_workloads_reduced_16_bit(name, shrink, T, C, dtype):
+    w = make_workload(name, shrink=shrink, dtype=dtype)
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats, dfgnn.SchedParams(T, C) if T else None)
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
 # ------------------------------------------------------------------ full benchmark sizes
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4"])
-def test_workloads_full_size(name):
-    w = make_workload(name)
+@pytest.mark.parametrize("name,dtype", [("cfg1", None), ("cfg2", None), ("cfg3", None), ("cfg4", None),
+                                        ("cfg3", "bf16"), ("cfg4", "bf16"), ("cfg3", "f16"), ("cfg4", "f16")])
+def test_workloads_full_size(name, dtype):
+    w = make_workload(name, **({"dtype": dtype} if dtype else {}))
     graph = make_graph(w)
     feats = make_features(w, graph.n)
     res, g = run_gpu(graph, w, feats)  # default scheduling parameters, as the benchmark runs it
@@ -153,24 +180,37 @@ def test_workloads_full_size(name):
     g.close()
 
 
-def test_cfg5_full_size_sampled():
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_cfg5_full_size_sampled(dtype):
     """123M edges: the oracle evaluates sampled nodes one by one (rows for O / dQ, and every row that a
-    sampled node feeds for its dK / dV), the GPU runs the whole graph."""
-    w = make_workload("cfg5")
+    sampled node feeds for its dK / dV), the GPU runs the whole graph with the default schedule, as the
+    benchmark does.  The sampled columns include super columns (out-degree >= super_threshold), whose dK / dV
+    go through the chunk + merge path of the column pass: the column of largest out-degree and the two
+    closest to the threshold from above."""
+    w = make_workload("cfg5", dtype=dtype)
     graph = make_graph(w)
     feats = make_features(w, graph.n)
+    print(f"cfg5 {dtype}: graph and features drawn", flush=True)
     res, g = run_gpu(graph, w, feats)
+    print("GPU pass done; oracle on the sampled rows and columns", flush=True)
+    T = g.query("n_super_threshold")
     deg = graph.degrees()
     rng = np.random.default_rng(77)
     sample = np.unique(np.concatenate([rng.choice(graph.n, 48, replace=False), np.argsort(deg)[-3:],
                                        np.argsort(deg)[:2]]))
     out_deg = np.bincount(graph.indices, minlength=graph.n)
-    light = sample[out_deg[sample] < 400]  # columns whose feeding rows the oracle can afford
+    light = sample[out_deg[sample] < 400]  # columns with few feeding rows
+    by_out = np.argsort(out_deg, kind="stable")
+    first_super = int(np.searchsorted(out_deg[by_out], T))
+    assert g.query("n_super_cols") == graph.n - first_super > 3
+    heavy = np.concatenate([by_out[first_super:first_super + 2], by_out[-1:]])  # super columns
+    assert np.all(out_deg[heavy] >= T)
+    cols = np.union1d(light, heavy)
     rows_of_edges = graph.rows_of_edges()
-    feed = np.unique(rows_of_edges[np.isin(graph.indices, light)])
+    feed = np.unique(rows_of_edges[np.isin(graph.indices, cols)])
     ref = run_oracle(graph, w, feats, rows=sample, backward_rows=np.union1d(sample, feed))
     compare_all(res, ref, w, rows=sample, keys=["out", "row_max", "row_sum", "d_x"])
-    compare_all(res, ref, w, rows=light, keys=["d_k", "d_v"])
+    compare_all(res, ref, w, rows=cols, keys=["d_k", "d_v"])
     g.close()
 
 

@@ -23,19 +23,7 @@ SCALES = {"gt": None, "gat": 1.0, "agnn": 1.3, "gatv2": 1.0}
 
 
 def compare_with_oracle(res, ref, w, graph):
-    """compare_all, except where no row has more than one edge.  Then dS = 0 and every gradient that flows
-    through the scores is exactly zero; a bf16 layer computes it as a difference of two equal fp32 terms of
-    size |dP| |k| (the exact-delta form of its row pass), whose rounding residue (some 1e-5 for 64-wide heads)
-    the element-wise bounds, relative to a reference of zero, cannot describe: those tensors get an
-    absolute bound of 1e-4 here."""
-    single = int(np.diff(graph.indptr).max(initial=0)) <= 1 and w.dtype == "bf16"
-    through_scores = [key for key in ("d_a_l", "d_a_r", "d_scale", "d_edge_bias") if key in ref]
-    through_scores += [key for key in ("d_x", "d_k") if key in ref and w.model in ("gt", "gatv2")]
-    if not single:
-        return compare_all(res, ref, w)
-    rest = [key for key in ("out", "row_max", "row_sum", "d_x", "d_k", "d_v") if key in ref and key not in through_scores]
-    compare_all(res, ref, w, keys=rest)
-    compare_all(res, ref, w, keys=through_scores, tol=(2e-2, 1e-4, 0.0))
+    return compare_all(res, ref, w)
 
 
 def draw_case(seed):
@@ -43,6 +31,8 @@ def draw_case(seed):
     model = ["gt", "gat", "agnn", "gatv2"][seed % 4]
     dtype = "bf16" if rng.random() < 0.4 else "f32"
     H, D = SHAPES[dtype][int(rng.integers(len(SHAPES[dtype])))]
+    if dtype == "bf16" and seed % 3 == 0:  # a third of the 16-bit cases store fp16 (same shapes)
+        dtype = "f16"
     kind = KINDS[int(rng.integers(len(KINDS)))]
     n = int(rng.integers(8, 400))
     T = int(rng.choice([4, 8, 16, 64, 0]))          # 0: library default
