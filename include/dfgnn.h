@@ -229,6 +229,27 @@ int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer, const void
                   size_t workspace_bytes, void* stream);
 
 /*
+ * dfgnn_forward for callers that cannot allocate device memory for a workspace (code recorded under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same computation with the same
+ * kernels and bit-identical results, but the chunk partials of super rows are kept in a static device
+ * array of DFGNN_STATIC_SCRATCH_BYTES owned by the library (each GPU that uses the library holds it until
+ * the process ends).  The call allocates and frees nothing, on the host side of HIP or on the device.
+ *  - Limit: the forward workspace of this graph and layer (fwd_bytes of dfgnn_workspace_bytes) must not
+ *    exceed DFGNN_STATIC_SCRATCH_BYTES, else EWORKSPACE and nothing is launched (about 29,000 chunks of
+ *    128-feature rows; graphs with more chunk work need dfgnn_forward and a caller workspace).
+ *  - The GPU of `stream` must be the calling thread's current device.  The first call on a GPU looks up the
+ *    array's address there; make that first call outside stream capture.
+ *  - Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different streams,
+ *    different threads) race and must be ordered by the caller.  Calls on one stream are ordered already.
+ *  - The array keeps the previous call's contents; the forward pass needs no part of it cleared.
+ * Arguments, layouts and errors otherwise as dfgnn_forward.
+ */
+#define DFGNN_STATIC_SCRATCH_BYTES (16u << 20)
+int dfgnn_forward_static(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                         const void* v, const float* a_l, const float* a_r, void* out, float* row_max,
+                         float* row_sum, void* stream);
+
+/*
  * Backward (Appendix B; the fused SDDMM -> softmax-backward -> SpMM chain of Sec. 4.3 over the CSR,
  * and the transposed products over the CSC).  Inputs are those of the forward call plus its results
  * out, row_max, row_sum and the upstream gradient d_out = dL/dO [N,H,D].

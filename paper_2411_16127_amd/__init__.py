@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     graph_query,
     workspace_bytes,
     forward,
+    forward_static,
     backward,
     forward_edge_bias,
     backward_edge_bias,

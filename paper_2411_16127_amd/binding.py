@@ -96,6 +96,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_graph_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.dfgnn_workspace_bytes.argtypes = [vp, vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.dfgnn_forward.argtypes = [vp, vp] + [vp] * 8 + [vp, sz, vp]
+        L.dfgnn_forward_static.argtypes = [vp, vp] + [vp] * 8 + [vp]
         L.dfgnn_backward.argtypes = [vp, vp] + [vp] * 15 + [vp, sz, vp]
         L.dfgnn_forward_edge_bias.argtypes = [vp, vp] + [vp] * 9 + [vp, sz, vp]
         L.dfgnn_attention_weights.argtypes = [vp, vp] + [vp] * 8 + [vp]
@@ -104,7 +105,7 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
         for name in ("dfgnn_graph_create_batch", "dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
-                     "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward",
+                     "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward", "dfgnn_forward_static",
                      "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias", "dfgnn_attention_weights"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -228,6 +229,13 @@ def forward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, work
     _check(lib().dfgnn_forward(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r), _ptr(out),
                                _ptr(row_max), _ptr(row_sum), _ptr(workspace), workspace_bytes_, _stream(stream)),
            "dfgnn_forward")
+
+
+def forward_static(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, stream=None) -> None:
+    """dfgnn_forward with the library's static scratch in place of a caller workspace (allocates nothing)."""
+    cl = layer._c()
+    _check(lib().dfgnn_forward_static(handle, ctypes.byref(cl), _ptr(x), _ptr(k), _ptr(v), _ptr(a_l), _ptr(a_r),
+                                      _ptr(out), _ptr(row_max), _ptr(row_sum), _stream(stream)), "dfgnn_forward_static")
 
 
 def backward(handle, layer: Layer, x, k, v, a_l, a_r, out, row_max, row_sum, d_out, d_x, d_k, d_v, d_a_l, d_a_r,

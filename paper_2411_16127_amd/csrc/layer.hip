@@ -3,7 +3,34 @@
 // column pass).  Every launch goes to the caller's stream; nothing here synchronises or allocates.
 #include "layer_launch.hpp"
 
+#include <mutex>
+
+// Library-owned scratch memory for dfgnn_forward_static: callers that cannot provide (allocate) a workspace
+// get the forward pass's chunk partials placed here.  The array exists once per GPU that loads the library;
+// in host code its name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[DFGNN_STATIC_SCRATCH_BYTES];
+
 namespace dfgnn {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, resolved on first use
+
+// Device address of this GPU's copy of `scratch` (the calling thread's current device).
+static int static_scratch(void** out) {
+    int dev = -1;
+    DFGNN_HIP(hipGetDevice(&dev));
+    DFGNN_REQUIRE(dev >= 0 && dev < kMaxDevices, DFGNN_EUNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        DFGNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        DFGNN_REQUIRE(p != nullptr && ((uintptr_t)p % kAlign) == 0, DFGNN_EHIP, "static scratch resolved to %p", p);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DFGNN_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 // lane geometry
@@ -330,6 +357,27 @@ extern "C" int dfgnn_forward(const dfgnn_graph* graph, const dfgnn_layer* layer,
                              float* row_sum, void* workspace, size_t workspace_bytes, void* stream) {
     return forward_impl(graph, layer, x, k, v, a_l, a_r, nullptr, out, row_max, row_sum, workspace, workspace_bytes,
                         stream);
+}
+
+extern "C" int dfgnn_forward_static(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
+                                    const void* v, const float* a_l, const float* a_r, void* out, float* row_max,
+                                    float* row_sum, void* stream) {
+    clear_error();
+    Geometry geo;
+    int rc = check_layer(graph, layer, &geo);
+    if (rc != DFGNN_OK) return rc;
+    const size_t need = workspace_layout(graph, layer, false, geo.heads).total;
+    DFGNN_REQUIRE(need <= (size_t)DFGNN_STATIC_SCRATCH_BYTES, DFGNN_EWORKSPACE,
+                  "this graph and layer need %zu bytes of forward workspace, the library's static scratch holds %zu: "
+                  "use dfgnn_forward with a caller-provided workspace",
+                  need, (size_t)DFGNN_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != DFGNN_OK) return rc;
+    // nothing in the forward workspace has to start at zero: every chunk partial is written by the pass
+    // kernel before the merge kernel of the same call reads it
+    return forward_impl(graph, layer, x, k, v, a_l, a_r, nullptr, out, row_max, row_sum, ws,
+                        (size_t)DFGNN_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int dfgnn_forward_edge_bias(const dfgnn_graph* graph, const dfgnn_layer* layer, const void* x, const void* k,
