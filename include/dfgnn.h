@@ -192,10 +192,10 @@ int dfgnn_graph_query(const dfgnn_graph* graph, int what, const void** d_ptr, in
  * the preprocessing of Sec. 5.3 (CSR, CSC, schedule) is paid for every mini-batch and has to cost about
  * what a training step costs.  Arguments as in those two calls; the result (every metadata array, the
  * batch tables) is bit for bit what they would produce.  When every graph of the batch has at most 4096
- * nodes and 262144 edges the metadata is built by one workgroup per graph in three launches with one
+ * nodes and 65536 edges the metadata is built by one workgroup per graph in three launches with one
  * synchronisation of `stream` (two when the batch has super rows or columns); other batches, forward-only
  * graphs and the scores-in-memory comparator go through the two general calls internally.
- * dfgnn_graph_create itself builds a graph of at most 4096 nodes and 262144 edges (without batch
+ * dfgnn_graph_create itself builds a graph of at most 4096 nodes and 65536 edges (without batch
  * structure) the same way, in one launch.
  * Errors: those of dfgnn_graph_create and dfgnn_graph_set_batch.
  */

@@ -553,6 +553,27 @@ static int prepare_build(Build& B, dfgnn_graph** out, int64_t N, int64_t E, cons
     return DFGNN_OK;
 }
 
+// Counters come back through a small page-locked staging block per host thread (allocated on first use and
+// kept): a copy to pageable memory goes through the runtime's own staging and costs tens of microseconds.
+static int* readback_block() {
+    thread_local int* block = nullptr;
+    if (block == nullptr) {
+        void* p = nullptr;
+        if (hipHostMalloc(&p, CNT_TOTAL * sizeof(int), hipHostMallocDefault) == hipSuccess) block = (int*)p;
+        else (void)hipGetLastError();
+    }
+    return block;
+}
+// n ints from device memory to dst, then a synchronisation of the stream
+static int read_back(int* dst, const int* d_src, int n, hipStream_t st) {
+    int* block = readback_block();
+    int* via = block ? block : dst;
+    DFGNN_HIP(hipMemcpyAsync(via, d_src, (size_t)n * sizeof(int), hipMemcpyDeviceToHost, st));
+    DFGNN_HIP(hipStreamSynchronize(st));
+    if (via != dst) memcpy(dst, via, (size_t)n * sizeof(int));
+    return DFGNN_OK;
+}
+
 static const char kCsrErrorText[] =
     "malformed CSR (flags 0x%x: 1 indptr[0]!=0, 2 indptr[N]!=E, 4 indptr decreases, 8 indptr out of range, 16 index out "
     "of range)";
@@ -576,8 +597,8 @@ static int build_general(Build& B, int* locality_stride) {
         hipLaunchKernelGGL(k_validate, dim3((unsigned)((span + tpb - 1) / tpb)), dim3(tpb), 0, st, d_indptr, d_indices,
                            (int)N, (int)E, d_counters + CNT_ERROR);
         int bad = 0;
-        DFGNN_HIP(hipMemcpyAsync(&bad, d_counters + CNT_ERROR, sizeof(int), hipMemcpyDeviceToHost, st));
-        DFGNN_HIP(hipStreamSynchronize(st));
+        rc = read_back(&bad, d_counters + CNT_ERROR, 1, st);
+        if (rc != DFGNN_OK) return rc;
         DFGNN_REQUIRE(bad == 0, DFGNN_EINVAL, kCsrErrorText, bad);
     }
 
@@ -656,6 +677,7 @@ static int build_local(Build& B, const int32_t* d_batch_ptr, int64_t n_graphs, i
     a.row_order = g.row_order; a.col_order = g.col_order;
     a.keys_tmp = (uint32_t*)(B.scratch + B.S.keys_a);
     a.vals_tmp = (int*)(B.scratch + B.S.vals);
+    a.edge_row = (int*)(B.scratch + B.S.keys_b);
     a.seg_hist = seg_tmp;
     a.seg_off = seg_tmp + (size_t)a.n_seg * kSegKeys;
     a.key_total = seg_tmp + (size_t)a.n_seg * kSegKeys * 2;
@@ -677,8 +699,8 @@ static int finish_build(Build& B, bool local, int locality_stride, int* host_cou
     hipStream_t st = B.st;
     int* d_counters = B.d_counters;
     const bool fwd_only = g.flags & DFGNN_SCHED_FORWARD_ONLY;
-    DFGNN_HIP(hipMemcpyAsync(host_counters, d_counters, CNT_TOTAL * sizeof(int), hipMemcpyDeviceToHost, st));
-    DFGNN_HIP(hipStreamSynchronize(st));
+    int rc = read_back(host_counters, d_counters, CNT_TOTAL, st);
+    if (rc != DFGNN_OK) return rc;
     if (local) {
         if (host_counters[CNT_SEG_FLAGS]) return DFGNN_OK;  // a segment was too large: the caller falls back
         DFGNN_REQUIRE(host_counters[CNT_ERROR] == 0, DFGNN_EINVAL, kCsrErrorText, host_counters[CNT_ERROR]);
@@ -692,15 +714,15 @@ static int finish_build(Build& B, bool local, int locality_stride, int* host_cou
     g.n_super_cols = g.col_bucket_ptr[1];
     if (g.n_super_rows > 0 || g.n_super_cols > 0) {
         const int64_t max_chunks = chunk_capacity(E, g.T, g.C);
-        int rc = schedule_chunks(g.indptr, g.n_super_rows, g.C, g.row_order, g.row_chunk_ptr, g.row_chunks, max_chunks,
+        rc = schedule_chunks(g.indptr, g.n_super_rows, g.C, g.row_order, g.row_chunk_ptr, g.row_chunks, max_chunks,
                                  d_counters, CNT_ROW_CHUNKS, B.scratch, B.S, st);
         if (rc != DFGNN_OK) return rc;
         rc = schedule_chunks(g.t_indptr, g.n_super_cols, g.C, g.col_order, g.col_chunk_ptr, g.col_chunks, max_chunks,
                              d_counters, CNT_COL_CHUNKS, B.scratch, B.S, st);
         if (rc != DFGNN_OK) return rc;
         int n_chunks[4] = {0, 0, 0, 0};  // counters CNT_ROW_CHUNKS .. CNT_COL_CHUNKS
-        DFGNN_HIP(hipMemcpyAsync(n_chunks, d_counters + CNT_ROW_CHUNKS, 3 * sizeof(int), hipMemcpyDeviceToHost, st));
-        DFGNN_HIP(hipStreamSynchronize(st));
+        rc = read_back(n_chunks, d_counters + CNT_ROW_CHUNKS, 3, st);
+        if (rc != DFGNN_OK) return rc;
         g.n_row_chunks = n_chunks[0];
         g.n_col_chunks = n_chunks[CNT_COL_CHUNKS - CNT_ROW_CHUNKS];
     }
