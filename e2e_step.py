@@ -2,7 +2,7 @@
 projections, ReLU and the optimiser around the fused graph convolutions of this library (the shape of the
 paper's end-to-end comparison, Sec. 5.3: forward + backward + update of a few layers on one graph).
 
-    python -m paper_2411_16127_amd.e2e_step --workload cfg3 --model gat --layers 2 --steps 20
+    python e2e_step.py --workload cfg3 --model gat --layers 2 --steps 20
 
 Prints one JSON line: milliseconds per training step and the share spent inside the fused kernels.
 """
@@ -14,7 +14,7 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 

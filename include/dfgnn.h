@@ -215,7 +215,11 @@ int dfgnn_workspace_bytes(const dfgnn_graph* graph, const dfgnn_layer* layer, si
  * Forward: O_i = sum_{j in N(i)} softmax_j(s_ij) Val_j per head (Eq. 1; edge softmax of Appendix A).
  *   GT   s_ij = scale * q_i . k_j                         x = Q, k = K, v = V (Val = V)
  *   GAT  s_ij = LeakyReLU(a_l . Wh_i + a_r . Wh_j)        x = Wh, a_l, a_r [H, D] fp32 device (Val = Wh); k = v = NULL
- *   AGNN s_ij = beta * cos(h_i, h_j) per head             x = h (Val = h, un-normalised); k = v = a_l = a_r = NULL
+ *   AGNN s_ij = beta * cos(h_i, h_j) per head             x = h (Val = h, un-normalised); k = v = a_r = NULL; a_l = NULL (beta is
+ *                                                         layer->scale) or a device pointer to one fp32 value that holds beta
+ *                                                         (layer->scale is ignored then: a trained beta stays on the device and
+ *                                                         the call can be recorded into a HIP graph); the same in dfgnn_backward
+ *                                                         and dfgnn_attention_weights
  *   GATv2 s_ij = sum_d a_d LeakyReLU(x_i,d + k_j,d)       x = destination-side, k = source-side projection of the
  *        (the other member of the GAT family cited in       node features (Val = k), a_l = a [H, D] fp32 device;
  *         Sec. 1; its score is not separable per node)       v = a_r = NULL
@@ -255,7 +259,7 @@ int dfgnn_forward_static(const dfgnn_graph* graph, const dfgnn_layer* layer, con
  * out, row_max, row_sum and the upstream gradient d_out = dL/dO [N,H,D].
  *   GT   -> d_x = dL/dQ, d_k = dL/dK, d_v = dL/dV                        (d_a_l = d_a_r = d_scale = NULL)
  *   GAT  -> d_x = dL/dWh, d_a_l, d_a_r [H,D] fp32                        (d_k = d_v = d_scale = NULL)
- *   AGNN -> d_x = dL/dh, d_scale = dL/dbeta (1 float, device)            (d_k = d_v = d_a_l = d_a_r = NULL)
+ *   AGNN -> d_x = dL/dh, d_scale = dL/dbeta (1 float, device)            (d_k = d_v = d_a_l = d_a_r = NULL; a_l as in dfgnn_forward)
  *   GATv2 -> d_x, d_k (destination- and source-side), d_a_l = dL/da      (d_v = d_a_r = d_scale = NULL)
  * Gradient node tensors are in the layer dtype.  workspace: >= bwd_bytes, 256-byte aligned.
  * Results are deterministic (no floating-point atomics).

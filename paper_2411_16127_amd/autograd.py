@@ -74,23 +74,27 @@ def gatv2_conv(graph: Graph, x_dst, x_src, a, neg_slope: float = 0.2):
 
 
 class _AgnnConv(torch.autograd.Function):
-    """AGNN needs the gradient of the scalar beta, which is a layer field rather than a tensor argument."""
+    """AGNN needs the gradient of the scalar beta.  A beta that lives on the GPU (a trained parameter) is handed to
+    the library as a device pointer, so neither call reads it back to the host."""
 
     @staticmethod
     def forward(ctx, graph: Graph, h, beta, eps: float):
+        on_device = beta.is_cuda
+        beta_dev = beta.detach().reshape(1).to(torch.float32).contiguous() if on_device else None
         layer = Layer("agnn", h.shape[1], h.shape[2], dtype=dtype_name(h.dtype),
-                      scale=float(beta.detach().float().cpu()), eps=eps)
+                      scale=1.0 if on_device else float(beta.detach()), eps=eps)
         h = h.contiguous()
-        out, row_max, row_sum = graph.forward(layer, h)
+        out, row_max, row_sum = graph.forward(layer, h, a_l=beta_dev)
         ctx.graph, ctx.layer = graph, layer
-        ctx.save_for_backward(h, out, row_max, row_sum, beta)
+        ctx.save_for_backward(h, out, row_max, row_sum, beta, *((beta_dev,) if on_device else ()))
         return out
 
     @staticmethod
     def backward(ctx, d_out):
-        h, out, row_max, row_sum, beta = ctx.saved_tensors
-        g = ctx.graph.backward(ctx.layer, h, None, None, None, None, out, row_max, row_sum, d_out.contiguous())
-        return None, g["d_x"], g["d_scale"].to(beta.dtype).reshape(beta.shape), None
+        h, out, row_max, row_sum, beta, *rest = ctx.saved_tensors
+        g = ctx.graph.backward(ctx.layer, h, None, None, rest[0] if rest else None, None, out, row_max, row_sum,
+                               d_out.contiguous())
+        return None, g["d_x"], g["d_scale"].to(dtype=beta.dtype, device=beta.device).reshape(beta.shape), None
 
 
 def agnn_conv(graph: Graph, h, beta, eps: float = 1e-12):

@@ -412,7 +412,10 @@ class Graph:
             if t.dtype != want or t.numel() != self.N * layer.H * layer.D or t.device != self.device:
                 raise ValueError(f"node tensor must be {want} with {self.N}x{layer.H}x{layer.D} elements on {self.device}")
         for t in head_tensors:
-            if t is not None and (t.dtype != torch.float32 or t.numel() != layer.H * layer.D):
+            if layer.model == "agnn":  # a_l carries beta: one float32 value on the device
+                if t is not None and (t.dtype != torch.float32 or t.numel() != 1 or t.device != self.device):
+                    raise ValueError(f"AGNN: a_l must be one float32 value on {self.device} (beta)")
+            elif t is not None and (t.dtype != torch.float32 or t.numel() != layer.H * layer.D):
                 raise ValueError("attention vectors must be float32 [H, D]")
         for t in stat_tensors:
             if t is not None and (t.dtype != torch.float32 or t.numel() != self.N * layer.H):

@@ -270,7 +270,8 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
-    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2,
+               agnn = layer->model == DFGNN_AGNN;
     if (graph->N == 0) return DFGNN_OK;  // nothing to compute; node tensors have no elements and may be NULL
     DFGNN_REQUIRE(x && out && row_max && row_sum, DFGNN_EINVAL, "x / out / row_max / row_sum is NULL");
     DFGNN_REQUIRE(!gt || (k && v), DFGNN_EINVAL, "GT needs k and v");
@@ -278,9 +279,11 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
     DFGNN_REQUIRE(gt || v2 || (!k && !v), DFGNN_EINVAL, "k and v must be NULL unless the model is GT or GATv2");
     DFGNN_REQUIRE(!gat || (a_l && a_r), DFGNN_EINVAL, "GAT needs a_l and a_r");
     DFGNN_REQUIRE(!v2 || (a_l && !a_r), DFGNN_EINVAL, "GATv2 needs a_l, and a_r must be NULL");
-    DFGNN_REQUIRE(gat || v2 || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT or GATv2");
-    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(a_l) && aligned16(a_r),
+    DFGNN_REQUIRE(gat || v2 || agnn || (!a_l && !a_r), DFGNN_EINVAL, "a_l and a_r must be NULL unless the model is GAT or GATv2");
+    DFGNN_REQUIRE(!agnn || !a_r, DFGNN_EINVAL, "AGNN: a_r must be NULL (a_l may point to beta on the device)");
+    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && (agnn || aligned16(a_l)) && aligned16(a_r),
                   DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+    DFGNN_REQUIRE(((uintptr_t)a_l & 3u) == 0, DFGNN_EUNSUPPORTED, "beta must be 4-byte aligned");
     DFGNN_REQUIRE(((uintptr_t)edge_bias & 3u) == 0, DFGNN_EUNSUPPORTED, "edge_bias must be 4-byte aligned");
     DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
                   "edge term of E*H*4 bytes must stay below 4 GiB");
@@ -300,7 +303,8 @@ static int forward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, cons
                   workspace_bytes, W.total);
     Args a{};
     fill_common(a, graph, layer, geo);
-    a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
+    a.x = x; a.k = k; a.v = v; a.a_l = agnn ? nullptr : a_l; a.a_r = a_r;
+    a.scale_dev = agnn ? a_l : nullptr;
     a.o = out; a.o_max = row_max; a.o_sum = row_sum;
     a.idx = graph->indices; a.edge_row = graph->edge_row; a.n_edges = (int)graph->E;
     a.bias = edge_bias;
@@ -323,21 +327,23 @@ extern "C" int dfgnn_attention_weights(const dfgnn_graph* graph, const dfgnn_lay
     Geometry geo;
     int rc = check_layer(graph, layer, &geo);
     if (rc != DFGNN_OK) return rc;
-    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2;
+    const bool gt = layer->model == DFGNN_GT, gat = layer->model == DFGNN_GAT, v2 = layer->model == DFGNN_GATV2,
+               agnn = layer->model == DFGNN_AGNN;
     if (graph->N == 0 || graph->E == 0) return DFGNN_OK;  // no edge, nothing to write
     DFGNN_REQUIRE(x && row_max && row_sum && p, DFGNN_EINVAL, "x / row_max / row_sum / p is NULL");
     DFGNN_REQUIRE((gt || v2) == (k != nullptr), DFGNN_EINVAL, "k is needed by GT and GATv2 and by no other model");
-    DFGNN_REQUIRE((gat || v2) == (a_l != nullptr) && gat == (a_r != nullptr), DFGNN_EINVAL,
-                  "GAT needs a_l and a_r, GATv2 a_l, the other models neither");
-    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(a_l) && aligned16(a_r), DFGNN_EUNSUPPORTED,
-                  "device pointers must be 16-byte aligned");
+    DFGNN_REQUIRE((agnn || (gat || v2) == (a_l != nullptr)) && gat == (a_r != nullptr), DFGNN_EINVAL,
+                  "GAT needs a_l and a_r, GATv2 a_l, GT neither; AGNN may pass beta on the device in a_l");
+    DFGNN_REQUIRE(aligned16(x) && aligned16(k) && (agnn || aligned16(a_l)) && aligned16(a_r) && ((uintptr_t)a_l & 3u) == 0,
+                  DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned (beta: 4-byte)");
     DFGNN_REQUIRE((((uintptr_t)edge_bias | (uintptr_t)p) & 3u) == 0, DFGNN_EUNSUPPORTED, "edge_bias / p must be 4-byte aligned");
     DFGNN_REQUIRE(!edge_bias || edge_term_fits(graph, layer), DFGNN_EUNSUPPORTED,
                   "edge term of E*H*4 bytes must stay below 4 GiB");
     Args a{};
     fill_common(a, graph, layer, geo);
     a.x = x; a.k = k; a.v = k;  // no value tensor is read; GT's value gathers are dropped by the compiler
-    a.a_l = a_l; a.a_r = a_r;
+    a.a_l = agnn ? nullptr : a_l; a.a_r = a_r;
+    a.scale_dev = agnn ? a_l : nullptr;
     a.row_max = row_max; a.row_sum = row_sum;
     a.bias = edge_bias;
     a.bias_bytes = (uint32_t)((uint64_t)graph->E * layer->H * 4u);
@@ -418,13 +424,13 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
     DFGNN_REQUIRE(!gat || (a_l && a_r && d_a_l && d_a_r), DFGNN_EINVAL, "GAT needs a_l, a_r, d_a_l and d_a_r");
     DFGNN_REQUIRE(!v2 || (a_l && d_a_l && !a_r && !d_a_r), DFGNN_EINVAL,
                   "GATv2 needs a_l and d_a_l; a_r and d_a_r must be NULL");
-    DFGNN_REQUIRE(gat || v2 || (!a_l && !a_r && !d_a_l && !d_a_r), DFGNN_EINVAL,
-                  "a_l, a_r, d_a_l, d_a_r must be NULL unless the model is GAT or GATv2");
+    DFGNN_REQUIRE(gat || v2 || (!a_r && !d_a_l && !d_a_r && (agnn || !a_l)), DFGNN_EINVAL,
+                  "a_l, a_r, d_a_l, d_a_r must be NULL unless the model is GAT or GATv2 (AGNN: a_l may point to beta)");
     DFGNN_REQUIRE(!agnn || d_scale, DFGNN_EINVAL, "AGNN needs d_scale");
     DFGNN_REQUIRE(agnn || !d_scale, DFGNN_EINVAL, "d_scale must be NULL unless the model is AGNN");
     DFGNN_REQUIRE(aligned16(x) && aligned16(k) && aligned16(v) && aligned16(out) && aligned16(d_out) && aligned16(d_x) &&
-                      aligned16(d_k) && aligned16(d_v) && aligned16(a_l) && aligned16(a_r),
-                  DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned");
+                      aligned16(d_k) && aligned16(d_v) && (agnn || aligned16(a_l)) && aligned16(a_r) && ((uintptr_t)a_l & 3u) == 0,
+                  DFGNN_EUNSUPPORTED, "device pointers must be 16-byte aligned (beta: 4-byte)");
     DFGNN_REQUIRE((((uintptr_t)edge_bias | (uintptr_t)d_edge_bias) & 3u) == 0, DFGNN_EUNSUPPORTED,
                   "edge_bias / d_edge_bias must be 4-byte aligned");
     DFGNN_REQUIRE(edge_bias || !d_edge_bias, DFGNN_EINVAL, "d_edge_bias without edge_bias");
@@ -455,7 +461,8 @@ static int backward_impl(const dfgnn_graph* graph, const dfgnn_layer* layer, con
 
     Args a{};
     fill_common(a, graph, layer, geo);
-    a.x = x; a.k = k; a.v = v; a.a_l = a_l; a.a_r = a_r;
+    a.x = x; a.k = k; a.v = v; a.a_l = agnn ? nullptr : a_l; a.a_r = a_r;
+    a.scale_dev = agnn ? a_l : nullptr;
     a.out = out; a.row_max = row_max; a.row_sum = row_sum; a.d_out = d_out;
     a.d_x = d_x; a.d_k = d_k; a.d_v = d_v;
     a.bias = edge_bias; a.d_bias = d_edge_bias;

@@ -188,6 +188,7 @@ struct Args {
     int n_direct, blocks_direct;            // whole-row items: order[first_direct + item]
     int n_small, first_small, first_direct; // short rows: order[first_small + r], one per edge slot
     int n_items;                            // merge kernel: super rows
+    int merge_groups;                       // merge kernels: largest number of chunk groups per super row (1: one level)
     int xcd_group;                          // workgroups per XCD-local run of the work list (0: no remapping)
     int n_nodes;
     uint32_t row_bytes;     // bytes of one node row
@@ -201,6 +202,7 @@ struct Args {
     int row_stride, stat_stride, bias_stride;
     float c_score;  // GT scale*log2(e); AGNN beta*log2(e); GAT log2(e)
     float scale;    // GT scale; AGNN beta
+    const float* scale_dev;  // AGNN: beta read from device memory instead (nullptr: the value above)
     float neg_slope, eps, inv_eps;
     // tensors in the layer dtype
     const void *x, *k, *v, *out, *d_out;
@@ -233,6 +235,9 @@ struct Args {
     const int* edge_row;  // [E] destination row of every CSR position
     int n_edges;
 };
+
+// AGNN's beta: a layer field, or one float in device memory (so that a trained beta never has to visit the host)
+__device__ inline float agnn_beta(const Args& a) { return a.scale_dev ? *a.scale_dev : a.scale; }
 
 // Lane geometry: LPE lanes per neighbour row, LPH lanes per head (0 = run-time), element type T.
 // EDGE_TERM: the kernels also handle the optional additive edge term of the score (kept out of the
@@ -647,9 +652,60 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
 template <class P, class = void> struct merge_batch { static constexpr int value = 8; };
 template <class P> struct merge_batch<P, std::void_t<decltype(P::kMergeBatch)>> { static constexpr int value = P::kMergeBatch; };
 
-// One wavefront per super row / column: the edge slots take the row's chunks round-robin and sum (or,
-// for the forward pass, softmax-merge) their partial results, the slots are combined as in the direct
-// pass, and the row is finished exactly as the direct pass would.  Summation order is fixed.
+// A super row with very many chunks (a hub with 10^5 neighbours) is merged in two levels, so that its merge
+// is not one wavefront's work: the row's chunks are cut into at most merge_groups groups of equal size, one
+// wavefront per group folds the group's partials into the slot of the group's first chunk (k_merge_groups),
+// and the final merge reads one partial per group.  Both kernels derive the grouping from the row's chunk count
+// alone, so the summation order is fixed.
+constexpr int kMergeGroupChunks = 32;  // a group is worth a wavefront from this many chunks on
+__device__ inline int merge_groups_of(int chunks, int max_groups) {
+    const int want = (chunks + kMergeGroupChunks - 1) / kMergeGroupChunks;
+    return want < max_groups ? (want < 1 ? 1 : want) : max_groups;
+}
+
+// the partials [cb, ce) with stride `step` folded into p (kMergeBatch per edge slot are loaded before any is
+// folded in; absent ones read the first and are masked, so the loop has no per-lane branch and its loads overlap)
+template <class G, class P> __device__ inline void fold_range(const Args& a, const Ctx& c, P& p, int cb, int ce, int step) {
+    constexpr int kMergeBatch = merge_batch<P>::value;
+    for (int base = cb; base < ce; base += G::EPW * kMergeBatch * step) {
+        PartialRegs<G::VEC> R[kMergeBatch];
+#pragma unroll
+        for (int m = 0; m < kMergeBatch; ++m) {
+            const int ch = base + (m * G::EPW + c.g) * step;
+            p.load_partial(a, c, ch < ce ? ch : cb, R[m]);
+        }
+#pragma unroll
+        for (int m = 0; m < kMergeBatch; ++m) p.fold_partial(R[m], base + (m * G::EPW + c.g) * step < ce);
+    }
+}
+
+// first level: wavefront (s, g) folds group g of super row s into the partial slot of the group's first chunk
+template <class G, template <class, int> class PassT, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge_groups(const Args a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = blockIdx.x * kWavesPerBlock + wave;
+    const int s = w / a.merge_groups, g = w - s * a.merge_groups;
+    if (s >= a.n_items) return;
+    const int node = __builtin_amdgcn_readfirstlane(a.order[s]);
+    const int c0 = __builtin_amdgcn_readfirstlane(a.chunk_ptr[s]);
+    const int c1 = __builtin_amdgcn_readfirstlane(a.chunk_ptr[s + 1]);
+    const int ng = merge_groups_of(c1 - c0, a.merge_groups);
+    if (ng <= 1 || g >= ng) return;  // a row with one group is merged by the final kernel alone
+    const int gs = (c1 - c0 + ng - 1) / ng;
+    const int cb = c0 + g * gs, ce = min(c1, cb + gs);
+    if (cb >= ce) return;
+    const Ctx c = make_ctx<G>(a, lane, node);
+    PassT<G, U> p;
+    p.init(a, c);
+    fold_range<G>(a, c, p, cb, ce, 1);
+    p.combine_slots(a, c);
+    p.store_partial(a, c, cb);
+}
+
+// One wavefront per super row / column: the edge slots take the row's chunks (or the partials of its chunk
+// groups) round-robin and sum (or, for the forward pass, softmax-merge) their partial results, the slots are
+// combined as in the direct pass, and the row is finished exactly as the direct pass would.  Summation order
+// is fixed.
 template <class G, template <class, int> class PassT, int U>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -661,19 +717,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_merge(const Args a) {
     const Ctx c = make_ctx<G>(a, lane, node);
     PassT<G, U> p;
     p.init(a, c);
-    // kMergeBatch chunks per edge slot are loaded before any is folded in (absent ones read the row's
-    // first chunk and are masked), so the loop has no per-lane branch and its loads overlap
-    constexpr int kMergeBatch = merge_batch<PassT<G, U>>::value;
-    for (int base = c0; base < c1; base += G::EPW * kMergeBatch) {
-        PartialRegs<G::VEC> P[kMergeBatch];
-#pragma unroll
-        for (int m = 0; m < kMergeBatch; ++m) {
-            const int ch = base + m * G::EPW + c.g;
-            p.load_partial(a, c, ch < c1 ? ch : c0, P[m]);
-        }
-#pragma unroll
-        for (int m = 0; m < kMergeBatch; ++m) p.fold_partial(P[m], base + m * G::EPW + c.g < c1);
-    }
+    const int ng = merge_groups_of(c1 - c0, a.merge_groups);
+    const int step = ng <= 1 ? 1 : (c1 - c0 + ng - 1) / ng;  // one partial per group, at the group's first chunk
+    fold_range<G>(a, c, p, c0, c1, step);
     p.combine_slots(a, c);
     p.finalize(a, c);
 }

@@ -86,7 +86,16 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
     }
     if (n_super > 0 && merge) {
         a.n_items = n_super;
+        // rows with very many chunks are merged in two levels; the group count follows the mean chunk count
+        // of the super rows (a power of two, at most 64), so graphs whose super rows have a few chunks each
+        // launch the final merge only
+        int groups = 1;
+        while (groups < 64 && (int64_t)groups * kMergeGroupChunks * n_super < n_chunks) groups <<= 1;
+        a.merge_groups = groups;
         KernelTimer t(labels[1], st);
+        if (groups > 1)
+            hipLaunchKernelGGL((k_merge_groups<G, PassT, kUnroll>), dim3(dfgnn::blocks_for((int64_t)n_super * groups)),
+                               dim3(64 * kWavesPerBlock), 0, st, a);
         hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(dfgnn::blocks_for(n_super)), dim3(64 * kWavesPerBlock), 0, st, a);
     }
 }

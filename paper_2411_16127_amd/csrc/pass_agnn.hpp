@@ -22,7 +22,7 @@ template <class G, int U, class Acc> struct AgnnFwdT {
         load_row<G>(a.x, c, x2);
         const float rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(x2, x2), a.lph), a.inv_eps);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x2[i] *= a.c_score * rn;
+        for (int i = 0; i < VEC; ++i) x2[i] *= agnn_beta(a) * kLog2e * rn;
         sm.init(a, c);
     }
     __device__ void issue(const Args& a, const Ctx& c, int u, int j, int e) {
@@ -59,12 +59,15 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
     static constexpr bool kExact = RowBackwardBase<G>::kExact;
     float xh[VEC], ga[VEC], px[VEC];  // px = sum_j p xhat_j (kExact only)
     float rn, dbeta, pc;              // pc = sum_j p cos_ij (kExact only)
+    float beta, beta2;                // beta and beta * log2(e)
     float B[U];
     int Ep[U];
     u32x4 V[U];
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, xh);
         rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(xh, xh), a.lph), a.inv_eps);
+        beta = agnn_beta(a);
+        beta2 = beta * kLog2e;
         dbeta = 0.f;
         pc = 0.f;
 #pragma unroll
@@ -84,7 +87,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             const float rnj = inv_norm(head_sum<G::LPH>(dotv<VEC>(vf, vf), a.lph), a.inv_eps);
             const float cs = head_sum<G::LPH>(dotv<VEC>(xh, vf), a.lph) * rnj;
             const float dp = head_sum<G::LPH>(dotv<VEC>(this->g, vf), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - this->lse2) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * beta2, B[u]) - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
                 if (u == 0) this->dp0 = dp;
@@ -159,7 +162,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
         }
         float o[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = a.scale * ga[i];
+        for (int i = 0; i < VEC; ++i) o[i] = beta * ga[i];
         store_f32<VEC>(a.g_row + c.woff, o);
         if (c.head0) {
             const size_t nh = (size_t)c.node * a.H + c.h;
@@ -175,7 +178,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
 template <class G, int U> struct AgnnBwdCol {
     static constexpr int VEC = G::VEC;
     float hj[VEC], xh[VEC], val[VEC], ga[VEC];
-    float rn;
+    float rn, beta;
     float B[U];
     int Ep[U];
     u32x4 Xi[U], Gd[U];
@@ -183,6 +186,7 @@ template <class G, int U> struct AgnnBwdCol {
     __device__ void init(const Args& a, const Ctx& c) {
         load_row<G>(a.x, c, hj);
         rn = inv_norm(head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph), a.inv_eps);
+        beta = agnn_beta(a);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { xh[i] = hj[i] * rn; val[i] = 0.f; ga[i] = 0.f; }
     }
@@ -201,7 +205,7 @@ template <class G, int U> struct AgnnBwdCol {
             Elem<typename G::T>::unpack(Gd[u], gf);
             const float cs = head_sum<G::LPH>(dotv<VEC>(xf, xh), a.lph) * St[u][0];
             const float dp = head_sum<G::LPH>(dotv<VEC>(gf, hj), a.lph);
-            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * a.c_score, B[u]) - St[u][1]) : 0.f;
+            const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * (beta * kLog2e), B[u]) - St[u][1]) : 0.f;
             const float ds = p * (dp - St[u][2]);
             store_dbias<G, false>(a, c, FULL || j[u] >= 0, Ep[u], ds);
             const float w = ds * St[u][0];
@@ -241,7 +245,7 @@ template <class G, int U> struct AgnnBwdCol {
             for (int i = 0; i < VEC; ++i) gt[i] = 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) gt[i] = fmaf(a.scale, ga[i], gt[i]);
+        for (int i = 0; i < VEC; ++i) gt[i] = fmaf(beta, ga[i], gt[i]);
         const float proj = head_sum<G::LPH>(dotv<VEC>(gt, xh), a.lph);
         const float nrm2 = head_sum<G::LPH>(dotv<VEC>(hj, hj), a.lph);
         const bool clamped = !(sqrtf(nrm2) > a.eps);

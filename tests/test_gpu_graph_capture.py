@@ -64,3 +64,55 @@ def test_step_replays_from_a_hip_graph(name, shrink):
         for got, want in zip(results, eager):
             assert torch.equal(got, want), (name, rep)  # same kernels, same order: bit-identical
     g.close()
+
+
+def test_agnn_beta_on_the_device_is_read_at_replay_time():
+    """AGNN with beta passed as a device pointer (a_l): the value is read by the kernels, so a captured step
+    follows an in-place update of beta between replays; each replay equals an eager call with that beta as the
+    layer's host-side scale, bit for bit."""
+    import torch
+    w = make_workload("cfg4", shrink=64)
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    g = dfgnn.Graph(graph.indptr, graph.indices, dfgnn.SchedParams(64, 32))
+    x = torch.from_numpy(feats["feat"]).cuda()
+    d_out = torch.from_numpy(feats["d_out"]).cuda()
+    N, H = graph.n, w.H
+    beta = torch.tensor([1.0], device="cuda")
+
+    def buffers():
+        return (torch.empty_like(x), torch.empty(N, H, device="cuda"), torch.empty(N, H, device="cuda"),
+                torch.empty_like(x), torch.empty(1, device="cuda"))
+
+    def step(L, a_l, bufs, stream):
+        out, rmax, rsum, d_x, d_s = bufs
+        dfgnn.forward(g.handle, L, x, None, None, a_l, None, out, rmax, rsum, ws, ws.numel(), stream)
+        dfgnn.backward(g.handle, L, x, None, None, a_l, None, out, rmax, rsum, d_out, d_x, None, None, None, None, d_s,
+                       ws, ws.numel(), stream)
+
+    L_dev = dfgnn.Layer("agnn", w.H, w.D, scale=123.0, eps=w.eps)  # the host-side value must be ignored
+    fb, bb = dfgnn.workspace_bytes(g.handle, L_dev)
+    ws = torch.empty(max(fb, bb, 256), dtype=torch.uint8, device="cuda")
+    captured = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    cg = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(L_dev, beta, captured, side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(cg, stream=side):
+            step(L_dev, beta, captured, side)
+    torch.cuda.synchronize()
+    for value in (1.0, 0.5, 2.25):
+        beta.fill_(value)
+        for t in captured:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        cg.replay()
+        torch.cuda.synchronize()
+        eager = buffers()
+        step(dfgnn.Layer("agnn", w.H, w.D, scale=value, eps=w.eps), None, eager, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for got, want in zip(captured, eager):
+            assert torch.equal(got, want), value
+    g.close()

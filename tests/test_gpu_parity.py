@@ -104,6 +104,25 @@ def test_complete_graph(model):
         g.close()
 
 
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_hub_rows_with_hundreds_of_chunks(model, dtype):
+    """16 hub rows of 6,250 neighbours cut into chunks of 16 edges: their 391 partials each are merged in two
+    levels (groups of chunks first, then the groups).  The hubs' sources are hub columns too for no node here, so
+    the column side is covered by the transposed graph: the same layer on the graph with every edge reversed."""
+    from dfgnn_synth import from_edge_list
+    base = make_workload("cfg4", shrink=32)
+    graph = make_graph(base)
+    scale = {"gt": 0.25, "agnn": 1.3}.get(model, 1.0)
+    w = Workload("hubs", 93, model, 2, 16, dtype, float(scale))
+    for g_in in (graph, from_edge_list(graph.n, graph.rows_of_edges(), graph.indices)):  # hub rows; hub columns
+        feats = make_features(w, g_in.n)
+        res, g = run_gpu(g_in, w, feats, dfgnn.SchedParams(64, 16))
+        assert g.query("n_super_rows") + g.query("n_super_cols") >= 16
+        compare_all(res, run_oracle(g_in, w, feats), w)
+        g.close()
+
+
 def test_split_rows_match_unsplit_rows():
     """The chunk + merge path and the one-wave-per-row path give the same numbers (to rounding)."""
     graph = make_graph(make_workload("cfg1"))
