@@ -97,8 +97,10 @@ typedef struct {
     int32_t H;       /* heads */
     int32_t D;       /* features per head; D * sizeof(element) must be a multiple of 16 bytes, D/vec a power
                         of two (vec = 4 for fp32, 8 for bf16 and fp16) and at most 64 (one head fits one wavefront of
-                        16-byte lanes: D <= 256 in fp32, 512 in bf16 / fp16), and one node tensor (N*H*D elements)
-                        must stay below 4 GiB.  Rows of more than 64 such lanes (H*D/vec > 64) are processed
+                        16-byte lanes: D <= 256 in fp32, 512 in bf16 / fp16).  Node tensors (N*H*D elements) of
+                        4 GiB and more are taken by a slower set of kernels (64-bit gather addresses, head
+                        reductions by shuffles) as long as N*H*16 bytes stay below 4 GiB; the dense-tile batch
+                        kernels are unaffected.  Rows of more than 64 such lanes (H*D/vec > 64) are processed
                         in groups of heads, one launch sequence per group.  Other head widths (a classifier
                         layer with 7 outputs, say) are used zero-padded to the next accepted width: zero
                         features change no score of any model and aggregate to zero. */

@@ -400,7 +400,11 @@ __device__ inline void seg_phase3(const SegArgs& a, int b, SegShared<W>& S, int 
 template <int W> __global__ __launch_bounds__(64 * W) void k_seg_phase1(const SegArgs a) {
     __shared__ SegShared<W> S;
     int first, n_b;
-    seg_phase1<W>(a, blockIdx.x, S, &first, &n_b);
+    if (!seg_phase1<W>(a, blockIdx.x, S, &first, &n_b)) {
+        // a refused segment leaves defined (empty) counts behind: the scan over the segments reads them
+        for (int i = threadIdx.x; i < kSegKeys; i += 64 * W) a.seg_hist[(size_t)blockIdx.x * kSegKeys + i] = 0;
+        if (a.tile_ptr && threadIdx.x == 0) a.tile_ptr[blockIdx.x] = 0;
+    }
 }
 
 // Block k < 72: exclusive scan over the segments of the node counts of degree class k.  Block 72: the same
@@ -453,6 +457,10 @@ __global__ __launch_bounds__(256) void k_seg_offsets(const SegArgs a) {
 template <int W> __global__ __launch_bounds__(64 * W) void k_seg_phase3(const SegArgs a) {
     __shared__ SegShared<W> S;
     int first, n_b, e0, m;
+    // Any flag of phase 1 (a segment too large for this builder, a malformed CSR or batch pointer, an edge
+    // between two graphs) means that the host discards the result: nothing is placed then, because the
+    // positions of the other segments would be built on the counts of a segment that was not processed.
+    if (a.counters[CNT_SEG_FLAGS] | a.counters[CNT_ERROR] | (a.counters[CNT_BATCH] & (BATCH_BAD_PTR | BATCH_CROSS_EDGE))) return;
     // the bounds were checked by phase 1; a segment it refused raises the same flag again and is skipped
     if (!seg_bounds(a, blockIdx.x, &first, &n_b, &e0, &m)) return;
     seg_phase3<W>(a, blockIdx.x, S, first, n_b, a.indptr + first, a.t_indptr + first);

@@ -45,11 +45,12 @@ struct Geometry {
     int id;      // index into the instantiation table
     int heads;   // heads per group (a divisor of H)
     int groups;  // H / heads
+    bool wide;   // node tensors of 4 GiB and more: run-time geometry with 64-bit gather addresses
 };
 
 static int elem_bytes(int dtype) { return dtype == DFGNN_F32 ? 4 : 2; }
 
-static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
+static int pick_geometry(const dfgnn_layer* L, bool wide, Geometry* out) {
     DFGNN_REQUIRE(L->dtype == DFGNN_F32 || L->dtype == DFGNN_BF16 || L->dtype == DFGNN_F16, DFGNN_EINVAL, "unknown dtype %d",
                   L->dtype);
     DFGNN_REQUIRE(L->H >= 1 && L->D >= 1, DFGNN_EINVAL, "H and D must be positive (H=%d D=%d)", L->H, L->D);
@@ -77,7 +78,8 @@ static int pick_geometry(const dfgnn_layer* L, Geometry* out) {
     for (const Entry& e : table)
         if (e.lph == 0 && e.dtype == L->dtype && e.lpe == g.lpe) g.id = e.id;
     for (const Entry& e : table)
-        if (e.lph != 0 && e.dtype == L->dtype && e.lpe == g.lpe && lanes == g.lpe && e.lph == g.lph) g.id = e.id;
+        if (!wide && e.lph != 0 && e.dtype == L->dtype && e.lpe == g.lpe && lanes == g.lpe && e.lph == g.lph) g.id = e.id;
+    g.wide = wide;
     DFGNN_REQUIRE(g.id >= 0, DFGNN_EUNSUPPORTED, "no kernel for dtype %d with %d lanes per row", L->dtype, g.lpe);
     *out = g;
     return DFGNN_OK;
@@ -196,18 +198,28 @@ static int check_layer(const dfgnn_graph* g, const dfgnn_layer* L, Geometry* geo
     DFGNN_REQUIRE(L->model == DFGNN_GT || L->model == DFGNN_GAT || L->model == DFGNN_AGNN || L->model == DFGNN_GATV2,
                   DFGNN_EINVAL, "unknown model %d", L->model);
     DFGNN_REQUIRE(L->reserved[0] == 0, DFGNN_EINVAL, "dfgnn_layer.reserved must be zero");
-    int rc = pick_geometry(L, geo);
-    if (rc != DFGNN_OK) return rc;
+    // Gathers address node rows with 32-bit byte offsets against a buffer resource, and an absent neighbour is
+    // read at offset 2^32 - row_bytes + ..., which must fall outside the tensor: tensors up to 2^32 - row_bytes
+    // bytes take that path.  Larger ones run on the run-time-geometry kernels with 64-bit gather addresses.
     const int64_t elem = elem_bytes(L->dtype);
-    DFGNN_REQUIRE((int64_t)g->N * L->H * L->D * elem < ((int64_t)1 << 32) - 4096, DFGNN_EUNSUPPORTED,
-                  "node tensor of %lld bytes: gathers use 32-bit byte offsets, tensors must stay below 4 GiB",
-                  (long long)((int64_t)g->N * L->H * L->D * elem));
+    const int64_t row_bytes = (int64_t)L->H * L->D * elem;
+    const bool wide = (int64_t)g->N * row_bytes > ((int64_t)1 << 32) - row_bytes;
+    int rc = pick_geometry(L, wide, geo);
+    if (rc != DFGNN_OK) return rc;
+    if (wide) {
+        // the packed per-(row, head) records of the backward pass are still gathered with 32-bit offsets
+        DFGNN_REQUIRE((int64_t)g->N * L->H * 16 < ((int64_t)1 << 32) - 4096, DFGNN_EUNSUPPORTED,
+                      "N * H = %lld: the per-row statistics records exceed 4 GiB", (long long)((int64_t)g->N * L->H));
+        DFGNN_REQUIRE(!(g->flags & DFGNN_SCHED_SCORES_IN_MEMORY), DFGNN_EUNSUPPORTED,
+                      "the scores-in-memory comparator does not take node tensors of 4 GiB and more");
+    }
     if (L->model == DFGNN_AGNN) DFGNN_REQUIRE(L->eps > 0.f, DFGNN_EINVAL, "AGNN eps must be positive");
     return DFGNN_OK;
 }
 
 static void fill_common(Args& a, const dfgnn_graph* g, const dfgnn_layer* L, const Geometry& geo) {
     a.n_nodes = (int)g->N;
+    a.wide = geo.wide ? 1 : 0;
     a.row_bytes = (uint32_t)(L->H * L->D * elem_bytes(L->dtype));
     a.tensor_bytes = (uint32_t)((uint64_t)g->N * a.row_bytes);
     a.nh_bytes = (uint32_t)((uint64_t)g->N * geo.heads * 4u);

@@ -191,8 +191,9 @@ struct Args {
     int merge_groups;                       // merge kernels: largest number of chunk groups per super row (1: one level)
     int xcd_group;                          // workgroups per XCD-local run of the work list (0: no remapping)
     int n_nodes;
+    int wide;               // node tensors of 4 GiB and more: gathers use 64-bit addresses (run-time geometries only)
     uint32_t row_bytes;     // bytes of one node row
-    uint32_t tensor_bytes;  // bytes of one node tensor (< 4 GiB)
+    uint32_t tensor_bytes;  // bytes of one node tensor (unused when wide)
     uint32_t nh_bytes;      // bytes of one [N, H] fp32 array
     // shape and constants.  H, HD describe the heads this launch works on; when a layer has more features
     // than one wavefront covers, the host runs it in groups of heads, and the caller's tensors keep the
@@ -303,8 +304,21 @@ template <class G> __device__ inline void load_row(const void* base, const Ctx& 
     }
 }
 
-// neighbour row j of a node tensor (zeros for j = -1)
+// neighbour row j of a node tensor (zeros for j = -1).  Tensors of 4 GiB and more are beyond a buffer
+// resource's 32-bit range: the kernels whose head width is a run-time value (LPH = 0) then form a 64-bit
+// address per lane and skip the load for an absent neighbour (and for lanes without features of their own,
+// which the range check would otherwise cover at the end of the tensor).  The branch is the same in every
+// lane of the launch; the kernels with compile-time geometries, which the host never picks for such tensors,
+// do not carry it.
 template <class G> __device__ inline u32x4 gather_raw(const void* base, const Args& a, const Ctx& c, int j) {
+    if constexpr (G::LPH == 0) {
+        if (a.wide) {
+            u32x4 r = {0u, 0u, 0u, 0u};
+            if (j >= 0 && c.active)
+                r = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + (size_t)(uint32_t)j * a.row_bytes + c.fbyte);
+            return r;
+        }
+    }
     return buf_load16(make_rsrc(base, a.tensor_bytes), (uint32_t)j * a.row_bytes + c.fbyte);
 }
 // packed row statistics of (i, head): 2 or 4 floats per record (zeros for i = -1)

@@ -88,7 +88,10 @@ def block_diagonal(sizes, density, seed, shuffle_rows=False, repeats=False):
 # for a segment sends the whole batch through the general builder; T and C small enough for super rows
 @pytest.mark.parametrize("sizes,density,T,C", [
     ([5, 1, 17, 64, 0, 33], 0.4, 1024, 512), ([65, 130, 3, 700], 0.1, 16, 8), ([0, 0, 9], 0.5, 4, 3),
-    ([4096, 10], 0.002, 64, 32), ([4097, 10], 0.002, 64, 32), ([40] * 300, 0.3, 0, 0), ([1] * 70, 1.0, 0, 0)])
+    ([4096, 10], 0.002, 64, 32), ([4097, 10], 0.002, 64, 32), ([40] * 300, 0.3, 0, 0), ([1] * 70, 1.0, 0, 0),
+    # 300 x 300 edges exceed a segment, 254 x 254 do not: some graphs are processed, one is refused, and the
+    # whole batch goes through the general builder (the refused graph's counts must not be used by the others)
+    ([254, 20, 300, 254, 7], 1.0, 0, 0)])
 @pytest.mark.parametrize("messy", [False, True])
 def test_batches_in_one_call(sizes, density, T, C, messy):
     graph = block_diagonal(sizes, density, seed=len(sizes), shuffle_rows=messy, repeats=messy)

@@ -233,14 +233,16 @@ def test_cfg5_full_size_sampled(dtype):
     g.close()
 
 
-def test_node_tensors_just_below_4_gib():
-    """Gathers address node rows with 32-bit byte offsets: a graph whose tensors end 300 KB below 4 GiB,
-    checked on rows and columns at both ends of the node range.  Tensors are drawn on the GPU; the oracle
-    gets the compact sub-problem of the sampled rows (whole neighbourhoods) and of every row that feeds a
-    sampled column."""
+@pytest.mark.parametrize("N", [8388000, 8390000])
+def test_node_tensors_around_4_gib(N):
+    """Gathers address node rows with 32-bit byte offsets up to 4 GiB minus one row and with 64-bit addresses
+    beyond: a graph whose tensors end 300 KB below 4 GiB (N = 8,388,000 rows of 512 bytes) and one whose
+    tensors end 700 KB above (N = 8,390,000), checked on rows and columns at both ends of the node range.
+    Tensors are drawn on the GPU; the oracle gets the compact sub-problem of the sampled rows (whole
+    neighbourhoods) and of every row that feeds a sampled column."""
     import torch
     from dfgnn_synth import from_edge_list
-    N, H, D = 8388000, 8, 16  # N * 512 bytes = 2^32 - 311,296
+    H, D = 8, 16
     rng = np.random.default_rng(21)
     src = rng.integers(0, N, size=(N, 2), dtype=np.int64)
     src[-4:, 0] = np.array([N - 1, 0, N - 2, 1])  # the last rows read the first and the last rows
