@@ -77,6 +77,7 @@ def algorithmic_bytes(w, graph, edge_bias=False):
     # dense-tile kernels for batches of small graphs do the work of the same passes in one launch each
     res["dense_fwd"] = res["fwd"]
     res["dense_bwd"] = res["bwd_row"] + res["bwd_col"]
+    res["bwd_row_col"] = res["bwd_row"] + res["bwd_col"]  # both sides in one launch (small graphs)
     if w.model == "gt":  # two-kernel comparator: the scores make a round trip through memory
         res["fwd_scores"] = (R + s + 8) * graph.nnz + R * graph.n  # q_i counted once per row, as in the fused pass
         res["fwd_softmax_spmm"] = (R + s + 4) * graph.nnz + (R + 2 * s + 4) * graph.n
@@ -206,6 +207,7 @@ def main() -> int:
     ap.add_argument("--no-short-rows", action="store_true", help="ablation: one wavefront for every row below the super threshold")
     ap.add_argument("--no-dense-batch", action="store_true", help="ablation: general kernels also for batches of small graphs")
     ap.add_argument("--no-xcd-groups", action="store_true", help="ablation: workgroups dealt round-robin to the XCDs for every graph")
+    ap.add_argument("--no-paired-passes", action="store_true", help="ablation: backward row side and column side always as separate launches")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one step (forward + backward) into a HIP graph and replay it K times in the timed region")
     ap.add_argument("--force-dense-batch", action="store_true", help="dense-tile batch kernels whenever they apply")
@@ -263,7 +265,7 @@ def main() -> int:
     sched = dfgnn.SchedParams(args.super_threshold, args.chunk_edges,
                               (1 if args.no_short_rows else 0) | (2 if args.no_dense_batch else 0) |
                               (4 if args.force_dense_batch else 0) | (8 if args.scores_in_memory else 0) |
-                              (16 if args.no_xcd_groups else 0))
+                              (16 if args.no_xcd_groups else 0) | (64 if args.no_paired_passes else 0))
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[w.dtype]
     dev = lambda a: torch.from_numpy(a).cuda().to(tdt).contiguous()
     x = dev(feats["q"] if w.model == "gt" else feats["feat"])

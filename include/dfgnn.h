@@ -89,6 +89,12 @@ typedef struct {
  * dfgnn_graph_set_batch work as usual; dfgnn_backward* return EINVAL; the CSC items of dfgnn_graph_query
  * have count 0. */
 #define DFGNN_SCHED_FORWARD_ONLY 32
+/* Ablation switch.  For small fp32 GT graphs (at most 262144 edges, no super rows or columns, no edge term) the
+ * backward call runs its row side and its column side as one launch: the column side recomputes the softmax
+ * statistics and delta_i = dO_i . O_i of every edge's row from the forward results instead of waiting for the
+ * row side to hand them over.  With this bit the two sides are separate launches for every graph.  Results
+ * are the same up to rounding order. */
+#define DFGNN_SCHED_NO_PAIRED_PASSES 64
 
 /* One layer call's model description. */
 typedef struct {

@@ -44,7 +44,7 @@ class _CLayer(ctypes.Structure):
 class SchedParams:
     super_threshold: int = 0  # 0 = library default
     chunk_edges: int = 0
-    flags: int = 0            # bits: 1 = no short-row mapping, 2 = no dense-tile batch kernels, 4 = dense-tile kernels whenever they apply, 8 = GT forward with scores through memory (comparator), 16 = no XCD-local runs of the work list, 32 = forward-only graph (no CSC; backward calls are refused)
+    flags: int = 0            # bits: 1 = no short-row mapping, 2 = no dense-tile batch kernels, 4 = dense-tile kernels whenever they apply, 8 = GT forward with scores through memory (comparator), 16 = no XCD-local runs of the work list, 32 = forward-only graph (no CSC; backward calls are refused), 64 = backward row side and column side always as separate launches
 
     def _c(self) -> _CSched:
         return _CSched(self.super_threshold, self.chunk_edges, self.flags, (ctypes.c_int32 * 5)())

@@ -432,7 +432,7 @@ static int resolve_params(const dfgnn_sched_params* sched, int64_t E, int* T, in
                       "negative scheduling parameter");
         DFGNN_REQUIRE((sched->flags & ~(DFGNN_SCHED_NO_SHORT_ROWS | DFGNN_SCHED_NO_DENSE_BATCH | DFGNN_SCHED_FORCE_DENSE_BATCH |
                                          DFGNN_SCHED_SCORES_IN_MEMORY | DFGNN_SCHED_NO_XCD_GROUPS |
-                                         DFGNN_SCHED_FORWARD_ONLY)) == 0,
+                                         DFGNN_SCHED_FORWARD_ONLY | DFGNN_SCHED_NO_PAIRED_PASSES)) == 0,
                       DFGNN_EINVAL, "unknown scheduling flag 0x%x", sched->flags);
         if (sched->chunk_edges > 0) *C = sched->chunk_edges;
         if (sched->super_threshold > 0) *T = sched->super_threshold;

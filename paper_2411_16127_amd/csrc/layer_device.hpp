@@ -321,6 +321,11 @@ template <class G> __device__ inline u32x4 gather_raw(const void* base, const Ar
     }
     return buf_load16(make_rsrc(base, a.tensor_bytes), (uint32_t)j * a.row_bytes + c.fbyte);
 }
+// one fp32 value of (i, head) from an [N, stat_stride] array (zero for i = -1)
+__device__ inline float gather_stat(const float* p, const Args& a, const Ctx& c, int i) {
+    return buf_load_f32(make_rsrc(p, (uint32_t)a.n_nodes * (uint32_t)a.stat_stride * 4u),
+                        i >= 0 ? (uint32_t)i * (uint32_t)(a.stat_stride * 4) + c.hbyte : 0xffffffffu);
+}
 // packed row statistics of (i, head): 2 or 4 floats per record (zeros for i = -1)
 __device__ inline f32x2 gather_stats2(const Args& a, const Ctx& c, int i) {
     return buf_load_f32x2(make_rsrc(a.stats, a.nh_bytes * 2u), (uint32_t)i * (uint32_t)(a.H * 8) + c.hbyte * 2u);
@@ -629,17 +634,16 @@ __device__ inline void wave_small_rows(const Args& a, int item, int lane) {
 // wavefront each), then the short rows, one per edge slot.  Each of the 4 wavefronts of a workgroup
 // works alone; the kind of work depends only on blockIdx, so a wavefront never diverges on it.
 template <class G, template <class, int> class PassT, int U>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
+__device__ inline void pass_block(const Args& a, int b, int grid) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wpb = (int)blockDim.x >> 6;  // wavefronts per workgroup (the host picks 1, 2 or 4)
-    int b = blockIdx.x;
     // The hardware deals workgroups to the 8 XCDs round-robin.  For graphs whose numbering is local the
     // work list is cut into runs of xcd_group workgroups and run r of every 8 goes to XCD r, so that rows
     // which are neighbours in the list (and share neighbour rows) meet in one L2, while all XCDs still
     // advance through the degree-ordered list at the same pace.
     if (a.xcd_group > 0) {
         const int sh = __builtin_ctz(a.xcd_group) + 3;  // the run length is a power of two
-        if (b < (int)((gridDim.x >> sh) << sh)) {
+        if (b < (int)((grid >> sh) << sh)) {
             const int r = b & ((1 << sh) - 1);
             b = (b - r) + (r & 7) * a.xcd_group + (r >> 3);
         }
@@ -660,6 +664,20 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
         const int item = b * wpb + wave;
         if (item * G::EPW < a.n_small) wave_small_rows<G, PassT, U>(a, item, lane);
     }
+}
+
+template <class G, template <class, int> class PassT, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass(const Args a) {
+    pass_block<G, PassT, U>(a, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Two passes that do not depend on each other in one launch (the row side and the column side of the
+// backward pass of a small graph, where a launch costs as much as the work it starts): the first blocks_a
+// workgroups run pass A over its work list, the others pass B over its own.
+template <class G, template <class, int> class PassA, template <class, int> class PassB, int U>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_pass_pair(const Args a, const Args b, int blocks_a) {
+    if ((int)blockIdx.x < blocks_a) pass_block<G, PassA, U>(a, (int)blockIdx.x, blocks_a);
+    else pass_block<G, PassB, U>(b, (int)blockIdx.x - blocks_a, (int)gridDim.x - blocks_a);
 }
 
 // chunks a merge wavefront loads per edge slot before folding them in (a pass may ask for fewer)

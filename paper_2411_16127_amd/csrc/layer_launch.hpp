@@ -38,47 +38,64 @@ template <class G> using with_edge_term = Geo<typename G::T, G::LPE, G::LPH, tru
 // ---------------------------------------------------------------------------------------------
 static inline unsigned blocks_for(int64_t waves) { return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock); }
 
-// chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
-template <class G, template <class, int> class PassT>
-static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st,
-                     bool merge = true) {
+// Work list of one pass over the rows (or columns) of a graph: chunk items of super rows, whole-row items,
+// short rows (fewer than EPW * U neighbours, i.e. less than one load round of a whole wavefront: one per edge
+// slot; they are the tail of the degree-ordered list).
+struct PassShape {
+    int n_super, n_chunks;
+    int64_t first_small, n_direct, n_small, waves;
+};
+template <class G> static PassShape pass_shape(const dfgnn_graph* g, bool columns) {
+    PassShape s{};
+    s.n_super = columns ? g->n_super_cols : g->n_super_rows;
+    s.n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
+    const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
+    s.first_small = g->N;
+    if (G::EPW > 1 && !(g->flags & DFGNN_SCHED_NO_SHORT_ROWS)) {
+        int lg = 0;
+        while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
+        s.first_small = bucket[33 - lg];
+        if (s.first_small < s.n_super) s.first_small = s.n_super;
+    }
+    s.n_direct = s.first_small - s.n_super;
+    s.n_small = g->N - s.first_small;
+    const int64_t small_waves = G::EPW > 1 ? (s.n_small + G::EPW - 1) / G::EPW : 0;
+    s.waves = s.n_chunks + s.n_direct + small_waves;
+    return s;
+}
+// small launches spread their wavefronts over more compute units with smaller workgroups
+// (2,708-node graph: 25.2 us per training step with 4 wavefronts per workgroup, 23.5 with 1)
+static inline int waves_per_block(int64_t waves) { return waves <= 1024 ? 1 : (waves <= 4096 ? 2 : kWavesPerBlock); }
+
+// fills the work-list fields of `a` for workgroups of wpb wavefronts; returns the number of workgroups
+template <class G> static unsigned bind_pass(const dfgnn_graph* g, bool columns, const PassShape& s, int wpb, Args& a) {
     a.ptr = columns ? g->t_indptr : g->indptr;
     a.idx = columns ? g->t_indices : g->indices;
     a.order = columns ? g->col_order : g->row_order;
     a.chunks = columns ? g->col_chunks : g->row_chunks;
     a.chunk_ptr = columns ? g->col_chunk_ptr : g->row_chunk_ptr;
     a.eid = (columns && a.bias) ? g->t_eid : nullptr;  // the edge term is stored in CSR edge order
-    const int n_super = columns ? g->n_super_cols : g->n_super_rows;
-    const int n_chunks = columns ? g->n_col_chunks : g->n_row_chunks;
-    // rows with fewer than EPW * U neighbours (less than one load round of a whole wavefront) go to the
-    // slot-per-row kernel; they are the tail of the degree-ordered list
-    const int32_t* bucket = columns ? g->col_bucket_ptr : g->row_bucket_ptr;
-    int64_t first_small = g->N;
-    if (G::EPW > 1 && !(g->flags & DFGNN_SCHED_NO_SHORT_ROWS)) {
-        int lg = 0;
-        while ((1 << (lg + 1)) <= G::EPW * kUnroll) ++lg;  // degree < 2^lg  <=>  bit_length(degree) <= lg
-        first_small = bucket[33 - lg];
-        if (first_small < n_super) first_small = n_super;
-    }
-    const int64_t n_direct = first_small - n_super;
-    const int64_t n_small = g->N - first_small;
-    // small launches spread their wavefronts over more compute units with smaller workgroups
-    // (2,708-node graph: 25.2 us per training step with 4 wavefronts per workgroup, 23.5 with 1)
-    const int64_t small_waves = G::EPW > 1 ? (n_small + G::EPW - 1) / G::EPW : 0;
-    const int64_t all_waves = n_chunks + n_direct + small_waves;
-    const int wpb = all_waves <= 1024 ? 1 : (all_waves <= 4096 ? 2 : kWavesPerBlock);
     auto blocks_for = [&](int64_t waves) { return (unsigned)((waves + wpb - 1) / wpb); };
-    a.n_chunks = n_chunks;
-    a.blocks_chunk = (int)blocks_for(n_chunks);
-    a.n_direct = (int)n_direct;
-    a.blocks_direct = (int)blocks_for(n_direct);
-    a.first_direct = n_super;
-    a.n_small = (int)n_small;
-    a.first_small = (int)first_small;
-    const unsigned blocks_small = blocks_for((n_small + G::EPW - 1) / G::EPW);
-    const unsigned total = (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_small;
-    const dim3 block(64 * wpb);
+    a.n_chunks = s.n_chunks;
+    a.blocks_chunk = (int)blocks_for(s.n_chunks);
+    a.n_direct = (int)s.n_direct;
+    a.blocks_direct = (int)blocks_for(s.n_direct);
+    a.first_direct = s.n_super;
+    a.n_small = (int)s.n_small;
+    a.first_small = (int)s.first_small;
     a.xcd_group = g->xcd_group;
+    return (unsigned)a.blocks_chunk + (unsigned)a.blocks_direct + blocks_for((s.n_small + G::EPW - 1) / G::EPW);
+}
+
+// chunk pass over super rows, direct pass over the rest, then the merge of the chunk partials
+template <class G, template <class, int> class PassT>
+static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* const (&labels)[2], hipStream_t st,
+                     bool merge = true) {
+    const PassShape s = pass_shape<G>(g, columns);
+    const int wpb = waves_per_block(s.waves);
+    const unsigned total = bind_pass<G>(g, columns, s, wpb, a);
+    const int n_super = s.n_super, n_chunks = s.n_chunks;
+    const dim3 block(64 * wpb);
     if (total > 0) {
         KernelTimer t(labels[0], st);
         if (a.bias) hipLaunchKernelGGL((k_pass<with_edge_term<G>, PassT, kUnroll>), dim3(total), block, 0, st, a);
@@ -98,6 +115,20 @@ static void run_pass(const dfgnn_graph* g, bool columns, Args a, const char* con
                                dim3(64 * kWavesPerBlock), 0, st, a);
         hipLaunchKernelGGL((k_merge<G, PassT, kUnroll>), dim3(dfgnn::blocks_for(n_super)), dim3(64 * kWavesPerBlock), 0, st, a);
     }
+}
+
+// Row pass and column pass of a backward call in one launch, for graphs without super rows or columns whose
+// passes do not depend on each other (the column pass recomputes what the row pass would hand over).
+template <class G, template <class, int> class RowPass, template <class, int> class ColPass>
+static void run_pass_pair(const dfgnn_graph* g, const Args& a, const char* label, hipStream_t st) {
+    const PassShape sr = pass_shape<G>(g, false), sc = pass_shape<G>(g, true);
+    const int wpb = waves_per_block(sr.waves + sc.waves);
+    Args ar = a, ac = a;
+    const unsigned blocks_r = bind_pass<G>(g, false, sr, wpb, ar), blocks_c = bind_pass<G>(g, true, sc, wpb, ac);
+    if (blocks_r + blocks_c == 0) return;
+    KernelTimer t(label, st);
+    hipLaunchKernelGGL((k_pass_pair<G, RowPass, ColPass, kUnroll>), dim3(blocks_r + blocks_c), dim3(64 * wpb), 0, st, ar, ac,
+                       (int)blocks_r);
 }
 
 [[maybe_unused]] static const char* const kFwdLabels[2] = {"fwd", "fwd_merge"};

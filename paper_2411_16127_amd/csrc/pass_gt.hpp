@@ -235,4 +235,66 @@ template <class G, int U> struct GtBwdCol {
     }
 };
 
+// The column pass without the row pass's hand-over: log-sum-exp and delta_i = dO_i.O_i of every edge's row are
+// recomputed from the forward statistics and the gathered output row (one more row per edge, which only a
+// cache-resident graph can afford), so that the row side and the column side of a small graph's backward
+// pass run as one launch (k_pass_pair).  fp32 tensors only: a 16-bit output row does not give delta to fp32
+// accuracy.  The row pass computes delta with the same instructions, so both sides see the same bits.
+template <class G, int U> struct GtBwdColSelf {
+    static constexpr int VEC = G::VEC;
+    float k2[VEC], vv[VEC], dk[VEC], dv[VEC];
+    u32x4 Q[U], Gd[U], O[U];
+    float Mx[U], Sm[U];
+    __device__ void init(const Args& a, const Ctx& c) {
+        load_row<G>(a.k, c, k2);
+        load_row<G>(a.v, c, vv);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { k2[i] *= a.c_score; dk[i] = 0.f; dv[i] = 0.f; }
+    }
+    __device__ void issue(const Args& a, const Ctx& c, int u, int i, int) {
+        Q[u] = gather_raw<G>(a.x, a, c, i);
+        Gd[u] = gather_raw<G>(a.d_out, a, c, i);
+        O[u] = gather_raw<G>(a.out, a, c, i);
+        Mx[u] = gather_stat(a.row_max, a, c, i);
+        Sm[u] = gather_stat(a.row_sum, a, c, i);
+    }
+    template <bool FULL> __device__ void consume(const Args& a, const Ctx&, const int (&j)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float qf[VEC], gf[VEC], of[VEC];
+            Elem<typename G::T>::unpack(Q[u], qf);
+            Elem<typename G::T>::unpack(Gd[u], gf);
+            Elem<typename G::T>::unpack(O[u], of);
+            const bool live = FULL || j[u] >= 0;
+            const float lse2 = Mx[u] * kLog2e + fast_log2(live ? Sm[u] : 1.f);
+            const float delta = head_sum<G::LPH>(dotv<VEC>(gf, of), a.lph);
+            const float s = head_sum<G::LPH>(dotv<VEC>(qf, k2), a.lph);
+            const float dp = head_sum<G::LPH>(dotv<VEC>(gf, vv), a.lph);
+            const float p = live ? fast_exp2(s - lse2) : 0.f;
+            const float ds = p * (dp - delta);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                dv[i] = fmaf(p, gf[i], dv[i]);
+                dk[i] = fmaf(ds, qf[i], dk[i]);
+            }
+        }
+    }
+    __device__ void combine_slots(const Args&, const Ctx&) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { dk[i] = slot_sum<G::LPE>(dk[i]); dv[i] = slot_sum<G::LPE>(dv[i]); }
+    }
+    // graphs with super columns do not take this pass (the host checks), so there are no partials
+    __device__ void store_partial(const Args&, const Ctx&, int) {}
+    __device__ void load_partial(const Args&, const Ctx&, int, PartialRegs<VEC>&) const {}
+    __device__ void fold_partial(const PartialRegs<VEC>&, bool) {}
+    __device__ void finalize(const Args& a, const Ctx& c) {
+        if (!c.writer || !c.active) return;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = a.scale * dk[i];
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_k) + c.off, o);
+        Elem<typename G::T>::store(static_cast<typename G::T*>(a.d_v) + c.off, dv);
+    }
+};
+
 }  // namespace dfgnn

@@ -136,6 +136,26 @@ def test_split_rows_match_unsplit_rows():
     g1.close(); g2.close()
 
 
+def test_backward_as_one_launch_matches_two_launches():
+    """Small fp32 GT graphs without super rows run the row side and the column side of the backward pass as one
+    launch (the column side recomputes delta from the output rows); flag 64 keeps them apart.  Both match the
+    oracle, and each other to rounding."""
+    w = make_workload("cfg1")
+    graph = make_graph(w)
+    feats = make_features(w, graph.n)
+    ref = run_oracle(graph, w, feats)
+    one, g1 = run_gpu(graph, w, feats)
+    two, g2 = run_gpu(graph, w, feats, dfgnn.SchedParams(flags=64))
+    assert g1.query("n_super_rows") == 0 and g1.query("n_super_cols") == 0
+    compare_all(one, ref, w)
+    compare_all(two, ref, w)
+    for key in ("d_x",):  # the row side is the same kernel code
+        assert np.array_equal(one[key], two[key])
+    for key in ("d_k", "d_v"):
+        np.testing.assert_allclose(one[key], two[key], rtol=2e-5, atol=2e-6)
+    g1.close(); g2.close()
+
+
 def test_large_scores_are_stable():
     graph = tiny_graph("hub", seed=4, n=70)
     w = small_workload("gt", 1, 64)
