@@ -6,7 +6,9 @@ resident in HBM before the timed region.  Prints ONE JSON line:
   metric/value : fwd+bwd throughput in GEdges/s  (E / (t_fwd + t_bwd)), E = stored edges incl. self-loops
   roofline     : the kernel with the largest share of the step, its algorithmic bytes (gather model: every
                  neighbour row counted once per edge) over its mean duration from HIP events recorded on
-                 the launch stream during the timed steps, against the 8 TB/s HBM peak
+                 the launch stream during the timed steps, against the 8 TB/s HBM peak.  This is an
+                 effective rate: rows served by the Infinity Cache count like rows from HBM (the counters
+                 behind `traffic` sit between L2 and the memory side and cannot tell the two apart)
   cpu_baseline : the CPU oracle timed on a bounded sample of rows of the same graph (one thread)
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1..cfg5]
@@ -26,14 +28,26 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the files
-# under profiles/ named after the kernel and workload); bytes per launch, None where not measured.
-MEASURED_TRAFFIC = {
-    # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB per launch, see profiles/{gt_cfg5,agnn_cfg4,gat_cfg3}_kernels.md
-    ("cfg5", "fwd"): 123928964733, ("cfg5", "bwd_row"): 127089949709, ("cfg5", "bwd_col"): 141920663322,
-    ("cfg4", "fwd"): 3487901460, ("cfg4", "bwd_row"): 4059106342, ("cfg4", "bwd_col"): 5937733470,
-    ("cfg3", "fwd"): 473009336, ("cfg3", "bwd_row"): 591679392, ("cfg3", "bwd_col"): 760945557,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.md")
+
+
+def measured_traffic(workload: str, kernel: str):
+    """Bytes per launch between L2 and the memory side (Infinity Cache + HBM) of one pass kernel, from the
+    table under profiles/ that the rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by the copy
+    calibration) were summarised into.  The table records the hash of the layer-kernel sources it was measured
+    on: when the sources in the tree differ, the figure is stale and None is returned."""
+    from paper_2411_16127_amd.build import kernels_id
+    try:
+        lines = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return None
+    current = kernels_id()
+    for line in lines:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0] == workload and cells[1] == kernel:
+            return int(cells[2]) if cells[3].strip("`") == current else None
+    return None
+
 
 DESCRIPTIONS = {
     "cfg1": "cfg1: GT fp32, Chung-Lu power-law graph N=2,708 (exponent 2.5) + self-loops, H=1 D=64",
@@ -436,7 +450,7 @@ def main() -> int:
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": None if achieved is None else round(achieved / HBM_PEAK_GBPS, 4),
                     # counters were collected for the workloads as defined, not for variants of them
-                    "traffic": None if (args.set or args.edge_bias or args.scores_in_memory) else MEASURED_TRAFFIC.get((w.name, dom)),
+                    "traffic": None if (args.set or args.edge_bias or args.scores_in_memory) else measured_traffic(w.name, dom),
                     "algorithmic_bytes_per_launch": model_bytes.get(dom), "avg_ms": kern[dom]["avg_ms"]}
     compulsory = compulsory_bytes(w, graph, args.edge_bias)
     total_model = sum(model_bytes.get(name, 0) for name in ("fwd", "bwd_row", "bwd_col", "param_reduce"))

@@ -55,6 +55,12 @@ def source_id() -> str:
     return _digest(sorted(os.path.join(CSRC, s) for s in SOURCES) + _headers(), " ".join(FLAGS))
 
 
+def kernels_id() -> str:
+    """Hash of the sources of the layer kernels alone (what the traffic counters under profiles/ were measured on)."""
+    names = sorted(f for f in os.listdir(CSRC) if f.startswith(("layer", "pass_")))
+    return _digest([os.path.join(CSRC, f) for f in names], " ".join(FLAGS))
+
+
 def built_id() -> str:
     """The hash the library in the tree carries ('' if there is no library or it has no id).  Read from the
     file, not through dlopen: loading the library pulls in a HIP runtime, and a test process must get that
