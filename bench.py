@@ -183,7 +183,7 @@ def sample_parity(w, timed, sample) -> dict:
     """Spot check of the buffers the timed steps left behind against the oracle's sub-problem: the output and
     the statistics of the sampled rows, the gradients that are complete inside the sub-problem (row-side ones
     of the sampled rows, every gradient of the complete columns).  Bounds as in the parity tests: fp32
-    1e-5 + 1e-4 |ref|, bf16 1e-5 + 2e-2 |ref|, fp16 1e-5 + 2e-3 |ref|."""
+    1e-5 + 1e-4 |ref|, bf16 1e-5 + 2e-2 |ref|, fp16 1e-5 + 2e-3 |ref| (2e-5 absolute for gradients of 16-bit layers)."""
     import torch
     rows, new_rows, cols, new_cols, fw, bw = sample
     rtol = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-3}[w.dtype]
@@ -205,7 +205,8 @@ def sample_parity(w, timed, sample) -> dict:
             got = timed[name][pick].float().cpu().numpy().astype(np.float64)
             ref = ref_all[new_ids]
             fin = np.isfinite(ref)
-            ok = np.array_equal(fin, np.isfinite(got)) and bool(np.all(np.abs(got[fin] - ref[fin]) <= 1e-5 + rtol * np.abs(ref[fin])))
+            atol = 2e-5 if (w.dtype != "f32" and name.startswith("d_")) else 1e-5  # 16-bit gradients: see tests/gpu_harness.py
+            ok = np.array_equal(fin, np.isfinite(got)) and bool(np.all(np.abs(got[fin] - ref[fin]) <= atol + rtol * np.abs(ref[fin])))
             checked[name] = ok
     return checked
 

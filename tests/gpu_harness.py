@@ -10,7 +10,8 @@ import paper_2411_16127_amd as dfgnn
 # term, and the one used is the fp32 one scaled by BF16_ATOL_SCALE (see tolerance()).
 F32_RTOL, F32_ATOL = 1e-4, 1e-5
 BF16_RTOL = 2e-2
-BF16_ATOL = 1e-5
+BF16_ATOL = 1e-5       # outputs and statistics of a 16-bit layer
+BF16_GRAD_ATOL = 2e-5  # its gradients (see tolerance())
 # fp16 storage (11-bit significands: the stored result is rounded by 2^-12 relative): 2e-3 relative, which is
 # the bf16 bound scaled by the ratio of the two roundings (2^-12 / 2^-9 = 1/8, rounded up); same absolute part
 F16_RTOL = 2e-3
@@ -137,14 +138,17 @@ def tolerance(name, ref, dtype):
     errors add up like sqrt(N) while single elements of the sum cancel to small values, so the relative part
     is taken against max(|ref|, rms of the gradient vector).  Without that floor 4 elements in 4 of the fp32
     GAT / GATv2 cases exceed the bound, by a factor of at most 1.9 (one element of 64 on the reduced cfg3).
-    bf16 layers (bf16 storage, fp32 arithmetic): inputs are exact in both implementations, so the error of an
-    element is the bf16 rounding of the stored result (2^-9 relative, inside the stated 2e-2) plus fp32
-    rounding of the terms that were added: the absolute part is the fp32 one, 1e-5.
+    bf16 / fp16 layers (16-bit storage, fp32 arithmetic): inputs are exact in both implementations, so the
+    error of an element is the rounding of the stored result (2^-9 / 2^-12 relative, inside the relative part)
+    plus fp32 rounding of the terms that were added: the absolute part is the fp32 one, 1e-5, for the output and
+    the statistics.  Gradients get 2e-5: the row passes of 16-bit layers form sum_j p dP y_j - delta sum_j p y_j,
+    the difference of two fp32 sums whose terms reach |dP| |y| ~ 10^2 for heads of 64 features, i.e. two
+    roundings of up to 6e-6 each where the result cancels (900 seeded random cases: largest error 1.5e-5, five
+    of 10^6 elements above 1e-5).
     """
-    if dtype == "bf16":
-        return BF16_RTOL, BF16_ATOL, 0.0
-    if dtype == "f16":
-        return F16_RTOL, BF16_ATOL, 0.0
+    if dtype in ("bf16", "f16"):
+        grad = name.startswith("d_")
+        return (BF16_RTOL if dtype == "bf16" else F16_RTOL), (BF16_GRAD_ATOL if grad else BF16_ATOL), 0.0
     if name in ("d_a_l", "d_a_r", "d_scale"):
         return F32_RTOL, F32_ATOL, _rms(ref)
     return F32_RTOL, F32_ATOL, 0.0
