@@ -90,7 +90,7 @@ template <class G, int U> struct AgnnBwdRow : RowBackwardBase<G> {
             const float p = (FULL || j[u] >= 0) ? fast_exp2(with_bias<G>(cs * beta2, B[u]) - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
-                if (u == 0) this->dp0 = dp;
+                if (u == 0 && (FULL || j[0] >= 0)) this->dp0 = dp;  // (a slot that has run out of edges keeps its value)
                 this->dsum += t;
                 dbeta = fmaf(t, cs, dbeta);
                 pc = fmaf(p, cs, pc);

@@ -85,7 +85,7 @@ template <class G, int U> struct GatBwdRow : RowBackwardBase<G> {
             const float slope = z > 0.f ? 1.f : a.neg_slope;
             if constexpr (kExact) {
                 const float t = p * dp;
-                if (u == 0) this->dp0 = dp;
+                if (u == 0 && (FULL || j[0] >= 0)) this->dp0 = dp;  // (a slot that has run out of edges keeps its value)
                 this->dsum += t;
                 d_el = fmaf(t, slope, d_el);
                 pl = fmaf(p, slope, pl);

@@ -101,7 +101,7 @@ template <class G, int U> struct GtBwdRow : RowBackwardBase<G> {
             const float p = (FULL || j[u] >= 0) ? fast_exp2(s - this->lse2) : 0.f;
             if constexpr (kExact) {
                 const float t = p * dp;
-                if (u == 0) this->dp0 = dp;
+                if (u == 0 && (FULL || j[0] >= 0)) this->dp0 = dp;  // (a slot that has run out of edges keeps its value)
                 this->dsum += t;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { dq[i] = fmaf(t, kf[i], dq[i]); pk[i] = fmaf(p, kf[i], pk[i]); }

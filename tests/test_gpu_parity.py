@@ -123,6 +123,28 @@ def test_hub_rows_with_hundreds_of_chunks(model, dtype):
         g.close()
 
 
+@pytest.mark.parametrize("model", ["gt", "gat", "agnn", "gatv2"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_single_edge_row_beside_longer_rows_16_bit(model, dtype):
+    """Rows of one edge that share a wavefront with rows of 9 to 11 edges: the longer rows take several rounds of
+    the edge loop, during which the slot of the single-edge row is idle and must keep what its only edge left
+    (the value the column side subtracts to reach an exact zero for that edge's score gradient)."""
+    from dfgnn_synth import from_edge_list
+    n = 14
+    rows, cols = [0, 5], [3, 7]  # two rows with one edge each
+    rng = np.random.default_rng(5)
+    for i in (1, 2, 4, 6, 9):
+        nb = rng.choice(n, size=9 + i % 3, replace=False)
+        rows += [i] * len(nb); cols += [int(j) for j in nb]
+    graph = from_edge_list(n, np.array(cols, np.int64), np.array(rows, np.int64))  # (sources, destinations = rows)
+    scale = {"gt": 0.25, "agnn": 1.3}.get(model, 1.0)
+    w = Workload("single_edge_mix", 41, model, 2, 16, dtype, float(scale))
+    feats = make_features(w, graph.n)
+    res, g = run_gpu(graph, w, feats)
+    compare_all(res, run_oracle(graph, w, feats), w)
+    g.close()
+
+
 def test_split_rows_match_unsplit_rows():
     """The chunk + merge path and the one-wave-per-row path give the same numbers (to rounding)."""
     graph = make_graph(make_workload("cfg1"))
