@@ -801,6 +801,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_edge_scores(const Args 
 // result then carries the rounding of its fp32 terms only, not of the summation.
 // ---------------------------------------------------------------------------------------------
 constexpr int kReduceBlocks = 256;
+constexpr int kReduceWaves = 16;  // wavefronts per workgroup of the first stage over node rows
 
 template <int LPE> __device__ inline double slot_sum_f64(double x) {
 #pragma unroll
@@ -810,18 +811,19 @@ template <int LPE> __device__ inline double slot_sum_f64(double x) {
 
 // stage 1 of da_l[h,d] = sum_v d_el[v,h] Wh[v,h,d] and da_r likewise.  Same lane geometry as the passes:
 // an edge slot reads one node row per step; wave w of the grid takes node groups w, w + W, ...;
-// one partial per workgroup.
+// one partial per workgroup.  Workgroups of 16 wavefronts: the 256 partials of the second stage then come
+// from 4,096 wavefronts, enough loads in flight to stream the node tensor at memory speed.
 template <class G>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const Args a, double* __restrict__ partial) {
-    __shared__ double red[kWavesPerBlock][2][G::LPE * G::VEC];
+__global__ __launch_bounds__(64 * kReduceWaves) void k_gat_param_partial(const Args a, double* __restrict__ partial) {
+    __shared__ double red[kReduceWaves][2][G::LPE * G::VEC];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int waves = gridDim.x * kWavesPerBlock;
+    const int waves = gridDim.x * kReduceWaves;
     double sl[G::VEC], sr[G::VEC];
 #pragma unroll
     for (int i = 0; i < G::VEC; ++i) { sl[i] = 0.0; sr[i] = 0.0; }
     constexpr int B = 4;  // node rows requested per edge slot before the first is used
     const int stride = waves * G::EPW;
-    for (int base = (blockIdx.x * kWavesPerBlock + wave) * G::EPW; base < a.n_nodes; base += stride * B) {
+    for (int base = (blockIdx.x * kReduceWaves + wave) * G::EPW; base < a.n_nodes; base += stride * B) {
         float x[B][G::VEC], del[B], der[B];
 #pragma unroll
         for (int k = 0; k < B; ++k) {
@@ -853,7 +855,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_gat_param_partial(const
         const int which = t / a.HD, f = t % a.HD;
         double sum = 0.0;
 #pragma unroll
-        for (int w = 0; w < kWavesPerBlock; ++w) sum += red[w][which][f];
+        for (int w = 0; w < kReduceWaves; ++w) sum += red[w][which][f];
         partial[((size_t)blockIdx.x * 2 + which) * a.HD + f] = sum;
     }
 }

@@ -9,10 +9,14 @@ static void run(const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* 
     run_pass<G, GatBwdRow>(g, false, a, kRowLabels, st);
     run_pass<G, GatBwdCol>(g, true, a, kColLabels, st);
     KernelTimer t("param_reduce", st);
-    hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(kReduceBlocks), dim3(64 * kWavesPerBlock), 0, st, a, reduce_tmp);
+    // one workgroup per 4 load rounds of its wavefronts, at most kReduceBlocks (the partial buffer's size)
+    const int64_t rows_per_block = (int64_t)kReduceWaves * G::EPW * 16;
+    int blocks = (int)((a.n_nodes + rows_per_block - 1) / rows_per_block);
+    blocks = blocks < 1 ? 1 : (blocks > kReduceBlocks ? kReduceBlocks : blocks);
+    hipLaunchKernelGGL((k_gat_param_partial<G>), dim3(blocks), dim3(64 * kReduceWaves), 0, st, a, reduce_tmp);
     int wf = 8;  // columns of the second stage: a power of two >= 2 * HD (HD <= 512)
     while (wf < 2 * a.HD) wf <<= 1;
-    hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(1024), 0, st, reduce_tmp, kReduceBlocks, a.HD, wf, d_a_l, d_a_r);
+    hipLaunchKernelGGL(k_gat_param_final, dim3(1), dim3(1024), 0, st, reduce_tmp, blocks, a.HD, wf, d_a_l, d_a_r);
 }
 
 int launch_backward_gat(int geo, const dfgnn_graph* g, const Args& a, double* reduce_tmp, float* d_a_l, float* d_a_r,
