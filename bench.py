@@ -158,6 +158,62 @@ def sample_subproblem(graph, feats, target_edges: int, seed: int, n_cols: int = 
     return sub, sub_feats, rows, new_rows, cols, np.searchsorted(nodes, cols), int(src.size)
 
 
+def gather_calibration(torch, dfgnn) -> dict:
+    """Rate of random row reads on this GPU, measured with the library's yardstick kernel (the gather instruction
+    of the pass kernels and nothing else): what `roofline.achieved` of a gather-bound pass can reach at most."""
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    n_idx = 1 << 26
+    out = torch.empty(8192 * 64 * 4, dtype=torch.int32, device="cuda")  # 8,192 wavefronts = 32 per compute unit
+    cases = []
+    for row_bytes in (128, 256, 512):
+        for table_mib in (64, 1024, 3072):
+            n_rows = table_mib * (1 << 20) // row_bytes
+            table = torch.zeros(n_rows * row_bytes // 4, dtype=torch.int32, device="cuda")
+            for kind in ("uniform", "power-law"):
+                if kind == "uniform":
+                    idx = torch.randint(0, n_rows, (n_idx,), dtype=torch.int32, device="cuda", generator=gen)
+                else:  # popularity ~ rank^-0.9 as in the power-law workloads, ranks scattered over the table
+                    u = torch.rand(n_idx, device="cuda", generator=gen, dtype=torch.float64)
+                    rank = ((u * (float(n_rows) ** 0.1 - 1.0) + 1.0) ** 10.0 - 1.0).clamp_(0, n_rows - 1).to(torch.int64)
+                    idx = ((rank * 2654435761) % n_rows).to(torch.int32)
+                for _ in range(2):
+                    dfgnn.probe_gather(table, row_bytes, idx, out)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                reps = 5
+                ev[0].record()
+                for _ in range(reps):
+                    dfgnn.probe_gather(table, row_bytes, idx, out)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1]) / reps
+                cases.append({"row_bytes": row_bytes, "table_MiB": table_mib, "indices": kind, "ms": round(ms, 4),
+                              "GBps": round(n_idx * (row_bytes + 4) / ms / 1e6, 1)})
+                del idx
+            del table
+    # the index arrays of the two HBM-sized workloads themselves, against one tensor of their row size
+    from dfgnn_synth import make_workload
+    from dfgnn_synth.workloads import make_graph
+    for name in ("cfg5", "cfg4"):
+        w = make_workload(name)
+        graph = make_graph(w)
+        row_bytes = w.H * w.D * 4
+        table = torch.zeros(graph.n * row_bytes // 4, dtype=torch.int32, device="cuda")
+        idx = torch.from_numpy(graph.indices).cuda()
+        for _ in range(2):
+            dfgnn.probe_gather(table, row_bytes, idx, out)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(5):
+            dfgnn.probe_gather(table, row_bytes, idx, out)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / 5
+        cases.append({"row_bytes": row_bytes, "table_MiB": round(graph.n * row_bytes / 2**20, 1), "indices": f"{name} (CSR order)",
+                      "reads": int(graph.nnz), "ms": round(ms, 4), "GBps": round(graph.nnz * (row_bytes + 4) / ms / 1e6, 1)})
+        del table, idx
+    return {"gather_calibration": cases, "reads": n_idx, "bytes_counted": "row_bytes + 4 (the index) per read"}
+
+
 def cpu_baseline(w, graph, feats, target_edges: int):
     import oracle
     sub, sf, rows, new_rows, cols, new_cols, n_edges = sample_subproblem(graph, feats, target_edges, seed=w.seed + 7)
@@ -167,15 +223,22 @@ def cpu_baseline(w, graph, feats, target_edges: int):
     kw = {k: (None if v is None else np.asarray(v, dtype=np.float64)) for k, v in kw.items()}
     g64 = np.asarray(sf["d_out"], dtype=np.float64)
     oracle.build_oracle()
-    t0 = time.perf_counter()
-    fw = oracle.forward(L, sub.indptr, sub.indices, **kw)
-    t1 = time.perf_counter()
-    bw = oracle.backward(L, sub.indptr, sub.indices, d_out=g64, **kw)
-    t2 = time.perf_counter()
+    # the oracle is single-threaded; its thread stays on one core while it is timed
+    allowed = sorted(os.sched_getaffinity(0))
+    core = allowed[len(allowed) // 2]
+    os.sched_setaffinity(0, {core})
+    try:
+        t0 = time.perf_counter()
+        fw = oracle.forward(L, sub.indptr, sub.indices, **kw)
+        t1 = time.perf_counter()
+        bw = oracle.backward(L, sub.indptr, sub.indices, d_out=g64, **kw)
+        t2 = time.perf_counter()
+    finally:
+        os.sched_setaffinity(0, allowed)
     secs = t2 - t0
     info = {"value": n_edges / secs / 1e9, "unit": "GEdges/s", "cores": 1, "kind": "oracle",
             "sample": f"{rows.size} random rows with their whole neighbourhoods ({n_edges} edges) of the same graph, "
-                      f"fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, fp64, one thread of {os.cpu_count()} host cores"}
+                      f"fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, fp64, one thread pinned to core {core} of {os.cpu_count()} host cores"}
     return info, (rows, new_rows, cols, new_cols, fw, bw)
 
 
@@ -243,6 +306,9 @@ def main() -> int:
                          "exceed the caches; they are always taken for cfg1-cfg3")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (scale reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--gather-calibration", action="store_true",
+                    help="only time the library's random-row-read yardstick (rows of 128 / 256 / 512 bytes, uniform and "
+                         "power-law indices, tables inside and beyond the Infinity Cache) and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -266,6 +332,9 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_each_way": src.numel() * 4, "launches": 5}))
+        return 0
+    if args.gather_calibration:
+        print(json.dumps(gather_calibration(torch, dfgnn)))
         return 0
     overrides = {}
     for item in args.set:

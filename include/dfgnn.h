@@ -323,6 +323,19 @@ int dfgnn_attention_weights(const dfgnn_graph* graph, const dfgnn_layer* layer, 
 int dfgnn_timing_enable(int enable);
 int dfgnn_timing_collect(int max_labels, const char** labels, double* total_ms, int64_t* launches, int* n_labels);
 
+/*
+ * Measurement yardstick, not part of the layer (Sec. 5.2 reports bandwidth utilisation; this gives the rate
+ * the memory system sustains for the access pattern the layer is made of).  Reads row idx[e] of `table`
+ * (device, n_rows rows of row_bytes bytes, row_bytes = 16, 32, ..., 1024; below 4 GiB in all) for every
+ * e < n_idx with the gather instruction of the pass kernels, one row per group of row_bytes / 16 lanes, and
+ * does nothing else with it; an index outside [0, n_rows) reads nothing.  `idx`: device, int32[n_idx].
+ * `out`: device scratch of the caller, out_bytes >= 4096; every 4096 bytes of it make one workgroup of 4
+ * wavefronts, each thread leaves the XOR of the 16-byte pieces it read there (16 bytes per thread), so the
+ * caller chooses the size of the launch.  Asynchronous on `stream`.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ */
+int dfgnn_probe_gather(const void* table, int64_t n_rows, int32_t row_bytes, const int32_t* idx, int64_t n_idx,
+                       void* out, size_t out_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

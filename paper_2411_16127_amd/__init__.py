@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     forward_edge_bias,
     backward_edge_bias,
     attention_weights,
+    probe_gather,
     timing_enable,
     timing_collect,
     QUERY,

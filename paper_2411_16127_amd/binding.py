@@ -101,12 +101,13 @@ def lib() -> ctypes.CDLL:
         L.dfgnn_forward_edge_bias.argtypes = [vp, vp] + [vp] * 9 + [vp, sz, vp]
         L.dfgnn_attention_weights.argtypes = [vp, vp] + [vp] * 8 + [vp]
         L.dfgnn_backward_edge_bias.argtypes = [vp, vp] + [vp] * 17 + [vp, sz, vp]
+        L.dfgnn_probe_gather.argtypes = [vp, i64, ctypes.c_int32, vp, i64, vp, sz, vp]
         L.dfgnn_timing_enable.argtypes = [ctypes.c_int]
         L.dfgnn_timing_collect.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]
         for name in ("dfgnn_graph_create_batch", "dfgnn_graph_set_batch", "dfgnn_graph_batch_bytes", "dfgnn_timing_enable", "dfgnn_timing_collect", "dfgnn_version", "dfgnn_graph_meta_bytes", "dfgnn_graph_create", "dfgnn_graph_destroy",
                      "dfgnn_graph_query", "dfgnn_workspace_bytes", "dfgnn_forward", "dfgnn_backward", "dfgnn_forward_static",
-                     "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias", "dfgnn_attention_weights"):
+                     "dfgnn_forward_edge_bias", "dfgnn_backward_edge_bias", "dfgnn_attention_weights", "dfgnn_probe_gather"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -263,6 +264,14 @@ def backward_edge_bias(handle, layer: Layer, x, k, v, a_l, a_r, edge_bias, out, 
                                           _ptr(d_x), _ptr(d_k), _ptr(d_v), _ptr(d_a_l), _ptr(d_a_r), _ptr(d_scale),
                                           _ptr(d_edge_bias), _ptr(workspace), workspace_bytes_, _stream(stream)),
            "dfgnn_backward_edge_bias")
+
+
+def probe_gather(table, row_bytes: int, idx, out, stream=None) -> None:
+    """Measurement yardstick: read rows idx[e] (row_bytes each) of `table` and nothing else; `out` (a device
+    buffer of a multiple of 4096 bytes) sets the size of the launch and receives the XOR of what each thread read."""
+    n_rows = table.numel() * table.element_size() // int(row_bytes)
+    _check(lib().dfgnn_probe_gather(_ptr(table), n_rows, int(row_bytes), _ptr(idx), idx.numel(), _ptr(out),
+                                    out.numel() * out.element_size(), _stream(stream)), "dfgnn_probe_gather")
 
 
 def attention_weights(handle, layer: Layer, x, k, a_l, a_r, edge_bias, row_max, row_sum, p, stream=None) -> None:

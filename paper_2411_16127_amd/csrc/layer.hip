@@ -511,3 +511,58 @@ extern "C" int dfgnn_backward_edge_bias(const dfgnn_graph* graph, const dfgnn_la
     return backward_impl(graph, layer, x, k, v, a_l, a_r, edge_bias, out, row_max, row_sum, d_out, d_x, d_k, d_v,
                          d_a_l, d_a_r, d_scale, d_edge_bias, workspace, workspace_bytes, stream);
 }
+
+// ---------------------------------------------------------------------------------------------
+// Yardstick for the gather kernels: the rows idx[e] of a table are read with the same instruction the
+// passes gather with (16 bytes per lane, row_bytes / 16 lanes per row, four rows of an edge slot in
+// flight) and nothing else happens to them, so the rate of this kernel is what the memory system gives
+// to random row reads of that size on this machine.
+// ---------------------------------------------------------------------------------------------
+namespace dfgnn {
+constexpr int kProbeRows = 4;  // rows requested per edge slot before the first is used (as in the passes)
+static __global__ __launch_bounds__(64 * kWavesPerBlock) void k_probe_gather(const void* __restrict__ table, uint32_t table_bytes,
+                                                                             uint32_t row_bytes, int lpe_shift,
+                                                                             const int* __restrict__ idx, int64_t n,
+                                                                             u32x4* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t thread = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t wave = thread >> 6, waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int epw = 64 >> lpe_shift, slot = lane >> lpe_shift;
+    const uint32_t part = (uint32_t)(lane & ((1 << lpe_shift) - 1)) * 16u;
+    const rsrc_t r = make_rsrc(table, table_bytes);
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    // wave w takes the rounds w, w + waves, ...; a round is epw * kProbeRows consecutive entries of idx
+    for (int64_t e0 = wave * epw * kProbeRows; e0 < n; e0 += waves * epw * kProbeRows) {
+        u32x4 v[kProbeRows];
+#pragma unroll
+        for (int u = 0; u < kProbeRows; ++u) {
+            const int64_t e = e0 + (int64_t)u * epw + slot;
+            const int j = e < n ? idx[e] : -1;
+            v[u] = buf_load16(r, j >= 0 ? (uint32_t)j * row_bytes + part : 0xffffffffu);  // (out of range: zeros)
+        }
+#pragma unroll
+        for (int u = 0; u < kProbeRows; ++u) acc ^= v[u];
+    }
+    out[thread] = acc;
+}
+}  // namespace dfgnn
+
+extern "C" int dfgnn_probe_gather(const void* table, int64_t n_rows, int32_t row_bytes, const int32_t* idx, int64_t n_idx,
+                                  void* out, size_t out_bytes, void* stream) {
+    clear_error();
+    DFGNN_REQUIRE(table && idx && out && n_rows > 0 && n_idx >= 0, DFGNN_EINVAL, "NULL pointer, n_rows <= 0 or n_idx < 0");
+    int lpe_shift = 0;
+    while (lpe_shift < 6 && (16 << lpe_shift) != row_bytes) ++lpe_shift;
+    DFGNN_REQUIRE((16 << lpe_shift) == row_bytes, DFGNN_EINVAL, "row_bytes = %d is not 16, 32, ..., 1024", row_bytes);
+    DFGNN_REQUIRE((uint64_t)n_rows * (uint64_t)row_bytes < (1ull << 32), DFGNN_EUNSUPPORTED, "the table must stay below 4 GiB");
+    const size_t block_bytes = (size_t)64 * kWavesPerBlock * 16;  // a workgroup writes 16 bytes per thread
+    DFGNN_REQUIRE(out_bytes >= block_bytes && out_bytes / block_bytes <= 0x7fffffffu, DFGNN_EINVAL,
+                  "out_bytes = %zu is below one workgroup's %zu bytes (or absurdly large)", out_bytes, block_bytes);
+    DFGNN_REQUIRE(aligned16(table) && aligned16(out) && ((uintptr_t)idx & 3u) == 0, DFGNN_EUNSUPPORTED,
+                  "table and out must be 16-byte aligned, idx 4-byte");
+    hipLaunchKernelGGL(dfgnn::k_probe_gather, dim3((unsigned)(out_bytes / block_bytes)), dim3(64 * kWavesPerBlock), 0,
+                       (hipStream_t)stream, table, (uint32_t)((uint64_t)n_rows * (uint64_t)row_bytes), (uint32_t)row_bytes,
+                       lpe_shift, idx, n_idx, (dfgnn::u32x4*)out);
+    DFGNN_HIP(hipGetLastError());
+    return DFGNN_OK;
+}

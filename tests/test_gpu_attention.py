@@ -150,3 +150,31 @@ def test_argument_errors():
     with pytest.raises(dfgnn.DfgnnError):  # attention vectors belong to GAT
         dfgnn.attention_weights(g.handle, L, q, k, rsum, None, None, rmax, rsum, p)
     g.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("row_bytes", [16, 128, 512, 1024])
+def test_gather_yardstick_reads_every_requested_row(row_bytes):
+    """dfgnn_probe_gather: the XOR of what all threads read equals the XOR of the requested rows, piece by piece
+    (an index of -1 or beyond the table reads nothing); wrong sizes are refused."""
+    import torch
+    rng = np.random.default_rng(row_bytes)
+    n_rows, n_idx = 1000, 12345
+    table = rng.integers(0, 2**31 - 1, size=(n_rows, row_bytes // 4), dtype=np.int32)
+    idx = rng.integers(0, n_rows, size=n_idx, dtype=np.int32)
+    idx[::97] = -1
+    idx[5::89] = n_rows + 3
+    out = torch.empty(6 * 1024, dtype=torch.int32, device="cuda")  # 6 workgroups
+    dfgnn.probe_gather(torch.from_numpy(table).cuda(), row_bytes, torch.from_numpy(idx).cuda(), out)
+    got = out.cpu().numpy().reshape(-1, 64, 4)  # wavefront, lane, word
+    lpe = row_bytes // 16
+    valid = idx[(idx >= 0) & (idx < n_rows)]
+    want = np.bitwise_xor.reduce(table[valid], axis=0).reshape(lpe, 4)
+    per_piece = np.zeros((lpe, 4), dtype=np.int32)
+    for lane in range(64):
+        per_piece[lane % lpe] ^= np.bitwise_xor.reduce(got[:, lane, :], axis=0)
+    assert np.array_equal(per_piece, want)
+    with pytest.raises(dfgnn.DfgnnError):
+        dfgnn.probe_gather(torch.from_numpy(table).cuda(), 48, torch.from_numpy(idx).cuda(), out)
+    with pytest.raises(dfgnn.DfgnnError):
+        dfgnn.probe_gather(torch.from_numpy(table).cuda(), row_bytes, torch.from_numpy(idx).cuda(), out[:16])
