@@ -8,7 +8,8 @@ resident in HBM before the timed region.  Prints ONE JSON line:
                  neighbour row counted once per edge) over its mean duration from HIP events recorded on
                  the launch stream during the timed steps, against the 8 TB/s HBM peak.  This is an
                  effective rate: rows served by the Infinity Cache count like rows from HBM (the counters
-                 behind `traffic` sit between L2 and the memory side and cannot tell the two apart)
+                 behind `traffic` sit between L2 and the memory side and cannot tell the two apart);
+                 `bare_gather` = the same rows read by a kernel that does nothing else, timed in this run
   cpu_baseline : the CPU oracle timed on a bounded sample of rows of the same graph (one thread)
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1..cfg5]
@@ -522,6 +523,29 @@ def main() -> int:
                     # counters were collected for the workloads as defined, not for variants of them
                     "traffic": None if (args.set or args.edge_bias or args.scores_in_memory) else measured_traffic(w.name, dom),
                     "algorithmic_bytes_per_launch": model_bytes.get(dom), "avg_ms": kern[dom]["avg_ms"]}
+    # The same rows read by a kernel that does nothing else (the library's yardstick, timed here): the
+    # dominant pass walks `walk` (CSR or CSC index array) and gathers `tensors` node rows per edge.
+    tensors = {"gt": {"fwd": 2, "bwd_row": 2, "bwd_col": 2, "bwd_row_col": 4}, "gat": {"fwd": 1, "bwd_row": 1, "bwd_col": 1},
+               "agnn": {"fwd": 1, "bwd_row": 1, "bwd_col": 2}, "gatv2": {"fwd": 1, "bwd_row": 1, "bwd_col": 2}}[w.model]
+    row_bytes = x.numel() // max(graph.n, 1) * x.element_size()
+    if roofline and roofline["kernel"] in tensors and graph.n * row_bytes < (1 << 32) and row_bytes in (16, 32, 64, 128, 256, 512, 1024):
+        walk = g.query("t_indices") if roofline["kernel"] == "bwd_col" else torch.from_numpy(graph.indices).cuda()
+        scratch = torch.empty(8192 * 64 * 4, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            dfgnn.probe_gather(x, row_bytes, walk, scratch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dfgnn.probe_gather(x, row_bytes, walk, scratch)
+        e1.record()
+        torch.cuda.synchronize()
+        bare_ms = e0.elapsed_time(e1) / 5
+        n_t = tensors[roofline["kernel"]]
+        roofline["bare_gather"] = {"what": "one node tensor's rows read at every entry of the index array the kernel walks, nothing else (dfgnn_probe_gather)",
+                                   "ms": round(bare_ms, 4), "GBps": round(graph.nnz * (row_bytes + 4) / bare_ms / 1e6, 1),
+                                   "tensors_gathered_by_kernel": n_t,
+                                   "kernel_time_over_bare_reads": round(kern[roofline["kernel"]]["avg_ms"] / (n_t * bare_ms), 3)}
+        del walk, scratch
     compulsory = compulsory_bytes(w, graph, args.edge_bias)
     total_model = sum(model_bytes.get(name, 0) for name in ("fwd", "bwd_row", "bwd_col", "param_reduce"))
 
