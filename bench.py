@@ -191,6 +191,27 @@ def gather_calibration(torch, dfgnn) -> dict:
                               "GBps": round(n_idx * (row_bytes + 4) / ms / 1e6, 1)})
                 del idx
             del table
+    # rate against the wavefronts in flight (the size of `out` sets the launch): what the loads a kernel
+    # keeps outstanding are worth; 4 KB of rows per wavefront for every row size
+    sweep = []
+    for row_bytes, table_mib in ((128, 122), (256, 244), (512, 1196)):
+        n_rows = table_mib * (1 << 20) // row_bytes
+        table = torch.zeros(n_rows * row_bytes // 4, dtype=torch.int32, device="cuda")
+        idx = torch.randint(0, n_rows, (n_idx // 2,), dtype=torch.int32, device="cuda", generator=gen)
+        for waves in (1024, 2048, 3072, 4096, 6144, 8192, 16384):
+            small = torch.empty(waves * 64 * 4, dtype=torch.int32, device="cuda")
+            for _ in range(2):
+                dfgnn.probe_gather(table, row_bytes, idx, small)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record()
+            for _ in range(5):
+                dfgnn.probe_gather(table, row_bytes, idx, small)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / 5
+            sweep.append({"row_bytes": row_bytes, "table_MiB": table_mib, "waves_per_simd": waves / 1024,
+                          "GBps": round(idx.numel() * (row_bytes + 4) / ms / 1e6, 1)})
+        del table, idx
     # the index arrays of the two HBM-sized workloads themselves, against one tensor of their row size
     from dfgnn_synth import make_workload
     from dfgnn_synth.workloads import make_graph
@@ -212,7 +233,8 @@ def gather_calibration(torch, dfgnn) -> dict:
         cases.append({"row_bytes": row_bytes, "table_MiB": round(graph.n * row_bytes / 2**20, 1), "indices": f"{name} (CSR order)",
                       "reads": int(graph.nnz), "ms": round(ms, 4), "GBps": round(graph.nnz * (row_bytes + 4) / ms / 1e6, 1)})
         del table, idx
-    return {"gather_calibration": cases, "reads": n_idx, "bytes_counted": "row_bytes + 4 (the index) per read"}
+    return {"gather_calibration": cases, "waves_in_flight_sweep": sweep, "reads": n_idx,
+            "bytes_counted": "row_bytes + 4 (the index) per read"}
 
 
 def cpu_baseline(w, graph, feats, target_edges: int):
