@@ -50,3 +50,29 @@ def test_compulsory_floor_is_every_array_once():
     # statistics, CSR and CSC
     assert bench.compulsory_bytes(w, g) == (4 * T + 2 * S + csr) + (8 * T + 2 * S + 2 * csr)
     assert bench.compulsory_bytes(w, g) < sum(bench.algorithmic_bytes(w, g)[k] for k in ("fwd", "bwd_row", "bwd_col"))
+
+
+def test_measured_traffic_is_given_only_for_the_kernel_sources_it_was_measured_on(tmp_path, monkeypatch):
+    """roofline.traffic comes from a table that names the hash of the layer-kernel sources; any other hash,
+    an unknown kernel or a missing table give None (the bench line then says null)."""
+    from paper_2411_16127_amd.build import kernels_id
+    table = tmp_path / "measured_traffic.md"
+    table.write_text("| workload | kernel | bytes per launch | layer-kernel sources |\n|---|---|---|---|\n"
+                     f"| cfg5 | bwd_col | 141900000000 | `{kernels_id()}` |\n"
+                     "| cfg5 | fwd | 123900000000 | `0123456789abcdef01234567` |\n")
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(table))
+    assert bench.measured_traffic("cfg5", "bwd_col") == 141900000000
+    assert bench.measured_traffic("cfg5", "fwd") is None       # measured on other sources: stale
+    assert bench.measured_traffic("cfg5", "bwd_row") is None   # not in the table
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "absent.md"))
+    assert bench.measured_traffic("cfg5", "bwd_col") is None
+
+
+def test_more_than_one_gpu_is_refused():
+    """This build runs on one GPU: `--gpus 2` ends with a message and a non-zero status before anything is set up."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
